@@ -1,0 +1,218 @@
+"""Pins for the scalar parts of the CPU oracle (no GPU): requantization, I-Poly, I-Exp, I-Erf/I-GELU, I-Sqrt.
+
+Every expected value here comes from the paper (cited), from a closed form, from a library routine
+(math.isqrt, numpy sqrt, exp, erf) or from exact rational arithmetic -- never from the HIP path.
+"""
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import params as P
+import fpref
+
+RNG = np.random.default_rng(1234)
+
+
+# ------------------------------------------------------------------ requantization (App. C.1)
+def test_dyadic_ties_round_half_up():
+    # x * 1/2: ties go toward +infinity
+    assert [oracle.dyadic(x, 1, 1) for x in (1, -1, 3, -3, 2, -2, 0)] == [1, 0, 2, -1, 1, -1, 0]
+    # x * 3/4
+    assert [oracle.dyadic(x, 3, 2) for x in (1, 2, -1, -2, -3)] == [1, 2, -1, -1, -2]
+    # s == 0 is a plain product, negative multipliers allowed
+    assert oracle.dyadic(-7, -5, 0) == 35
+
+
+def test_dyadic_equals_exact_rational_rounding():
+    for _ in range(4000):
+        s = int(RNG.choice([0, 1, 2, 7, 30, 31, 32, 45, 62]))
+        m = int(RNG.integers(-2 ** 31 + 1, 2 ** 31))
+        x = int(RNG.integers(-2 ** 31, 2 ** 31))
+        want = math.floor(Fraction(x * m, 2 ** s) + Fraction(1, 2))
+        assert oracle.dyadic(x, m, s) == want
+    # exact ties at a large shift
+    for x, m, s in [(1, 2 ** 30, 31), (-1, 2 ** 30, 31), (3, 2 ** 30, 31), (-3, 2 ** 30, 31),
+                    (2 ** 31 - 1, 2 ** 31 - 1, 62), (-2 ** 31, 2 ** 31 - 1, 62), (-2 ** 31, -2 ** 31 + 1, 62)]:
+        assert oracle.dyadic(x, m, s) == math.floor(Fraction(x * m, 2 ** s) + Fraction(1, 2))
+
+
+def test_dyadic_matches_real_multiplier_within_bound():
+    # |DY(x) - x*M| <= 1/2 + |x| |M| 2^-31 : rounding to nearest plus the 31-bit multiplier error
+    for _ in range(3000):
+        M = float(np.exp(RNG.uniform(math.log(1e-8), math.log(50.0)))) * (1 if RNG.random() < 0.7 else -1)
+        m, s = P.dyadic_from_double(M)
+        assert 2 ** 30 <= abs(m) < 2 ** 31 and 0 <= s <= 62
+        assert abs(Fraction(m, 2 ** s) - Fraction(M)) <= abs(Fraction(M)) / 2 ** 31
+        x = int(RNG.integers(-2 ** 31, 2 ** 31))
+        got = oracle.dyadic(x, m, s)
+        assert abs(Fraction(got) - Fraction(x) * Fraction(M)) <= Fraction(1, 2) + abs(x) * abs(Fraction(M)) / 2 ** 31
+
+
+def test_dyadic_from_double_special_values():
+    assert P.dyadic_from_double(1.0) == (2 ** 30, 30)
+    assert P.dyadic_from_double(0.5) == (2 ** 30, 31)
+    assert P.dyadic_from_double(-0.75) == (-3 * 2 ** 29, 31)
+    assert P.dyadic_from_double(0.0) == (0, 0)
+    assert P.dyadic_from_double(2.0 ** -40) == (0, 0)         # below 2^-32: multiplier vanishes
+    assert P.dyadic_from_double(2.0 ** -31) == (2 ** 30, 61)
+    # a mantissa that rounds up to 2^31 is renormalised
+    assert P.dyadic_from_double(math.nextafter(1.0, 0.0)) == (2 ** 30, 30)
+    with pytest.raises(ValueError):
+        P.dyadic_from_double(2.0 ** 31)
+
+
+# ------------------------------------------------------------------ Alg. 1
+def test_ipoly_tracks_real_polynomial():
+    # q_out * S_out ~ a (x+b)^2 + c with S_out = a S^2 (Alg. 1), for the exp constants of Eq. 13
+    a, b, c = 0.3585, 1.353, 0.344
+    for S in (2.0 ** -4, 2.0 ** -6, 0.013, 2.0 ** -10):
+        q_b, q_c = math.floor(b / S), math.floor(c / (a * S * S))
+        for q in range(-math.floor(math.log(2) / S), 1):
+            x = q * S
+            real = a * (x + b) ** 2 + c
+            got = oracle.ipoly(q, q_b, q_c) * (a * S * S)
+            # flooring q_b moves b by < S, flooring q_c moves c by < a S^2
+            assert abs(got - real) <= 2 * a * (x + b) * S + a * S * S + 1e-12
+
+
+# ------------------------------------------------------------------ Alg. 3 / Eq. 12-14: i-exp
+def _real_iexp(x):
+    ln2 = math.log(2.0)
+    z = math.floor(-x / ln2)
+    p = x + z * ln2
+    return (0.3585 * (p + 1.353) ** 2 + 0.344) / 2 ** z
+
+
+def test_exp_polynomial_gap_matches_paper():
+    # Sec. 3.4 reports a largest gap of 1.9e-3; the printed 4-digit constants give 2.13e-3.
+    xs = np.linspace(-20.0, 0.0, 400001)
+    gap = max(abs(_real_iexp(float(x)) - math.exp(float(x))) for x in xs[::7])
+    assert 1.8e-3 <= gap <= 2.2e-3
+    assert abs(_real_iexp(0.0) - 1.000273) < 2e-6
+    assert abs((0.3585 * (-math.log(2.0) + 1.353) ** 2 + 0.344) - 0.500093) < 2e-6
+
+
+@pytest.mark.parametrize("S", [2.0 ** -4, 2.0 ** -5, 2.0 ** -6, 2.0 ** -7, 2.0 ** -8, 0.01, 2.0 ** -10, 2.0 ** -12])
+def test_integer_iexp_vs_exp(S):
+    sp = P.softmax_params(S)
+    S_exp = P.softmax_exp_scale(S)
+    worst = 0.0
+    qmin = -int(25.0 / S)
+    step = max(1, (-qmin) // 200000)
+    prev = None
+    for q in range(0, qmin, -step):
+        e, z = oracle.iexp(q, sp.q_ln2, sp.q_b, sp.q_c)
+        q_p = q + z * sp.q_ln2
+        assert z >= 0 and -sp.q_ln2 < q_p <= 0            # x~ = -z ln2 + p, p in (-ln2, 0]
+        assert e >= 0
+        if step == 1 and prev is not None:
+            assert e <= prev                               # non-increasing as x decreases
+        prev = e
+        worst = max(worst, abs(e * S_exp - math.exp(q * S)))
+    # polynomial gap (2.2e-3) + floor of q_b (d/db a(p+b)^2 <= 2a*b ~ 0.97, times S)
+    # + floor of q_ln2 (shifts p by z*S at most, weight 2^-z: z 2^-z <= 1/2, slope <= 1) + floors of q_c, >>z
+    assert worst <= 2.2e-3 + 0.97 * S + 0.5 * S + 2 * S_exp
+    if S <= 2.0 ** -12:
+        assert worst <= 2.6e-3                             # the paper's figure is the S -> 0 limit
+
+
+def test_iexp_halves_across_ln2():
+    sp = P.softmax_params(2.0 ** -8)
+    for r in (0, 1, 50, sp.q_ln2 - 1):
+        e0, z0 = oracle.iexp(-r, sp.q_ln2, sp.q_b, sp.q_c)
+        for z in (1, 2, 5, 20, 40, 70):
+            e, zz = oracle.iexp(-r - z * sp.q_ln2, sp.q_ln2, sp.q_b, sp.q_c)
+            assert zz == z0 + z and e == e0 >> z
+
+
+# ------------------------------------------------------------------ Alg. 2 / Eq. 8-9: i-GELU
+def _real_igelu(x):
+    a, b = -0.2888, -1.769
+    u = min(abs(x) / math.sqrt(2.0), -b)
+    L = math.copysign(1.0, x) * (a * (u + b) ** 2 + 1.0) if x != 0 else 0.0
+    return x * 0.5 * (1.0 + L)
+
+
+def test_igelu_polynomial_error_matches_table1():
+    xs = np.linspace(-4.0, 4.0, 80001)
+    err = np.array([_real_igelu(float(x)) for x in xs]) - fpref.gelu(xs)
+    assert abs(np.max(np.abs(err)) - 0.018) < 6e-4        # Table 1: L-inf 0.018
+    assert abs(math.sqrt(np.mean(err ** 2)) - 0.0082) < 1.5e-4   # Table 1: "L2" 0.0082 (an RMS)
+
+
+@pytest.mark.parametrize("S", [2.0 ** -4, 2.0 ** -5, 2.0 ** -6, 2.0 ** -7, 0.011, 2.0 ** -10])
+def test_integer_igelu_vs_gelu(S):
+    gp = P.gelu_params(S, 1.0)
+    assert oracle.lib().orc_gelu_check(gp) == 0
+    assert gp.q_b < 0 and gp.q_c < 0 and gp.q_1 == gp.q_c
+    S_t = P.gelu_t_scale(S)
+    assert S_t < 0
+    qs = np.unique(np.concatenate([np.arange(-int(10 / S), int(10 / S) + 1, max(1, int(0.002 / S))),
+                                   np.array([0, 1, -1, gp.q_max, -gp.q_max, gp.q_max + 5, -gp.q_max - 5])]))
+    worst = 0.0
+    for q in qs.tolist():
+        t = oracle.igelu_t(q, gp)
+        assert abs(t) < 2 ** 31
+        x = max(-gp.q_max, min(gp.q_max, q)) * S
+        if abs(x) <= 10.0:
+            worst = max(worst, abs(t * S_t - float(fpref.gelu(x))))
+        else:
+            # saturated: exactly linear for x > 0 with slope (q_c+q_1) S_erf / 2 in (1 - |S_erf|, 1]
+            assert abs(t * S_t - float(fpref.gelu(x))) <= abs(x) * 0.1445 * S * S + 1e-9
+    assert oracle.igelu_t(0, gp) == 0
+    # negative saturation is exactly zero: erf part equals -1 there
+    if gp.q_max > -gp.q_b + 3:
+        assert oracle.igelu_t(-(-gp.q_b) - 3, gp) == 0
+    else:
+        # fine scales leave little room in 32 bits: the input clamp q_max*S (~1.55e8 S^3) is below 2.5
+        assert S <= 2.0 ** -8
+    # Table 1 gap + floor of q_b (moves b by < S/sqrt2; |dL/db| <= 2|a||b| ~ 1.02; weight x/2 <= 1.25)
+    # + floors of q_c, q_1 (relative |S_erf| = 0.1444 S^2, times |x| <= 10)
+    assert worst <= 0.0182 + 1.0 * S + 1.5 * S * S
+
+
+def test_ierf_is_odd_and_saturates_at_one():
+    S = 2.0 ** -7
+    gp = P.gelu_params(S, 1.0)
+    S_erf = -0.2888 * (S / math.sqrt(2)) ** 2
+    for q in (1, 17, 200, -gp.q_b, -gp.q_b + 1, 10 ** 6):
+        assert oracle.ierf(-q, gp.q_b, gp.q_c) == -oracle.ierf(q, gp.q_b, gp.q_c)
+    assert oracle.ierf(0, gp.q_b, gp.q_c) == 0
+    assert abs(oracle.ierf(10 ** 6, gp.q_b, gp.q_c) * S_erf - 1.0) < 1e-4
+    for q in range(0, -gp.q_b + 10, 7):
+        x = q * S / math.sqrt(2)
+        # second-order fit of erf (Eq. 8): the fit targets x*erf(x), so the gap peaks at 1 + a b^2 = 0.096
+        # just right of the origin and stays below 0.016 from x = 0.5 on
+        assert abs(oracle.ierf(q, gp.q_b, gp.q_c) * S_erf - math.erf(x)) < (0.1 if x < 0.5 else 0.02) + 2 * S
+
+
+# ------------------------------------------------------------------ Alg. 4: I-Sqrt
+def test_isqrt_dense_range_equals_floor_sqrt():
+    n = np.arange(0, 1 << 22, dtype=np.uint64)
+    got, iters = oracle.isqrt_array(n)
+    want = np.floor(np.sqrt(n.astype(np.float64))).astype(np.uint64)
+    assert np.array_equal(got, want)
+    assert iters.max() <= 8
+
+
+def test_isqrt_squares_neighbours_and_random_uint32():
+    k = np.arange(1, 65536, dtype=np.uint64)
+    for n, want in ((k * k, k), (k * k - 1, k - 1), (k * k + 1, k)):
+        got, _ = oracle.isqrt_array(n)
+        assert np.array_equal(got, want)
+    for e in range(1, 33):
+        for n in ((1 << e) - 1, 1 << e, (1 << e) + 1):
+            if n < 2 ** 32 + 2:
+                assert oracle.isqrt(n)[0] == math.isqrt(n)
+    n = RNG.integers(0, 2 ** 32, size=300000, dtype=np.uint64)
+    got, iters = oracle.isqrt_array(n)
+    assert all(int(g) == math.isqrt(int(v)) for g, v in zip(got[:20000], n[:20000]))
+    want = np.floor(np.sqrt(n.astype(np.float64))).astype(np.uint64)
+    assert np.array_equal(got, want)
+    # Sec. 3.6 says "at most four iterations"; the algorithm as printed needs more passes for some inputs
+    # (the result is still exact), so nothing may hard-code four.
+    assert oracle.isqrt(17413928) == (math.isqrt(17413928), 6)
+    assert iters.max() <= 7
