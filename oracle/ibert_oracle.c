@@ -204,6 +204,7 @@ int orc_softmax_check(const orc_softmax_t* p, int cols)
 {
     if (!p || cols < 1) return ORC_E_ARG;
     if (p->q_ln2 < 1 || p->q_b < 1 || p->q_c < 0) return ORC_E_PARAM;
+    if (p->q_ln2 > p->q_b) return ORC_E_PARAM;   /* ln2 < b (Eq. 13): q_b + q_p stays in (0, q_b] */
     if (p->out_frac_bits < 0) return ORC_E_PARAM;
     if (p->out_dtype == ORC_I8 && p->out_frac_bits > 7) return ORC_E_PARAM;
     if (p->out_dtype == ORC_I32 && p->out_frac_bits > 30) return ORC_E_PARAM;

@@ -1,0 +1,105 @@
+// Integer-only GELU (Alg. 2, Eq. 8-9) fused with the requantization to INT8.
+// Element-wise and HBM-bound: 4 bytes in, 1 byte out per element.  Each lane streams 16-byte
+// chunks (four int32), several in flight, and writes one packed dword per chunk.
+#include "common.h"
+
+namespace ibert {
+
+struct GeluArgs {
+    const int32_t* x;
+    int8_t* y;
+    int64_t n;
+    int32_t q_b, q_c, q_1, q_max;
+    int32_t m, s;
+};
+
+// One element.  All products stay inside 32 bits by the host-checked preconditions
+// ((u+q_b)^2 + q_c and q*(erf+q_1) are bounded by q_max * (|poly| + |q_1|) < 2^31).
+__device__ __forceinline__ int32_t gelu_one(int32_t q, const GeluArgs& a)
+{
+    q = clamp_i32(q, -a.q_max, a.q_max);
+    int32_t u = q < 0 ? -q : q;
+    u = u > -a.q_b ? -a.q_b : u;                      // clip(|q|, max = -q_b)
+    const int32_t v = u + a.q_b;
+    // I-Poly, Alg. 1.  Unsigned arithmetic: the true values fit 32 bits, partial terms may wrap.
+    const uint32_t poly = (uint32_t)v * (uint32_t)v + (uint32_t)a.q_c;
+    const uint32_t erf = q < 0 ? 0u - poly : (q == 0 ? 0u : poly);          // sgn(q) * poly
+    const int32_t t = (int32_t)((uint32_t)q * (erf + (uint32_t)a.q_1));
+    return clamp_i64_to_i32(dyadic64(t, a.m, a.s), 127);
+}
+
+constexpr int GELU_THREADS = 256;
+constexpr int GELU_UNROLL = 4;                        // 16-byte chunks per lane
+
+template <bool VEC>
+__global__ __launch_bounds__(GELU_THREADS) void gelu_kernel(GeluArgs a)
+{
+    const int64_t block_base = (int64_t)blockIdx.x * (GELU_THREADS * GELU_UNROLL * 4);
+    if (VEC) {
+        int4 v[GELU_UNROLL];
+        int64_t base[GELU_UNROLL];
+#pragma unroll
+        for (int u = 0; u < GELU_UNROLL; ++u) {
+            base[u] = block_base + ((int64_t)u * GELU_THREADS + threadIdx.x) * 4;
+            if (base[u] + 3 < a.n) v[u] = *reinterpret_cast<const int4*>(a.x + base[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < GELU_UNROLL; ++u) {
+            if (base[u] + 3 < a.n) {
+                const uint32_t o = pack4_i8(gelu_one(v[u].x, a), gelu_one(v[u].y, a), gelu_one(v[u].z, a),
+                                            gelu_one(v[u].w, a));
+                *reinterpret_cast<uint32_t*>(a.y + base[u]) = o;
+            } else {
+                for (int64_t i = base[u]; i < a.n; ++i) a.y[i] = (int8_t)gelu_one(a.x[i], a);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < GELU_UNROLL * 4; ++u) {
+            const int64_t i = block_base + (int64_t)u * GELU_THREADS + threadIdx.x;
+            if (i < a.n) a.y[i] = (int8_t)gelu_one(a.x[i], a);
+        }
+    }
+}
+
+int check_gelu(const ibert_gelu_params& p)
+{
+    if (p.q_b > 0 || p.q_max < 0 || !dyadic_ok(p.out)) return IBERT_ERR_PARAM_RANGE;
+    const int64_t top = (int64_t)p.q_b * p.q_b + p.q_c;          // I-Poly at u = 0
+    const int64_t a1 = top < 0 ? -top : top;
+    const int64_t a2 = p.q_c < 0 ? -(int64_t)p.q_c : p.q_c;      // I-Poly at u = -q_b
+    const int64_t a = a1 > a2 ? a1 : a2;
+    const int64_t q1 = p.q_1 < 0 ? -(int64_t)p.q_1 : p.q_1;
+    if (a > 2147483647LL) return IBERT_ERR_PARAM_RANGE;
+    if ((__int128)p.q_max * (a + q1) > 2147483647LL) return IBERT_ERR_PARAM_RANGE;
+    return IBERT_OK;
+}
+
+int launch_gelu(const int32_t* x, int8_t* y, int64_t n, const ibert_gelu_params& p, hipStream_t stream)
+{
+    if (n == 0) return IBERT_OK;
+    GeluArgs a{x, y, n, p.q_b, p.q_c, p.q_1, p.q_max, p.out.m, p.out.s};
+    const int64_t per_block = (int64_t)GELU_THREADS * GELU_UNROLL * 4;
+    const int64_t blocks = (n + per_block - 1) / per_block;
+    if (blocks > 0x7fffffffLL) return IBERT_ERR_SHAPE;
+    const bool vec = aligned(x, 16) && aligned(y, 4);
+    if (vec)
+        hipLaunchKernelGGL(gelu_kernel<true>, dim3((unsigned)blocks), dim3(GELU_THREADS), 0, stream, a);
+    else
+        hipLaunchKernelGGL(gelu_kernel<false>, dim3((unsigned)blocks), dim3(GELU_THREADS), 0, stream, a);
+    IBERT_LAUNCH_CHECK("gelu_kernel");
+    return IBERT_OK;
+}
+
+}  // namespace ibert
+
+extern "C" int ibert_gelu_i(const int32_t* x, int8_t* y, int64_t n, const ibert_gelu_params* params, void* stream)
+{
+    if (!params) return IBERT_ERR_NULL;
+    if (n < 0) return IBERT_ERR_SHAPE;
+    const int rc = ibert::check_gelu(*params);
+    if (rc) return rc;
+    if (n == 0) return IBERT_OK;
+    if (!x || !y) return IBERT_ERR_NULL;
+    return ibert::launch_gelu(x, y, n, *params, (hipStream_t)stream);
+}

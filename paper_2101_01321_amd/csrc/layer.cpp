@@ -1,0 +1,209 @@
+// ibert_encoder_layer_i / ibert_encoder_i: the ten-step post-LN encoder layer as a sequence of
+// kernel launches on one stream (Fig. 1 right; Sec. 4.1; App. C.1).  Host code only: validation,
+// workspace carving, enqueueing.  No allocation, no synchronisation.
+#include <cstring>
+
+#include "common.h"
+
+namespace ibert {
+
+static size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+static int layout(int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn,
+                  ibert_layer_workspace_layout* o)
+{
+    if (batch < 1 || seq < 1 || hidden < 1 || heads < 1 || ffn < 1 || hidden % heads) return IBERT_ERR_SHAPE;
+    const size_t T = (size_t)batch * seq, H = hidden, F = ffn, BH = (size_t)batch * heads, L = seq;
+    size_t p = 0;
+    o->qkv = p;    p += align_up(T * 3 * H);
+    o->scores = p; p += align_up(BH * L * L * 4);
+    o->probs = p;  p += align_up(BH * L * L);
+    o->ctx = p;    p += align_up(T * H);
+    o->r1 = p;     p += align_up(T * H * 4);
+    o->h1 = p;     p += align_up(T * H);
+    o->f1 = p;     p += align_up(T * F * 4);
+    o->g = p;      p += align_up(T * F);
+    o->r2 = p;     p += align_up(T * H * 4);
+    o->total = p;
+    return IBERT_OK;
+}
+
+static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, const int8_t* x, int8_t* y,
+                     int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn, char* ws,
+                     const ibert_layer_workspace_layout& lo, hipStream_t stream)
+{
+    const int64_t B = batch, L = seq, H = hidden, nh = heads, F = ffn, T = B * L, dh = H / nh;
+    int8_t* qkv = reinterpret_cast<int8_t*>(ws + lo.qkv);
+    int32_t* scores = reinterpret_cast<int32_t*>(ws + lo.scores);
+    int8_t* probs = reinterpret_cast<int8_t*>(ws + lo.probs);
+    int8_t* ctx = reinterpret_cast<int8_t*>(ws + lo.ctx);
+    int32_t* r1 = reinterpret_cast<int32_t*>(ws + lo.r1);
+    int8_t* h1 = reinterpret_cast<int8_t*>(ws + lo.h1);
+    int32_t* f1 = reinterpret_cast<int32_t*>(ws + lo.f1);
+    int8_t* g = reinterpret_cast<int8_t*>(ws + lo.g);
+    int32_t* r2 = reinterpret_cast<int32_t*>(ws + lo.r2);
+
+    ibert_gemm_desc d;
+    int rc;
+#define RUN_GEMM(A_, W_, b_, m_, s_, R_, C_)                                             \
+    do {                                                                                 \
+        rc = check_gemm(d, A_, W_, m_, s_, R_, C_);                                      \
+        if (rc) return rc;                                                               \
+        rc = launch_gemm(d, A_, W_, b_, m_, s_, R_, C_, stream);                         \
+        if (rc) return rc;                                                               \
+    } while (0)
+
+    // 1: QKV projection, one GEMM with N = 3H
+    std::memset(&d, 0, sizeof d);
+    d.M = (int32_t)T; d.N = (int32_t)(3 * H); d.K = (int32_t)H; d.batch_outer = d.batch_inner = 1;
+    d.lda = H; d.ldw = H; d.ldc = 3 * H; d.per_channel = 1; d.out_dtype = IBERT_I8; d.out_clamp = 127;
+    RUN_GEMM(x, w.w_qkv, w.b_qkv, w.m_qkv, w.s_qkv, nullptr, qkv);
+
+    // 2: attention scores Q_h K_h^T per (batch, head); 1/sqrt(d) is inside scores_dy
+    std::memset(&d, 0, sizeof d);
+    d.M = (int32_t)L; d.N = (int32_t)L; d.K = (int32_t)dh; d.batch_outer = (int32_t)B; d.batch_inner = (int32_t)nh;
+    d.lda = 3 * H; d.ldw = 3 * H; d.ldc = L;
+    d.strideA_outer = L * 3 * H; d.strideA_inner = dh;
+    d.strideW_outer = L * 3 * H; d.strideW_inner = dh;
+    d.strideC_outer = nh * L * L; d.strideC_inner = L * L;
+    d.per_channel = 0; d.requant = q.scores_dy; d.out_dtype = IBERT_I32; d.out_clamp = 2147483647;
+    RUN_GEMM(qkv, qkv + H, nullptr, nullptr, nullptr, nullptr, scores);
+
+    // 3: softmax over the key axis
+    rc = launch_softmax(scores, probs, B * nh * L, (int32_t)L, L, L, q.softmax, stream);
+    if (rc) return rc;
+
+    // 4: context P V_h, scattered back into [T, H]
+    std::memset(&d, 0, sizeof d);
+    d.M = (int32_t)L; d.N = (int32_t)dh; d.K = (int32_t)L; d.batch_outer = (int32_t)B; d.batch_inner = (int32_t)nh;
+    d.lda = L; d.ldw = 3 * H; d.ldc = H; d.trans_w = 1;
+    d.strideA_outer = nh * L * L; d.strideA_inner = L * L;
+    d.strideW_outer = L * 3 * H; d.strideW_inner = dh;
+    d.strideC_outer = L * H; d.strideC_inner = dh;
+    d.per_channel = 0; d.requant = q.ctx_dy; d.out_dtype = IBERT_I8; d.out_clamp = 127;
+    RUN_GEMM(probs, qkv + 2 * H, nullptr, nullptr, nullptr, nullptr, ctx);
+
+    // 5: output projection + residual x, INT32 at the LayerNorm input scale
+    std::memset(&d, 0, sizeof d);
+    d.M = (int32_t)T; d.N = (int32_t)H; d.K = (int32_t)H; d.batch_outer = d.batch_inner = 1;
+    d.lda = H; d.ldw = H; d.ldc = H; d.ldr = H; d.per_channel = 1; d.out_dtype = IBERT_I32; d.out_clamp = 32767;
+    d.residual_dy = q.res1_dy;
+    RUN_GEMM(ctx, w.w_o, w.b_o, w.m_o, w.s_o, x, r1);
+
+    // 6: LayerNorm
+    rc = launch_layernorm(r1, h1, T, (int32_t)H, H, H, w.ln1_gamma_q, w.ln1_beta_q, q.ln1_shift, stream);
+    if (rc) return rc;
+
+    // 7: FFN up-projection, INT32 at the GELU input scale
+    std::memset(&d, 0, sizeof d);
+    d.M = (int32_t)T; d.N = (int32_t)F; d.K = (int32_t)H; d.batch_outer = d.batch_inner = 1;
+    d.lda = H; d.ldw = H; d.ldc = F; d.per_channel = 1; d.out_dtype = IBERT_I32; d.out_clamp = q.gelu.q_max;
+    RUN_GEMM(h1, w.w_1, w.b_1, w.m_1, w.s_1, nullptr, f1);
+
+    // 8: GELU
+    rc = launch_gelu(f1, g, T * F, q.gelu, stream);
+    if (rc) return rc;
+
+    // 9: FFN down-projection + residual h1
+    std::memset(&d, 0, sizeof d);
+    d.M = (int32_t)T; d.N = (int32_t)H; d.K = (int32_t)F; d.batch_outer = d.batch_inner = 1;
+    d.lda = F; d.ldw = F; d.ldc = H; d.ldr = H; d.per_channel = 1; d.out_dtype = IBERT_I32; d.out_clamp = 32767;
+    d.residual_dy = q.res2_dy;
+    RUN_GEMM(g, w.w_2, w.b_2, w.m_2, w.s_2, h1, r2);
+
+    // 10: LayerNorm
+    rc = launch_layernorm(r2, y, T, (int32_t)H, H, H, w.ln2_gamma_q, w.ln2_beta_q, q.ln2_shift, stream);
+    return rc;
+#undef RUN_GEMM
+}
+
+static int check_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, int32_t seq, int32_t hidden)
+{
+    const void* ptrs[] = {w.w_qkv, w.b_qkv, w.m_qkv, w.s_qkv, w.w_o, w.b_o, w.m_o, w.s_o, w.ln1_gamma_q,
+                          w.ln1_beta_q, w.w_1, w.b_1, w.m_1, w.s_1, w.w_2, w.b_2, w.m_2, w.s_2, w.ln2_gamma_q,
+                          w.ln2_beta_q};
+    for (const void* p : ptrs)
+        if (!p) return IBERT_ERR_NULL;
+    if (!dyadic_ok(q.scores_dy) || !dyadic_ok(q.ctx_dy) || !dyadic_ok(q.res1_dy) || !dyadic_ok(q.res2_dy))
+        return IBERT_ERR_PARAM_RANGE;
+    if (q.softmax.out_dtype != IBERT_I8) return IBERT_ERR_PARAM_RANGE;
+    int rc = check_softmax(q.softmax, seq);
+    if (rc) return rc;
+    rc = check_gelu(q.gelu);
+    if (rc) return rc;
+    rc = check_layernorm(hidden, q.ln1_shift);
+    if (rc) return rc;
+    return check_layernorm(hidden, q.ln2_shift);
+}
+
+}  // namespace ibert
+
+extern "C" {
+
+int ibert_encoder_layer_workspace_layout(int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn,
+                                         ibert_layer_workspace_layout* out)
+{
+    if (!out) return IBERT_ERR_NULL;
+    return ibert::layout(batch, seq, hidden, heads, ffn, out);
+}
+
+size_t ibert_encoder_layer_workspace_bytes(int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn)
+{
+    ibert_layer_workspace_layout lo;
+    if (ibert::layout(batch, seq, hidden, heads, ffn, &lo)) return 0;
+    return lo.total;
+}
+
+size_t ibert_encoder_workspace_bytes(int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn)
+{
+    ibert_layer_workspace_layout lo;
+    if (ibert::layout(batch, seq, hidden, heads, ffn, &lo)) return 0;
+    return lo.total + 2 * ibert::align_up((size_t)batch * seq * hidden);
+}
+
+int ibert_encoder_layer_i(const ibert_layer_weights* weights, const ibert_layer_quant* quant, const int8_t* x,
+                          int8_t* y, int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn,
+                          void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!weights || !quant || !x || !y || !workspace) return IBERT_ERR_NULL;
+    ibert_layer_workspace_layout lo;
+    int rc = ibert::layout(batch, seq, hidden, heads, ffn, &lo);
+    if (rc) return rc;
+    if (x == y) return IBERT_ERR_SHAPE;
+    if (workspace_bytes < lo.total || !ibert::aligned(workspace, 256)) return IBERT_ERR_WORKSPACE;
+    rc = ibert::check_layer(*weights, *quant, seq, hidden);
+    if (rc) return rc;
+    return ibert::run_layer(*weights, *quant, x, y, batch, seq, hidden, heads, ffn, (char*)workspace, lo,
+                            (hipStream_t)stream);
+}
+
+int ibert_encoder_i(const ibert_layer_weights* weights, const ibert_layer_quant* quant, int32_t n_layers,
+                    const int8_t* x, int8_t* y, int32_t batch, int32_t seq, int32_t hidden, int32_t heads,
+                    int32_t ffn, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!weights || !quant || !x || !y || !workspace) return IBERT_ERR_NULL;
+    if (n_layers < 1) return IBERT_ERR_SHAPE;
+    ibert_layer_workspace_layout lo;
+    int rc = ibert::layout(batch, seq, hidden, heads, ffn, &lo);
+    if (rc) return rc;
+    if (x == y) return IBERT_ERR_SHAPE;
+    const size_t act = ibert::align_up((size_t)batch * seq * hidden);
+    if (workspace_bytes < lo.total + 2 * act || !ibert::aligned(workspace, 256)) return IBERT_ERR_WORKSPACE;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        rc = ibert::check_layer(weights[l], quant[l], seq, hidden);
+        if (rc) return rc;
+    }
+    char* ws = (char*)workspace;
+    int8_t* pp[2] = {reinterpret_cast<int8_t*>(ws + lo.total), reinterpret_cast<int8_t*>(ws + lo.total + act)};
+    const int8_t* in = x;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        int8_t* out = (l == n_layers - 1) ? y : pp[l & 1];
+        rc = ibert::run_layer(weights[l], quant[l], in, out, batch, seq, hidden, heads, ffn, ws, lo,
+                              (hipStream_t)stream);
+        if (rc) return rc;
+        in = out;
+    }
+    return IBERT_OK;
+}
+
+}  // extern "C"
