@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark of the integer-only encoder (I-BERT) on one MI355X.
+
+A step is one forward pass of the whole hot path -- all twelve layers of the RoBERTa-Base-shaped
+integer-only encoder, ten kernels each -- over one batch of 32 synthetic sequences of 128 tokens,
+with inputs and weights already resident in HBM.  Prints ONE JSON line:
+
+  value / ms_per_step   K forwards replayed from a HIP graph captured once (no per-step host work)
+  roofline              the kernel family with the largest share of the forward: algorithmic ops (or bytes)
+                        per launch over its mean launch time, HIP events around every step of every layer
+                        in a second, instrumented pass of K forwards on the same stream
+  cpu_baseline          the CPU oracle timed on this machine's host cores on a bounded sample
+
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config base_b32] [--no-graph] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_INT8_OPS = 5.0e15      # dense INT8 MFMA, op/s
+PEAK_HBM = 8.0e12           # B/s
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="base_b32")
+    ap.add_argument("--no-graph", action="store_true", help="launch every step from the host instead of a HIP graph")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--cpu-seqs", type=int, default=8, help="sequences of the workload the CPU oracle runs")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2101_01321_amd import binding as B, synth
+
+    B.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS[args.config]
+    c = cfg
+
+    # ---- model and input, resident on the GPU
+    x_q, S_x, _ = synth.input_activations(cfg)
+    scales = synth.model_scales(cfg, S_x)
+    layers = [B.DeviceLayer(synth.layer_raw(cfg, l), scales[l], c.hidden, c.heads, c.seq, dev) for l in range(c.layers)]
+    weights = (B.LayerWeights * c.layers)(*[l.weights for l in layers])
+    quant = (B.LayerQuant * c.layers)(*[l.quant for l in layers])
+    ws = torch.zeros(B.ibert_encoder_workspace_bytes(c.batch, c.seq, c.hidden, c.heads, c.ffn), dtype=torch.uint8, device=dev)
+    x = torch.from_numpy(x_q).to(dev)
+    y = torch.empty_like(x)
+
+    stream = torch.cuda.Stream()          # default priority
+
+    def forward():
+        B.ibert_encoder_i(weights, quant, c.layers, x, y, c.batch, c.seq, c.hidden, c.heads, c.ffn, ws, stream=stream)
+
+    with torch.cuda.stream(stream):
+        forward()
+    torch.cuda.synchronize()
+    y_eager = y.clone()
+
+    graph = None
+    if not args.no_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            forward()
+        # replays must reproduce the eager result, with eager work and synchronisation in between
+        for _ in range(3):
+            y.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y, y_eager), "graph replay differs from the eager forward"
+
+    def step():
+        if graph is not None:
+            graph.replay()
+        else:
+            forward()
+
+    with torch.cuda.stream(stream):
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    seq_per_s = c.batch / (ms_per_step * 1e-3)
+
+    # ---- instrumented pass: HIP events around each of the ten steps of every layer, same stream
+    cap = 10 * c.layers * args.steps
+    with torch.cuda.stream(stream):
+        for _ in range(3):
+            forward()
+        torch.cuda.synchronize()
+        B.ibert_profile_begin(cap)
+        for _ in range(args.steps):
+            forward()
+        recs = B.ibert_profile_end(cap)
+    per_step = {}
+    for step_no, ms, ops, nbytes, kernel in recs:
+        d = per_step.setdefault(step_no, {"ms": 0.0, "n": 0, "ops": ops, "bytes": nbytes, "kernel": kernel})
+        d["ms"] += ms
+        d["n"] += 1
+    fam = {}
+    for step_no, d in per_step.items():
+        f = fam.setdefault(d["kernel"], {"ms": 0.0, "launches": 0, "ops": 0.0, "bytes": 0.0, "steps": []})
+        f["ms"] += d["ms"]
+        f["launches"] += d["n"]
+        f["ops"] += d["ops"] * d["n"]
+        f["bytes"] += d["bytes"] * d["n"]
+        f["steps"].append(step_no)
+    dom_name, dom = max(fam.items(), key=lambda kv: kv[1]["ms"])
+    avg_s = dom["ms"] * 1e-3 / dom["launches"]
+    if dom["ops"] > 0:
+        achieved = dom["ops"] / dom["launches"] / avg_s / 1e12
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_INT8_OPS / 1e12, "unit": "TOP/s",
+                    "frac": achieved * 1e12 / PEAK_INT8_OPS, "traffic": None}
+    else:
+        achieved = dom["bytes"] / dom["launches"] / avg_s / 1e9
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                    "frac": achieved * 1e9 / PEAK_HBM, "traffic": None}
+    roofline.update({"kernel": dom_name, "steps": sorted(dom["steps"]), "avg_launch_us": avg_s * 1e6,
+                     "launches": dom["launches"]})
+    step_table = {}
+    for step_no in sorted(per_step):
+        d = per_step[step_no]
+        us = d["ms"] * 1e3 / d["n"]
+        e = {"kernel": d["kernel"], "us": round(us, 2)}
+        if d["ops"] > 0:
+            e["TOP/s"] = round(d["ops"] / (us * 1e-6) / 1e12, 1)
+            e["mfma_frac"] = round(d["ops"] / (us * 1e-6) / PEAK_INT8_OPS, 4)
+        e["GB/s"] = round(d["bytes"] / (us * 1e-6) / 1e9, 1)
+        e["hbm_frac"] = round(d["bytes"] / (us * 1e-6) / PEAK_HBM, 4)
+        step_table["S%d" % step_no] = e
+
+    # ---- CPU oracle on a bounded sample of the same workload (reported baseline, not the target)
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        from oracle import params as P
+        n = min(args.cpu_seqs, c.batch)
+        sub = cfg.with_batch(n)
+        cur = x_q[:n * c.seq]
+        t0 = time.perf_counter()
+        for l in range(c.layers):
+            w, q = P.layer_params(synth.layer_raw(cfg, l), scales[l], c.hidden, c.heads)
+            if l == 0:
+                t0 = time.perf_counter()          # parameter derivation of the first layer is not inference
+            cur = oracle.encoder_layer(w, q, cur, sub.batch, sub.seq, sub.hidden, sub.heads, sub.ffn)
+        dt = time.perf_counter() - t0
+        ok = bool(np.array_equal(cur, y_eager[:n * c.seq].cpu().numpy()))
+        cpu = {"value": n / dt, "unit": "sequences/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "%d of %d sequences through all %d layers (%.1f s); GPU output equal: %s"
+                         % (n, c.batch, c.layers, dt, ok)}
+
+    out = {
+        "metric": "sequences/sec, int encoder (Base shape, seq128 b32)" if args.config == "base_b32"
+                  else "sequences/sec, int encoder (%s)" % args.config,
+        "value": seq_per_s, "unit": "sequences/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "%s: %d layers, hidden %d, heads %d, ffn %d, seq %d, batch %d" % (
+            c.name, c.layers, c.hidden, c.heads, c.ffn, c.seq, c.batch),
+            "launch": "hip-graph replay" if graph is not None else "host launches"},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "per_step": step_table,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

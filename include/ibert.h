@@ -259,6 +259,25 @@ typedef struct {
 int ibert_layer_quant_from_scales(const ibert_layer_scales* scales, int32_t seq, int32_t head_dim,
                                   ibert_layer_quant* out);
 
+/* ------------------------------------------------------------------------------------------------
+ * Optional instrumentation for benchmarks (not part of the method): while a profile is open,
+ * ibert_encoder_layer_i / ibert_encoder_i bracket each of the ten steps with HIP events on the caller's
+ * stream.  ibert_profile_begin creates the events (host objects; no device memory) for up to `capacity`
+ * steps; ibert_profile_end waits for the recorded events, fills `out` (host) with one record per executed
+ * step, destroys the events and closes the profile.  Steps beyond the capacity are not recorded.
+ * Not thread-safe; one profile at a time.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+    int32_t step;        /* 1..10, the step numbers of ibert_encoder_layer_i */
+    float ms;            /* event-to-event time of the step's launch(es) */
+    double ops;          /* algorithmic integer ops: 2*M*N*K*batch for MatMul steps, 0 otherwise */
+    double bytes;        /* algorithmic bytes: operands read once + outputs written once */
+    char kernel[48];     /* name of the kernel family the step launched */
+} ibert_profile_record;
+
+int ibert_profile_begin(int32_t capacity);
+int ibert_profile_end(ibert_profile_record* out, int32_t capacity, int32_t* count);
+
 const char* ibert_status_string(int status);
 const char* ibert_last_hip_error(void);
 int ibert_version(void);

@@ -79,6 +79,11 @@ class LayerScales(C.Structure):
                                           "S_g_in", "S_g_out", "S_r2", "S_y")] + [("softmax_k", C.c_int32)]
 
 
+class ProfileRecord(C.Structure):
+    _fields_ = [("step", C.c_int32), ("ms", C.c_float), ("ops", C.c_double), ("bytes", C.c_double),
+                ("kernel", C.c_char * 48)]
+
+
 # Every symbol include/ibert.h declares, with its ctypes signature.
 SIGNATURES = {
     "ibert_gemm_i8_requant": (C.c_int, [C.POINTER(GemmDesc)] + [_P] * 8),
@@ -98,6 +103,8 @@ SIGNATURES = {
     "ibert_gelu_params_from_scale": (C.c_int, [C.c_double, C.c_double, C.POINTER(GeluParams)]),
     "ibert_layernorm_params_from_float": (C.c_int, [_P, _P, C.c_int32, C.c_double, _P, _P, C.POINTER(C.c_int32)]),
     "ibert_layer_quant_from_scales": (C.c_int, [C.POINTER(LayerScales), C.c_int32, C.c_int32, C.POINTER(LayerQuant)]),
+    "ibert_profile_begin": (C.c_int, [C.c_int32]),
+    "ibert_profile_end": (C.c_int, [C.POINTER(ProfileRecord), C.c_int32, C.POINTER(C.c_int32)]),
     "ibert_status_string": (C.c_char_p, [C.c_int]),
     "ibert_last_hip_error": (C.c_char_p, []),
     "ibert_version": (C.c_int, []),
@@ -236,6 +243,18 @@ def ibert_encoder_i(weights, quant, n_layers: int, x, y, batch, seq, hidden, hea
     _chk(lib().ibert_encoder_i(weights, quant, n_layers, _dp(x), _dp(y), batch, seq, hidden, heads, ffn,
                                _dp(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
          "ibert_encoder_i")
+
+
+def ibert_profile_begin(capacity: int):
+    _chk(lib().ibert_profile_begin(capacity), "ibert_profile_begin")
+
+
+def ibert_profile_end(capacity: int):
+    """Returns a list of (step, ms, ops, bytes, kernel)."""
+    recs = (ProfileRecord * capacity)()
+    n = C.c_int32(0)
+    _chk(lib().ibert_profile_end(recs, capacity, C.byref(n)), "ibert_profile_end")
+    return [(r.step, r.ms, r.ops, r.bytes, r.kernel.decode()) for r in recs[:n.value]]
 
 
 # ------------------------------------------------------------------------- model marshalling

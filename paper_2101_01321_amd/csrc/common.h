@@ -57,6 +57,9 @@ __device__ __forceinline__ uint32_t pack4_i8(int32_t a, int32_t b, int32_t c, in
            ((uint32_t)(d & 0xff) << 24);
 }
 
+// Name of the kernel family chosen by the most recent launch_* call (for the optional profile).
+extern const char* g_last_kernel;
+
 // ---- internal launchers (validated arguments) -----------------------------------------------
 int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, const int32_t* bias,
                 const int32_t* mult, const int32_t* shift, const int8_t* residual, void* C,

@@ -88,6 +88,7 @@ int launch_gelu(const int32_t* x, int8_t* y, int64_t n, const ibert_gelu_params&
     else
         hipLaunchKernelGGL(gelu_kernel<false>, dim3((unsigned)blocks), dim3(GELU_THREADS), 0, stream, a);
     IBERT_LAUNCH_CHECK("gelu_kernel");
+    g_last_kernel = "gelu_kernel";
     return IBERT_OK;
 }
 

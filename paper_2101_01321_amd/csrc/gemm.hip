@@ -291,6 +291,7 @@ static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
         hipLaunchKernelGGL((gemm_nt_mfma_kernel<BM, BN, WAVES_M, WAVES_N, false>), dim3((unsigned)blocks),
                            dim3(GEMM_THREADS), 0, stream, g);
     IBERT_LAUNCH_CHECK("gemm_nt_mfma_kernel");
+    g_last_kernel = "gemm_nt_mfma_kernel";
     return IBERT_OK;
 }
 
@@ -337,6 +338,7 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
         else hipLaunchKernelGGL((gemm_generic_kernel<false, false>), dim3((unsigned)blocks), dim3(GEMM_THREADS), 0, stream, g);
     }
     IBERT_LAUNCH_CHECK("gemm_generic_kernel");
+    g_last_kernel = "gemm_generic_kernel";
     return IBERT_OK;
 }
 

@@ -17,6 +17,8 @@ int hip_failed(hipError_t e, const char* what)
     return IBERT_ERR_HIP;
 }
 
+const char* g_last_kernel = "";
+
 static const double kLn2 = 0.6931471805599453;   // ln 2 rounded to binary64
 
 }  // namespace ibert

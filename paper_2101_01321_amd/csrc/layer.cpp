@@ -9,6 +9,40 @@ namespace ibert {
 
 static size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
+// ---- optional per-step event profile ----------------------------------------------------------
+struct StepMeta {
+    int32_t step;
+    double ops, bytes;
+    const char* kernel;
+};
+static struct {
+    bool open = false;
+    int32_t capacity = 0, count = 0;
+    hipEvent_t* ev = nullptr;      // 2 * capacity events: [2i] before, [2i+1] after step record i
+    StepMeta* meta = nullptr;
+} g_prof;
+
+static void prof_before(hipStream_t s)
+{
+    if (g_prof.open && g_prof.count < g_prof.capacity) (void)hipEventRecord(g_prof.ev[2 * g_prof.count], s);
+}
+static void prof_after(hipStream_t s, int32_t step, double ops, double bytes)
+{
+    if (g_prof.open && g_prof.count < g_prof.capacity) {
+        (void)hipEventRecord(g_prof.ev[2 * g_prof.count + 1], s);
+        g_prof.meta[g_prof.count] = StepMeta{step, ops, bytes, g_last_kernel};
+        g_prof.count += 1;
+    }
+}
+
+// Algorithmic bytes of a MatMul step: each operand read once, the output written once, 12 bytes of
+// per-channel constants per output column.
+static double gemm_bytes(double M, double N, double K, double batch, double out_size, bool residual, bool w_shared)
+{
+    return batch * (M * K + (w_shared ? 0.0 : N * K) + M * N * out_size + (residual ? M * N : 0.0)) +
+           (w_shared ? N * K : 0.0) + 12.0 * N;
+}
+
 static int layout(int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn,
                   ibert_layer_workspace_layout* o)
 {
@@ -57,7 +91,9 @@ static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, c
     std::memset(&d, 0, sizeof d);
     d.M = (int32_t)T; d.N = (int32_t)(3 * H); d.K = (int32_t)H; d.batch_outer = d.batch_inner = 1;
     d.lda = H; d.ldw = H; d.ldc = 3 * H; d.per_channel = 1; d.out_dtype = IBERT_I8; d.out_clamp = 127;
+    prof_before(stream);
     RUN_GEMM(x, w.w_qkv, w.b_qkv, w.m_qkv, w.s_qkv, nullptr, qkv);
+    prof_after(stream, 1, 2.0 * T * 3 * H * H, gemm_bytes(T, 3 * H, H, 1, 1, false, true));
 
     // 2: attention scores Q_h K_h^T per (batch, head); 1/sqrt(d) is inside scores_dy
     std::memset(&d, 0, sizeof d);
@@ -67,11 +103,15 @@ static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, c
     d.strideW_outer = L * 3 * H; d.strideW_inner = dh;
     d.strideC_outer = nh * L * L; d.strideC_inner = L * L;
     d.per_channel = 0; d.requant = q.scores_dy; d.out_dtype = IBERT_I32; d.out_clamp = 2147483647;
+    prof_before(stream);
     RUN_GEMM(qkv, qkv + H, nullptr, nullptr, nullptr, nullptr, scores);
+    prof_after(stream, 2, 2.0 * B * nh * L * L * dh, gemm_bytes(L, L, dh, B * nh, 4, false, false));
 
     // 3: softmax over the key axis
+    prof_before(stream);
     rc = launch_softmax(scores, probs, B * nh * L, (int32_t)L, L, L, q.softmax, stream);
     if (rc) return rc;
+    prof_after(stream, 3, 0.0, 5.0 * B * nh * L * L);
 
     // 4: context P V_h, scattered back into [T, H]
     std::memset(&d, 0, sizeof d);
@@ -81,39 +121,54 @@ static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, c
     d.strideW_outer = L * 3 * H; d.strideW_inner = dh;
     d.strideC_outer = L * H; d.strideC_inner = dh;
     d.per_channel = 0; d.requant = q.ctx_dy; d.out_dtype = IBERT_I8; d.out_clamp = 127;
+    prof_before(stream);
     RUN_GEMM(probs, qkv + 2 * H, nullptr, nullptr, nullptr, nullptr, ctx);
+    prof_after(stream, 4, 2.0 * B * nh * L * dh * L, gemm_bytes(L, dh, L, B * nh, 1, false, false));
 
     // 5: output projection + residual x, INT32 at the LayerNorm input scale
     std::memset(&d, 0, sizeof d);
     d.M = (int32_t)T; d.N = (int32_t)H; d.K = (int32_t)H; d.batch_outer = d.batch_inner = 1;
     d.lda = H; d.ldw = H; d.ldc = H; d.ldr = H; d.per_channel = 1; d.out_dtype = IBERT_I32; d.out_clamp = 32767;
     d.residual_dy = q.res1_dy;
+    prof_before(stream);
     RUN_GEMM(ctx, w.w_o, w.b_o, w.m_o, w.s_o, x, r1);
+    prof_after(stream, 5, 2.0 * T * H * H, gemm_bytes(T, H, H, 1, 4, true, true));
 
     // 6: LayerNorm
+    prof_before(stream);
     rc = launch_layernorm(r1, h1, T, (int32_t)H, H, H, w.ln1_gamma_q, w.ln1_beta_q, q.ln1_shift, stream);
     if (rc) return rc;
+    prof_after(stream, 6, 0.0, 5.0 * T * H);
 
     // 7: FFN up-projection, INT32 at the GELU input scale
     std::memset(&d, 0, sizeof d);
     d.M = (int32_t)T; d.N = (int32_t)F; d.K = (int32_t)H; d.batch_outer = d.batch_inner = 1;
     d.lda = H; d.ldw = H; d.ldc = F; d.per_channel = 1; d.out_dtype = IBERT_I32; d.out_clamp = q.gelu.q_max;
+    prof_before(stream);
     RUN_GEMM(h1, w.w_1, w.b_1, w.m_1, w.s_1, nullptr, f1);
+    prof_after(stream, 7, 2.0 * T * F * H, gemm_bytes(T, F, H, 1, 4, false, true));
 
     // 8: GELU
+    prof_before(stream);
     rc = launch_gelu(f1, g, T * F, q.gelu, stream);
     if (rc) return rc;
+    prof_after(stream, 8, 0.0, 5.0 * T * F);
 
     // 9: FFN down-projection + residual h1
     std::memset(&d, 0, sizeof d);
     d.M = (int32_t)T; d.N = (int32_t)H; d.K = (int32_t)F; d.batch_outer = d.batch_inner = 1;
     d.lda = F; d.ldw = F; d.ldc = H; d.ldr = H; d.per_channel = 1; d.out_dtype = IBERT_I32; d.out_clamp = 32767;
     d.residual_dy = q.res2_dy;
+    prof_before(stream);
     RUN_GEMM(g, w.w_2, w.b_2, w.m_2, w.s_2, h1, r2);
+    prof_after(stream, 9, 2.0 * T * H * F, gemm_bytes(T, H, F, 1, 4, true, true));
 
     // 10: LayerNorm
+    prof_before(stream);
     rc = launch_layernorm(r2, y, T, (int32_t)H, H, H, w.ln2_gamma_q, w.ln2_beta_q, q.ln2_shift, stream);
-    return rc;
+    if (rc) return rc;
+    prof_after(stream, 10, 0.0, 5.0 * T * H);
+    return IBERT_OK;
 #undef RUN_GEMM
 }
 
@@ -139,6 +194,63 @@ static int check_layer(const ibert_layer_weights& w, const ibert_layer_quant& q,
 }  // namespace ibert
 
 extern "C" {
+
+int ibert_profile_begin(int32_t capacity)
+{
+    using ibert::g_prof;
+    if (g_prof.open) return IBERT_ERR_PARAM_RANGE;
+    if (capacity < 1 || capacity > (1 << 20)) return IBERT_ERR_SHAPE;
+    g_prof.ev = new hipEvent_t[2 * (size_t)capacity];
+    g_prof.meta = new ibert::StepMeta[(size_t)capacity];
+    for (int32_t i = 0; i < 2 * capacity; ++i) {
+        const hipError_t e = hipEventCreate(&g_prof.ev[i]);
+        if (e != hipSuccess) {
+            for (int32_t j = 0; j < i; ++j) (void)hipEventDestroy(g_prof.ev[j]);
+            delete[] g_prof.ev;
+            delete[] g_prof.meta;
+            g_prof.ev = nullptr;
+            g_prof.meta = nullptr;
+            return ibert::hip_failed(e, "hipEventCreate");
+        }
+    }
+    g_prof.capacity = capacity;
+    g_prof.count = 0;
+    g_prof.open = true;
+    return IBERT_OK;
+}
+
+int ibert_profile_end(ibert_profile_record* out, int32_t capacity, int32_t* count)
+{
+    using ibert::g_prof;
+    if (!g_prof.open) return IBERT_ERR_PARAM_RANGE;
+    int rc = IBERT_OK;
+    const int32_t n = g_prof.count < capacity ? g_prof.count : capacity;
+    if (!out || !count) rc = IBERT_ERR_NULL;
+    for (int32_t i = 0; rc == IBERT_OK && i < n; ++i) {
+        hipError_t e = hipEventSynchronize(g_prof.ev[2 * i + 1]);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]);
+        if (e != hipSuccess) {
+            rc = ibert::hip_failed(e, "profile event");
+            break;
+        }
+        out[i].step = g_prof.meta[i].step;
+        out[i].ms = ms;
+        out[i].ops = g_prof.meta[i].ops;
+        out[i].bytes = g_prof.meta[i].bytes;
+        std::strncpy(out[i].kernel, g_prof.meta[i].kernel, sizeof out[i].kernel - 1);
+        out[i].kernel[sizeof out[i].kernel - 1] = 0;
+    }
+    if (count) *count = rc == IBERT_OK ? n : 0;
+    for (int32_t i = 0; i < 2 * g_prof.capacity; ++i) (void)hipEventDestroy(g_prof.ev[i]);
+    delete[] g_prof.ev;
+    delete[] g_prof.meta;
+    g_prof.ev = nullptr;
+    g_prof.meta = nullptr;
+    g_prof.open = false;
+    g_prof.capacity = g_prof.count = 0;
+    return rc;
+}
 
 int ibert_encoder_layer_workspace_layout(int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn,
                                          ibert_layer_workspace_layout* out)

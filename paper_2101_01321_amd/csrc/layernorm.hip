@@ -178,6 +178,7 @@ int launch_layernorm(const int32_t* x, int8_t* y, int64_t rows, int32_t C, int64
         else launch_rows<16, 16>(a, al, stream);
     }
     IBERT_LAUNCH_CHECK("layernorm kernel");
+    g_last_kernel = "layernorm_rows_kernel";
     return IBERT_OK;
 }
 

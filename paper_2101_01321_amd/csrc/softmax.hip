@@ -234,6 +234,7 @@ int launch_softmax(const int32_t* x, void* y, int64_t rows, int32_t cols, int64_
         else hipLaunchKernelGGL(softmax_long_kernel<false>, dim3((unsigned)rows), dim3(SM_THREADS), 0, stream, a);
     }
     IBERT_LAUNCH_CHECK("softmax kernel");
+    g_last_kernel = cols <= 64 * 32 ? "softmax_rows_kernel" : "softmax_long_kernel";
     return IBERT_OK;
 }
 
