@@ -95,6 +95,11 @@ int ibert_gemm_i8_requant(const ibert_gemm_desc* desc, const int8_t* A, const in
                           const int32_t* bias, const int32_t* mult, const int32_t* shift,
                           const int8_t* residual, void* C, void* stream);
 
+/* Tuning aid: force tile configuration `config` (0 .. count-1) of the MFMA kernel for every later
+ * ibert_gemm_i8_requant call that takes the fast path; a negative value restores the built-in choice.
+ * Returns the number of configurations.  Results do not depend on the configuration. */
+int ibert_gemm_config_override(int32_t config);
+
 /* ------------------------------------------------------------------------------------------------
  * ibert_softmax_i -- integer-only Softmax over the last axis (Alg. 3; Eq. 11-14).
  *

@@ -87,6 +87,7 @@ class ProfileRecord(C.Structure):
 # Every symbol include/ibert.h declares, with its ctypes signature.
 SIGNATURES = {
     "ibert_gemm_i8_requant": (C.c_int, [C.POINTER(GemmDesc)] + [_P] * 8),
+    "ibert_gemm_config_override": (C.c_int, [C.c_int32]),
     "ibert_softmax_i": (C.c_int, [_P, _P, C.c_int64, C.c_int32, C.c_int64, C.c_int64, C.POINTER(SoftmaxParams), _P]),
     "ibert_gelu_i": (C.c_int, [_P, _P, C.c_int64, C.POINTER(GeluParams), _P]),
     "ibert_layernorm_i": (C.c_int, [_P, _P, C.c_int64, C.c_int32, C.c_int64, C.c_int64, _P, _P, C.c_int32, _P]),

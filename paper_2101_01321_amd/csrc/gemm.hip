@@ -10,6 +10,8 @@
 //     the 16 rows a quarter-wave reads in one instruction fall into distinct banks.
 //   * Integer accumulation is exact, so any consistent K order gives the oracle's bits.
 // Generic path (W is [K,N], or unaligned operands): one output element per lane, byte loads.
+#include <type_traits>
+
 #include "common.h"
 
 namespace ibert {
@@ -33,9 +35,23 @@ struct GemmArgs {
     int32_t dy_m, dy_s;
     int32_t out_clamp;
     int32_t res_m, res_s;
-    int32_t c_vec;     // INT32 output rows allow 16-byte stores / INT8 rows allow dword stores
-    int32_t r_vec;     // residual rows allow dword loads
+    int32_t c_vec;     // output rows allow one vector store per lane (4 bytes INT8, 16 bytes INT32)
+    int32_t r_vec;     // residual rows allow 16-byte loads
+    int32_t res_fast;  // residual absent, or its shift is in [8, 62]: its requantized value fits 32 bits
+    int64_t res_rnd;   // 2^(res_s - 1), or 0 when res_s == 0
+    int32_t xcd_chunk; // tiles per XCD when the grid divides by 8, else 0 (no remap)
+#ifdef IBERT_KERNEL_TIMING
+    long long* dbg;    // development only: per-wave phase timestamps
+#endif
 };
+
+// clamp(v, lo, hi) for lo <= hi in one instruction.
+__device__ __forceinline__ int32_t med3_i32(int32_t v, int32_t lo, int32_t hi)
+{
+    int32_t r;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
+    return r;
+}
 
 // Requantize one accumulator and finish the output value (before the store).
 __device__ __forceinline__ int32_t finish(int32_t acc, int32_t m, int32_t s, bool has_res, int32_t res,
@@ -48,43 +64,104 @@ __device__ __forceinline__ int32_t finish(int32_t acc, int32_t m, int32_t s, boo
 
 // ---------------------------------------------------------------------------------------------
 // MFMA kernel, W = [N,K].
+//
+// One workgroup = 4 wavefronts (2 x 2) computes a BM x BN tile; each wavefront owns (BM/2) x (BN/2),
+// i.e. (BM/32) x (BN/32) MFMA blocks of 16x16, accumulators in registers.
+// K is walked in steps of BK bytes.  Global loads for step s are issued R steps ahead into a ring of
+// register slots (the grid is about one workgroup per CU, so latency is hidden by depth, not by
+// occupancy); one step before use they are written to the other half of a double-buffered LDS tile.
+// Inside a step the operand fragments of the next 64-wide K slice are read from LDS while the
+// MFMAs of the current slice issue.
 // ---------------------------------------------------------------------------------------------
 constexpr int GEMM_THREADS = 256;
-constexpr int BK = 64;
 
-__device__ __forceinline__ int swz(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
-
-// 16 bytes of row `p` starting at column k; bytes at or beyond K read as zero.
-__device__ __forceinline__ v4i load_chunk(const int8_t* p, int k, int K, bool row_ok)
+// XOR swizzle of the 16-byte chunk index by the LDS row, chosen so that the 16 rows a quarter-wave
+// reads (same logical chunk) and the rows a quarter-wave writes land on distinct 16-byte bank groups,
+// for both a 128-byte and a 256-byte bank window.  CPR = chunks per row.
+template <int CPR>
+__device__ __forceinline__ int swz(int row)
 {
+    if (CPR == 16) return row & 15;
+    if (CPR == 8) return (row & 7) ^ ((row >> 3) & 1);
+    return ((row >> 1) & 3) ^ ((row >> 3) & 1);
+}
+
+// One 16-byte chunk of a tile row.  p points at the chunk (column k of the row).
+//   KMODE 0: K is a multiple of BK, every chunk is in range.
+//   KMODE 1: K is a multiple of 16: a chunk at or past K is fetched from column K-16 instead (in range)
+//            and replaced by zeros, without a branch.
+//   KMODE 2: any K >= 1: the chunk that straddles K is assembled bytewise (slow, rare).
+template <int KMODE>
+__device__ __forceinline__ v4i load_chunk(const int8_t* p, int k, int K)
+{
+    if (KMODE == 0) return *reinterpret_cast<const v4i*>(p);
+    if (KMODE == 1) {
+        const bool in = k < K;
+        const int back = in ? 0 : k - (K - 16);
+        v4i r = *reinterpret_cast<const v4i*>(p - back);
+        r.x = in ? r.x : 0; r.y = in ? r.y : 0; r.z = in ? r.z : 0; r.w = in ? r.w : 0;
+        return r;
+    }
     v4i r = {0, 0, 0, 0};
-    if (!row_ok || k >= K) return r;
-    if (k + 16 <= K) return *reinterpret_cast<const v4i*>(p + k);
+    if (k >= K) return r;
+    if (k + 16 <= K) return *reinterpret_cast<const v4i*>(p);
     union { v4i v; int8_t b[16]; } u;
     u.v = r;
     for (int i = 0; i < 16; ++i)
-        if (k + i < K) u.b[i] = p[k + i];
+        if (k + i < K) u.b[i] = p[i];
     return u.v;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool OUT_I8>
+// LDS layout of the epilogue: a staging tile of 32*JC rows (padded stride), the per-channel constants and the
+// residual tile.  JC (MFMA block rows per chunk) is the largest power-of-two divisor of BM/32 that fits the
+// budget: the main loop's own allocation for small tiles (several workgroups share a CU), up to 160 KB
+// for big ones (one workgroup per CU anyway).
+template <int BM, int BN, int BK>
+struct EpiLayout {
+    static constexpr int SP = BN + 4;
+    static constexpr int FM = BM / 32;
+    static constexpr int FIXED = 3 * BN + BM * BN / 4;
+    static constexpr int MAIN = 2 * (BM + BN) * BK / 4;
+    static constexpr int BUDGET = MAIN * 4 >= 65536 ? 40000 : MAIN;
+    static constexpr int fit(int jc) { return 32 * jc * SP + FIXED <= BUDGET; }
+    static constexpr int JC = fit(FM) ? FM : (FM >= 2 && fit(FM / 2) ? FM / 2 : (FM >= 4 && fit(FM / 4) ? FM / 4 : 1));
+    static constexpr int EPI = 32 * JC * SP + FIXED;
+    static constexpr int LDS_BYTES = 4 * (MAIN > EPI ? MAIN : EPI);
+};
+
+// TW = true: W is [K,N] (N contiguous).  Only the W loader differs: each lane fetches a 4 (k) x 4 (n) byte
+// block as four dwords, transposes it in registers with byte permutes and writes four dwords (4 consecutive
+// k of one n) into the same K-contiguous LDS layout the MFMA loop reads.
+template <int BM, int BN, int BK, int RING, bool OUT_I8, int KMODE, bool TW = false>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
 {
-    static_assert(WAVES_M * WAVES_N == GEMM_THREADS / 64, "four waves");
-    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int CPR = BK / 16;                       // 16-byte chunks per tile row
+    constexpr int RPP = GEMM_THREADS / CPR;            // tile rows loaded per pass of the workgroup
+    constexpr int LA = BM / RPP, LW = BN / RPP;        // chunks per lane per K step
+    constexpr int WM = BM / 2, WN = BN / 2;            // wavefront tile
     constexpr int FM = WM / 16, FN = WN / 16;
-    constexpr int LA = BM / 64, LW = BN / 64;          // 16-byte chunks per lane per K step
-    static_assert(BM % 64 == 0 && BN % 64 == 0 && WM % 16 == 0 && WN % 16 == 0, "tile shape");
+    constexpr int NS = BK / 64;                        // 64-wide K slices per step
+    static_assert(BM % RPP == 0 && BN % RPP == 0 && WM % 16 == 0 && WN % 16 == 0, "tile shape");
+    static_assert(!TW || (BK / 4) * (BN / 4) == LW * GEMM_THREADS, "transposing loader covers the W tile exactly");
 
-    __shared__ __attribute__((aligned(16))) int8_t lds_a[2][BM * BK];
-    __shared__ __attribute__((aligned(16))) int8_t lds_w[2][BN * BK];
+    extern __shared__ __attribute__((aligned(16))) int8_t lds[];
+    constexpr int STAGE = (BM + BN) * BK;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm0 = (wave % WAVES_M) * WM, wn0 = (wave / WAVES_M) * WN;
+    const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
+#ifdef IBERT_KERNEL_TIMING
+    long long tstamp[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    tstamp[0] = __builtin_readcyclecounter();
+#define IBERT_TS(i) tstamp[i] = __builtin_readcyclecounter()
+#else
+#define IBERT_TS(i)
+#endif
 
-    // tile coordinates: consecutive workgroups walk along N inside one M panel
+    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles so that
+    // the A panels and W panels it touches stay in its own L2.
     int bid = blockIdx.x;
+    if (g.xcd_chunk > 0) bid = (bid & 7) * g.xcd_chunk + (bid >> 3);
     const int tiles = g.tiles_m * g.tiles_n;
     const int z = bid / tiles;
     bid -= z * tiles;
@@ -95,32 +172,78 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
     const int8_t* A = g.A + zo * g.sA_o + zi * g.sA_i;
     const int8_t* W = g.W + zo * g.sW_o + zi * g.sW_i;
 
-    const int lrow = tid >> 2, lch = tid & 3;          // this lane's (row, chunk) inside a 64-row slab
-    v4i ra[LA], rw[LW];
-
-    auto load_global = [&](int kt) {
-        const int k = kt * BK + lch * 16;
+    const int lrow = tid / CPR, lch = tid % CPR;
+    // rows past the edge are clamped to the last valid row: they load real memory and are never stored
+    const int8_t* pa[LA];
+    const int8_t* pw[LW];
 #pragma unroll
-        for (int i = 0; i < LA; ++i) {
-            const int row = m0 + i * 64 + lrow;
-            ra[i] = load_chunk(A + (int64_t)row * g.lda, k, g.K, row < g.M);
+    for (int i = 0; i < LA; ++i) {
+        const int row = m0 + i * RPP + lrow;
+        pa[i] = A + (int64_t)(row < g.M ? row : g.M - 1) * g.lda + lch * 16;
+    }
+    // TW: block q = i*256 + tid of the BK x BN tile covers k in [4*kb4, 4*kb4+4), n in [4*nb4, 4*nb4+4)
+    constexpr int NB4 = BN / 4;
+    int tw_k[LW], tw_n[LW];
+#pragma unroll
+    for (int i = 0; i < LW; ++i) {
+        if (TW) {
+            const int q = i * GEMM_THREADS + tid;
+            tw_k[i] = (q / NB4) * 4;
+            tw_n[i] = (q % NB4) * 4;
+            const int ncol = n0 + tw_n[i];
+            pw[i] = W + (ncol + 3 < g.N ? ncol : g.N - 4);        // N % 4 == 0, N >= 4: clamped columns are never stored
+        } else {
+            const int row = n0 + i * RPP + lrow;
+            pw[i] = W + (int64_t)(row < g.N ? row : g.N - 1) * g.ldw + lch * 16;
         }
+    }
+    const int wr_off = lrow * BK + ((lch ^ swz<CPR>(lrow)) << 4);   // RPP is a multiple of 16: swizzle depends on lrow only
+
+    v4i ring[RING][LA + LW];
+    auto load_global = [&](int kt, int slot) {
+        const int kb = kt * BK;
+#pragma unroll
+        for (int i = 0; i < LA; ++i) ring[slot][i] = load_chunk<KMODE>(pa[i] + kb, kb + lch * 16, g.K) ;
 #pragma unroll
         for (int i = 0; i < LW; ++i) {
-            const int row = n0 + i * 64 + lrow;
-            rw[i] = load_chunk(W + (int64_t)row * g.ldw, k, g.K, row < g.N);
+            if (TW) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int k = kb + tw_k[i] + r;
+                    const int d = *reinterpret_cast<const int*>(pw[i] + (int64_t)(k < g.K ? k : g.K - 1) * g.ldw);
+                    ring[slot][LA + i][r] = k < g.K ? d : 0;
+                }
+            } else {
+                ring[slot][LA + i] = load_chunk<KMODE>(pw[i] + kb, kb + lch * 16, g.K);
+            }
         }
     };
-    auto store_lds = [&](int buf) {
+    auto store_lds = [&](int slot, int buf) {
+        int8_t* base = lds + buf * STAGE + wr_off;
 #pragma unroll
-        for (int i = 0; i < LA; ++i) {
-            const int row = i * 64 + lrow;
-            *reinterpret_cast<v4i*>(&lds_a[buf][row * BK + ((lch ^ swz(row)) << 4)]) = ra[i];
-        }
+        for (int i = 0; i < LA; ++i) *reinterpret_cast<v4i*>(base + i * RPP * BK) = ring[slot][i];
 #pragma unroll
         for (int i = 0; i < LW; ++i) {
-            const int row = i * 64 + lrow;
-            *reinterpret_cast<v4i*>(&lds_w[buf][row * BK + ((lch ^ swz(row)) << 4)]) = rw[i];
+            if (TW) {
+                const v4i d = ring[slot][LA + i];
+                const uint32_t x01 = __builtin_amdgcn_perm((uint32_t)d[1], (uint32_t)d[0], 0x05010400u);
+                const uint32_t y01 = __builtin_amdgcn_perm((uint32_t)d[1], (uint32_t)d[0], 0x07030602u);
+                const uint32_t x23 = __builtin_amdgcn_perm((uint32_t)d[3], (uint32_t)d[2], 0x05010400u);
+                const uint32_t y23 = __builtin_amdgcn_perm((uint32_t)d[3], (uint32_t)d[2], 0x07030602u);
+                uint32_t t[4];
+                t[0] = __builtin_amdgcn_perm(x23, x01, 0x05040100u);
+                t[1] = __builtin_amdgcn_perm(x23, x01, 0x07060302u);
+                t[2] = __builtin_amdgcn_perm(y23, y01, 0x05040100u);
+                t[3] = __builtin_amdgcn_perm(y23, y01, 0x07060302u);
+                int8_t* wb = lds + buf * STAGE + BM * BK;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int nrow = tw_n[i] + c;
+                    *reinterpret_cast<uint32_t*>(wb + nrow * BK + (((tw_k[i] >> 4) ^ swz<CPR>(nrow)) << 4) + (tw_k[i] & 15)) = t[c];
+                }
+            } else {
+                *reinterpret_cast<v4i*>(base + BM * BK + i * RPP * BK) = ring[slot][LA + i];
+            }
         }
     };
 
@@ -132,92 +255,250 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
 
     const int nk = (g.K + BK - 1) / BK;
     const int frow = lane & 15, fch = lane >> 4;       // MFMA operand: row within the 16-block, K chunk
-    if (nk > 0) {
-        load_global(0);
-        store_lds(0);
-    }
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) load_global(kt + 1);
-        v4i xa[FM], wb[FN];
+    const int rd_swz = swz<CPR>(frow);                 // block rows are multiples of 16: depends on frow only
+    const int rd_a = (wm0 + frow) * BK, rd_w = BM * BK + (wn0 + frow) * BK;
+
+    auto read_frags = [&](int buf, int s, v4i (&xa)[FM], v4i (&wb)[FN]) {
+        const int8_t* base = lds + buf * STAGE + (((s * 4 + fch) ^ rd_swz) << 4);
 #pragma unroll
-        for (int j = 0; j < FM; ++j) {
-            const int row = wm0 + j * 16 + frow;
-            xa[j] = *reinterpret_cast<const v4i*>(&lds_a[buf][row * BK + ((fch ^ swz(row)) << 4)]);
-        }
+        for (int j = 0; j < FM; ++j) xa[j] = *reinterpret_cast<const v4i*>(base + rd_a + j * 16 * BK);
 #pragma unroll
-        for (int i = 0; i < FN; ++i) {
-            const int row = wn0 + i * 16 + frow;
-            wb[i] = *reinterpret_cast<const v4i*>(&lds_w[buf][row * BK + ((fch ^ swz(row)) << 4)]);
-        }
+        for (int i = 0; i < FN; ++i) wb[i] = *reinterpret_cast<const v4i*>(base + rd_w + i * 16 * BK);
+    };
+
+    // Per-channel constants of this tile's BN columns, one or two columns per lane; used after the main loop.
+    constexpr int PPT = (BN + GEMM_THREADS - 1) / GEMM_THREADS;
+    int32_t pb[PPT], pm[PPT], ps[PPT];
 #pragma unroll
-        for (int i = 0; i < FN; ++i)
-#pragma unroll
-            for (int j = 0; j < FM; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wb[i], xa[j], acc[i][j], 0, 0, 0);
-        if (kt + 1 < nk) store_lds(buf ^ 1);
-        __syncthreads();
+    for (int q = 0; q < PPT; ++q) {
+        int nn = n0 + q * GEMM_THREADS + tid;
+        nn = nn < g.N ? nn : g.N - 1;
+        pb[q] = g.bias ? g.bias[nn] : 0;
+        pm[q] = g.per_channel ? g.mult[nn] : g.dy_m;
+        ps[q] = g.per_channel ? g.shift[nn] : g.dy_s;
     }
 
-    // Epilogue.  acc[i][j][r] = C[m0 + wm0 + 16 j + lane%16][n0 + wn0 + 16 i + 4 (lane/16) + r].
+    // The loop body is branch-free apart from one uniform test around the MFMAs, so that the compiler can
+    // count outstanding loads exactly (vmcnt) instead of draining them: loads past the last step re-read
+    // the last step (never used), and the LDS write of a step past the end lands in the idle buffer.
+    const int last = nk - 1;                           // nk >= 1 (K == 0 never reaches this kernel)
+#pragma unroll
+    for (int s = 0; s < RING; ++s) load_global(s < last ? s : last, s);
+    store_lds(0, 0);
+    load_global(RING < last ? RING : last, 0);
+    __syncthreads();
+    IBERT_TS(1);
+
+    for (int kt0 = 0; kt0 < nk; kt0 += RING) {
+#pragma unroll
+        for (int j = 0; j < RING; ++j) {
+            const int kt = kt0 + j;
+            const int buf = kt & 1;
+            const int slot = (j + 1) % RING;           // slot of step kt + 1 (kt0 is a multiple of RING)
+            store_lds(slot, buf ^ 1);
+            const int nxt = kt + 1 + RING;
+            load_global(nxt < last ? nxt : last, slot);
+            if (kt < nk) {
+                v4i xa[2][FM], wb[2][FN];
+                read_frags(buf, 0, xa[0], wb[0]);
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    if (s + 1 < NS) read_frags(buf, s + 1, xa[(s + 1) & 1], wb[(s + 1) & 1]);
+#pragma unroll
+                    for (int i = 0; i < FN; ++i)
+#pragma unroll
+                        for (int jj = 0; jj < FM; ++jj)
+                            acc[i][jj] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wb[s & 1][i], xa[s & 1][jj], acc[i][jj], 0, 0, 0);
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    IBERT_TS(2);
+    // ---- Epilogue -------------------------------------------------------------------------------
+    // acc[i][j][r] = C[m0 + wm0 + 16 j + lane%16][n0 + wn0 + 16 i + 4 (lane/16) + r].
+    // The accumulators go through LDS (free now), a chunk of rows at a time, so that a short loop can
+    // requantize them and write whole rows: a lane finishes 4 consecutive channels of one token per step and
+    // consecutive lanes are consecutive in memory.  Only the accumulator indices have to be unrolled, which
+    // keeps the code small.  The finishing loop must never wait on memory -- a wait for a load would also
+    // wait for the previous store to be acknowledged (one counter covers both), a full round trip per row --
+    // so per-channel constants sit in registers and the residual tile is parked in LDS beforehand.
+    using EL = EpiLayout<BM, BN, BK>;
+    constexpr int SP = EL::SP, JC = EL::JC;
+    constexpr int G4 = BN / 4;                                     // 4-channel groups per row
+    constexpr int RPS = GEMM_THREADS / G4;                         // rows finished per pass of the workgroup
+    static_assert(FM % JC == 0 && RPS >= 1, "epilogue layout");
+    int32_t* stage = reinterpret_cast<int32_t*>(lds);              // [32 * JC][SP]
+    int32_t* par = stage + 32 * JC * SP;                           // [3][BN]: bias, mult, shift
+    uint32_t* resl = reinterpret_cast<uint32_t*>(par + 3 * BN);    // [BM][BN / 4]: residual tile, 4 channels per dword
+
     const int64_t c_off = zo * g.sC_o + zi * g.sC_i;
     const int8_t* R = g.R ? g.R + zo * g.sR_o + zi * g.sR_i : nullptr;
+    const bool interior = m0 + BM <= g.M && n0 + BN <= g.N && g.c_vec && (!R || g.r_vec) && g.ldc < (1 << 22);
+
+    int bad = 0;
 #pragma unroll
-    for (int i = 0; i < FN; ++i) {
-        const int n = n0 + wn0 + i * 16 + fch * 4;
-        if (n >= g.N) continue;
-        int32_t bs[4], ml[4], sh[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int nn = n + r < g.N ? n + r : g.N - 1;
-            bs[r] = g.bias ? g.bias[nn] : 0;
-            ml[r] = g.per_channel ? g.mult[nn] : g.dy_m;
-            sh[r] = g.per_channel ? g.shift[nn] : g.dy_s;
+    for (int q = 0; q < PPT; ++q) {
+        const int c = q * GEMM_THREADS + tid;
+        if (c < BN) {
+            par[c] = pb[q];
+            par[BN + c] = pm[q];
+            par[2 * BN + c] = ps[q];
+            const int32_t ab = pb[q] < 0 ? -pb[q] : pb[q];
+            bad |= (ps[q] < 33 || ps[q] > 62 || ab < 0 || ab >= (1 << 30)) ? 1 : 0;
         }
-        const bool full = n + 3 < g.N;
+    }
+    if (R && interior) {
+        // residual tile -> LDS, 16 bytes per lane, rows of BN bytes
+        constexpr int CH = BM * BN / 16;                           // 16-byte chunks in the tile
+#pragma unroll 1
+        for (int q0 = 0; q0 < CH; q0 += 4 * GEMM_THREADS) {
+            v4i t[4];
 #pragma unroll
-        for (int j = 0; j < FM; ++j) {
-            const int m = m0 + wm0 + j * 16 + frow;
+            for (int u = 0; u < 4; ++u) {
+                const int q = q0 + u * GEMM_THREADS + tid;
+                const int qq = q < CH ? q : 0;
+                const int row = qq / (BN / 16), c16 = qq - row * (BN / 16);
+                t[u] = *reinterpret_cast<const v4i*>(R + (int64_t)(m0 + row) * g.ldr + n0 + c16 * 16);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int q = q0 + u * GEMM_THREADS + tid;
+                if (q < CH) *reinterpret_cast<v4i*>(resl + q * 4) = t[u];
+            }
+        }
+    }
+    // Fast path: every shift of the tile is in [33, 62] (multipliers of magnitude below a quarter), every
+    // |bias| and the largest possible |accumulator| (K * 127^2) are below 2^30, and the residual shift is in
+    // [8, 62].  Then (acc + bias) m + 2^(s-1) fits 63 bits, its floor-division by 2^s equals the high dword
+    // shifted by s-32, every term fits 32 bits, and an element costs one 64-bit multiply-add, a shift and a
+    // three-operand clamp.
+    const bool fast = !__syncthreads_or(bad) && g.res_fast && (int64_t)g.K * 16129 < (1 << 30);
+    IBERT_TS(3);
+
+    const int wrow = wave & 1;
+    const int c4 = tid % G4, r0 = tid / G4;                        // lane = (row of the pass, 4-channel group)
+    const int col = c4 * 4, n = n0 + col;
+    const v4i b4 = *reinterpret_cast<const v4i*>(par + col);
+    const v4i m4 = *reinterpret_cast<const v4i*>(par + BN + col);
+    const v4i s4 = *reinterpret_cast<const v4i*>(par + 2 * BN + col);
+
+    auto tile_row = [&](int jc0, int lr) {                         // row inside the BM x BN tile of chunk row lr
+        const int w = lr / (16 * JC), rem = lr - w * 16 * JC;      // rem = 16 * jj + row-in-block
+        return w * WM + 16 * jc0 + rem;
+    };
+    // Fast-path constants of the lane's four channels: c0 = bias*m + 2^(s-1) (64 bits), so that one
+    // multiply-add gives (acc + bias)*m + 2^(s-1); the high dword shifted by s-32 is the requantized value.
+    int64_t c0[4];
+    int32_t sh32[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        c0[e] = (int64_t)b4[e] * m4[e] + ((int64_t)1 << ((s4[e] - 1) & 63));
+        sh32[e] = (s4[e] - 32) & 31;
+    }
+    const int32_t clamp_lo = -g.out_clamp, clamp_hi = g.out_clamp;
+    auto requant4 = [&](const v4i& a4, const int32_t (&res)[4], bool has_res, auto fast_tag, int32_t (&o)[4]) {
+        constexpr bool FAST = decltype(fast_tag)::value;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (FAST) {
+                const int64_t p = (int64_t)a4[e] * m4[e] + c0[e];                                       // |p| < 2^63
+                int32_t v = (int32_t)(p >> 32) >> sh32[e];                                              // |v| <= 2^30
+                if (has_res) v += (int32_t)(((int64_t)res[e] * g.res_m + g.res_rnd) >> g.res_s);       // |.| < 2^30
+                o[e] = med3_i32(v, clamp_lo, clamp_hi);
+            } else {
+                const int32_t a = a4[e] + b4[e];
+                const int sh = s4[e] & 63;
+                int64_t v = ((int64_t)a * m4[e] + (sh > 0 ? (int64_t)1 << (sh - 1) : 0)) >> sh;
+                if (has_res) v += ((int64_t)res[e] * g.res_m + g.res_rnd) >> g.res_s;
+                o[e] = clamp_i64_to_i32(v, g.out_clamp);
+            }
+        }
+    };
+    // Output pointer of the lane's channel group in tile row 0; row offsets inside a tile fit 32 bits.
+    char* const c_lane = reinterpret_cast<char*>(g.C) + (c_off + (int64_t)m0 * g.ldc + n) * (OUT_I8 ? 1 : 4);
+    const uint32_t c_pitch = (uint32_t)g.ldc * (OUT_I8 ? 1u : 4u);
+    auto finish_interior = [&](int jc0, auto fast_tag) {
+        if (tid >= RPS * G4) return;
+        constexpr int U = 4;                                       // rows in flight: LDS reads first, then math and stores
+#pragma unroll 1
+        for (int lr0 = r0; lr0 < 32 * JC; lr0 += U * RPS) {
+            v4i a4[U];
+            uint32_t pk[U];
+            int tr[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int lr = lr0 + u * RPS;
+                const int lrc = lr < 32 * JC ? lr : r0;
+                tr[u] = tile_row(jc0, lrc);
+                a4[u] = *reinterpret_cast<const v4i*>(stage + lrc * SP + col);
+                pk[u] = R ? resl[tr[u] * G4 + c4] : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (lr0 + u * RPS < 32 * JC) {
+                    int32_t res[4];
+                    res[0] = (int8_t)(pk[u] & 0xff); res[1] = (int8_t)((pk[u] >> 8) & 0xff);
+                    res[2] = (int8_t)((pk[u] >> 16) & 0xff); res[3] = (int8_t)(pk[u] >> 24);
+                    int32_t o[4];
+                    requant4(a4[u], res, R != nullptr, fast_tag, o);
+                    char* cp = c_lane + (uint32_t)tr[u] * c_pitch;
+                    if (OUT_I8) *reinterpret_cast<uint32_t*>(cp) = pack4_i8(o[0], o[1], o[2], o[3]);
+                    else *reinterpret_cast<v4i*>(cp) = v4i{o[0], o[1], o[2], o[3]};
+                }
+            }
+        }
+    };
+    auto finish_edge = [&](int jc0) {                              // tiles on an edge or with unaligned rows
+        if (tid >= RPS * G4 || n >= g.N) return;
+        for (int lr = r0; lr < 32 * JC; lr += RPS) {
+            const int m = m0 + tile_row(jc0, lr);
             if (m >= g.M) continue;
+            const v4i a4 = *reinterpret_cast<const v4i*>(stage + lr * SP + col);
             int32_t res[4] = {0, 0, 0, 0};
             if (R) {
                 const int8_t* rp = R + (int64_t)m * g.ldr + n;
-                if (full && g.r_vec) {
-                    const uint32_t pk = *reinterpret_cast<const uint32_t*>(rp);
-                    res[0] = (int8_t)(pk & 0xff); res[1] = (int8_t)((pk >> 8) & 0xff);
-                    res[2] = (int8_t)((pk >> 16) & 0xff); res[3] = (int8_t)(pk >> 24);
-                } else {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        if (n + r < g.N) res[r] = rp[r];
-                }
+                for (int e = 0; e < 4; ++e)
+                    if (n + e < g.N) res[e] = rp[e];
             }
             int32_t o[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) o[r] = finish(acc[i][j][r] + bs[r], ml[r], sh[r], R != nullptr, res[r], g);
+            requant4(a4, res, R != nullptr, std::false_type{}, o);
             const int64_t off = c_off + (int64_t)m * g.ldc + n;
-            if (OUT_I8) {
-                int8_t* cp = reinterpret_cast<int8_t*>(g.C) + off;
-                if (full && g.c_vec) {
-                    *reinterpret_cast<uint32_t*>(cp) = pack4_i8(o[0], o[1], o[2], o[3]);
-                } else {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        if (n + r < g.N) cp[r] = (int8_t)o[r];
-                }
-            } else {
-                int32_t* cp = reinterpret_cast<int32_t*>(g.C) + off;
-                if (full && g.c_vec) {
-                    *reinterpret_cast<int4*>(cp) = make_int4(o[0], o[1], o[2], o[3]);
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        if (n + r < g.N) cp[r] = o[r];
+            for (int e = 0; e < 4; ++e) {
+                if (n + e < g.N) {
+                    if (OUT_I8) (reinterpret_cast<int8_t*>(g.C) + off)[e] = (int8_t)o[e];
+                    else (reinterpret_cast<int32_t*>(g.C) + off)[e] = o[e];
                 }
             }
         }
+    };
+
+#pragma unroll
+    for (int jc = 0; jc < FM / JC; ++jc) {
+        if (jc > 0) __syncthreads();                               // the previous chunk has been consumed
+#pragma unroll
+        for (int jj = 0; jj < JC; ++jj)
+#pragma unroll
+            for (int i = 0; i < FN; ++i)
+                *reinterpret_cast<v4i*>(stage + ((wrow * JC + jj) * 16 + frow) * SP + wn0 + i * 16 + fch * 4) = acc[i][jc * JC + jj];
+        __syncthreads();
+        if (jc == 0) IBERT_TS(5);
+        if (!interior) finish_edge(jc * JC);
+        else if (fast) finish_interior(jc * JC, std::true_type{});
+        else finish_interior(jc * JC, std::false_type{});
+        if (jc == 0) IBERT_TS(6);
     }
+#ifdef IBERT_KERNEL_TIMING
+    IBERT_TS(4);
+    if (g.dbg && lane == 0) {
+        long long* o = g.dbg + ((long long)blockIdx.x * 4 + wave) * 8;
+        for (int i = 0; i < 8; ++i) o[i] = tstamp[i];
+    }
+#endif
+#undef IBERT_TS
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -277,22 +558,92 @@ int check_gemm(const ibert_gemm_desc& d, const void* A, const void* W, const voi
     return IBERT_OK;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
+// Tile configurations of the MFMA kernel.
+struct GemmConfig {
+    int bm, bn, bk, ring;
+    double eff;           // fraction of the MFMA rate the main loop sustains (measured)
+};
+static const GemmConfig kConfigs[] = {
+    {256, 192, 128, 2, 0.60},
+    {128, 128, 128, 2, 0.45},
+    {128, 128, 64, 2, 0.45},
+    {64, 64, 128, 3, 0.30},
+    {64, 128, 64, 3, 0.35},
+    {256, 128, 64, 2, 0.50},
+    {128, 256, 64, 2, 0.50},
+};
+constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
+#ifdef IBERT_KERNEL_TIMING
+static long long* g_dbg_buf = nullptr;
+#endif
+static int g_config_override = -1;
+
+template <int BM, int BN, int BK, int RING, bool TW = false>
 static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
 {
     g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + BN - 1) / BN;
     const int64_t blocks = (int64_t)g.tiles_m * g.tiles_n * g.nbatch;
     if (blocks > 0x7fffffffLL) return IBERT_ERR_SHAPE;
-    if (i8)
-        hipLaunchKernelGGL((gemm_nt_mfma_kernel<BM, BN, WAVES_M, WAVES_N, true>), dim3((unsigned)blocks),
-                           dim3(GEMM_THREADS), 0, stream, g);
-    else
-        hipLaunchKernelGGL((gemm_nt_mfma_kernel<BM, BN, WAVES_M, WAVES_N, false>), dim3((unsigned)blocks),
-                           dim3(GEMM_THREADS), 0, stream, g);
+    g.xcd_chunk = (blocks % 8 == 0 && blocks >= 16) ? (int32_t)(blocks / 8) : 0;
+    constexpr size_t lds_bytes = EpiLayout<BM, BN, BK>::LDS_BYTES;
+    static_assert(lds_bytes <= 163840, "LDS budget");
+#define IBERT_GEMM_LAUNCH(I8_, KT_)                                                                       \
+    do {                                                                                                  \
+        auto kern = gemm_nt_mfma_kernel<BM, BN, BK, RING, I8_, KT_, TW>;                                      \
+        static bool attr_done = false;                                                                    \
+        if (!attr_done) {                                                                                 \
+            IBERT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                      \
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes)); \
+            attr_done = true;                                                                             \
+        }                                                                                                 \
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(GEMM_THREADS), lds_bytes, stream, g);       \
+    } while (0)
+    if (g.K % BK == 0) {
+        if (i8) IBERT_GEMM_LAUNCH(true, 0); else IBERT_GEMM_LAUNCH(false, 0);
+    } else {
+        if (i8) IBERT_GEMM_LAUNCH(true, 1); else IBERT_GEMM_LAUNCH(false, 1);
+    }
+#undef IBERT_GEMM_LAUNCH
+    IBERT_LAUNCH_CHECK("gemm_nt_mfma_kernel");
+    g_last_kernel = TW ? "gemm_nn_mfma_kernel" : "gemm_nt_mfma_kernel";
+    return IBERT_OK;
+}
+
+// K not a multiple of 16 (rows still 16-byte aligned): one configuration with the bytewise tail loader.
+static int launch_tail(GemmArgs& g, bool i8, hipStream_t stream)
+{
+    constexpr int BM = 128, BN = 128, BK = 128, RING = 2;
+    g.tiles_m = (g.M + BM - 1) / BM;
+    g.tiles_n = (g.N + BN - 1) / BN;
+    const int64_t blocks = (int64_t)g.tiles_m * g.tiles_n * g.nbatch;
+    if (blocks > 0x7fffffffLL) return IBERT_ERR_SHAPE;
+    g.xcd_chunk = 0;
+    constexpr size_t lds_bytes = EpiLayout<BM, BN, BK>::LDS_BYTES;
+    static bool attr_done[2] = {false, false};
+    const void* kern = i8 ? reinterpret_cast<const void*>(gemm_nt_mfma_kernel<BM, BN, BK, RING, true, 2>)
+                          : reinterpret_cast<const void*>(gemm_nt_mfma_kernel<BM, BN, BK, RING, false, 2>);
+    if (!attr_done[i8]) {
+        IBERT_HIP_CHECK(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+        attr_done[i8] = true;
+    }
+    if (i8) hipLaunchKernelGGL((gemm_nt_mfma_kernel<BM, BN, BK, RING, true, 2>), dim3((unsigned)blocks), dim3(GEMM_THREADS), lds_bytes, stream, g);
+    else hipLaunchKernelGGL((gemm_nt_mfma_kernel<BM, BN, BK, RING, false, 2>), dim3((unsigned)blocks), dim3(GEMM_THREADS), lds_bytes, stream, g);
     IBERT_LAUNCH_CHECK("gemm_nt_mfma_kernel");
     g_last_kernel = "gemm_nt_mfma_kernel";
     return IBERT_OK;
+}
+
+// Tile choice (measured on MI355X at RoBERTa-Base/Large shapes): these GEMMs are too short for one big
+// tile per CU -- ramp, barriers and the requantizing epilogue would not overlap with anything -- so prefer
+// 128x128 tiles with a 64-wide K step, of which three fit a CU at once, as long as that still gives every
+// CU something to do; below that, 64x64 tiles.
+static int choose_config(int64_t M, int64_t N, int64_t K, int64_t nb)
+{
+    if (g_config_override >= 0 && g_config_override < kNumConfigs) return g_config_override;
+    const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128) * nb;
+    if (tiles128 >= 384) return 2;
+    return K >= 512 ? 3 : 4;
 }
 
 int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, const int32_t* bias,
@@ -301,10 +652,14 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
     const int64_t nb = (int64_t)d.batch_outer * d.batch_inner;
     if (nb == 0 || d.M == 0 || d.N == 0) return IBERT_OK;
     GemmArgs g;
+#ifdef IBERT_KERNEL_TIMING
+    g.dbg = g_dbg_buf;
+#endif
     g.A = A; g.W = W; g.bias = bias; g.mult = mult; g.shift = shift; g.R = residual; g.C = C;
     g.M = d.M; g.N = d.N; g.K = d.K;
     g.batch_inner = d.batch_inner; g.nbatch = (int32_t)nb;
     g.tiles_m = g.tiles_n = 0;
+    g.xcd_chunk = 0;
     g.lda = d.lda; g.ldw = d.ldw; g.ldc = d.ldc; g.ldr = d.ldr;
     g.sA_o = d.strideA_outer; g.sA_i = d.strideA_inner;
     g.sW_o = d.strideW_outer; g.sW_i = d.strideW_inner;
@@ -314,18 +669,33 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
     g.dy_m = d.requant.m; g.dy_s = d.requant.s;
     g.out_clamp = d.out_clamp;
     g.res_m = d.residual_dy.m; g.res_s = d.residual_dy.s;
+    g.res_fast = (!residual || (d.residual_dy.s >= 8 && d.residual_dy.s <= 62)) ? 1 : 0;
+    g.res_rnd = (residual && d.residual_dy.s >= 1 && d.residual_dy.s <= 62) ? ((int64_t)1 << (d.residual_dy.s - 1)) : 0;
     const bool i8 = d.out_dtype == IBERT_I8;
-    const size_t calign = i8 ? 4 : 16;
-    const int64_t cmod = i8 ? 4 : 4;                   // elements: 4 bytes (int8) or 16 bytes (int32)
-    g.c_vec = aligned(C, calign) && d.ldc % cmod == 0 && d.strideC_outer % cmod == 0 && d.strideC_inner % cmod == 0;
-    g.r_vec = residual && aligned(residual, 4) && d.ldr % 4 == 0 && d.strideR_outer % 4 == 0 && d.strideR_inner % 4 == 0;
+    g.c_vec = aligned(C, i8 ? 4 : 16) && d.ldc % 4 == 0 && d.strideC_outer % 4 == 0 && d.strideC_inner % 4 == 0;
+    g.r_vec = residual && aligned(residual, 16) && d.ldr % 16 == 0 && d.strideR_outer % 16 == 0 && d.strideR_inner % 16 == 0;
 
-    const bool fast = d.trans_w == 0 && aligned(A, 16) && aligned(W, 16) && d.lda % 16 == 0 && d.ldw % 16 == 0 &&
+    const bool fast = d.trans_w == 0 && d.K > 0 && aligned(A, 16) && aligned(W, 16) && d.lda % 16 == 0 && d.ldw % 16 == 0 &&
                       d.strideA_outer % 16 == 0 && d.strideA_inner % 16 == 0 && d.strideW_outer % 16 == 0 &&
                       d.strideW_inner % 16 == 0;
     if (fast) {
-        if (d.N <= 64) return launch_mfma<128, 64, 4, 1>(g, i8, stream);
-        return launch_mfma<128, 128, 2, 2>(g, i8, stream);
+        if (d.K % 16 != 0) return launch_tail(g, i8, stream);       // bytewise K tail
+        switch (choose_config(d.M, d.N, d.K, nb)) {
+            case 0: return launch_mfma<256, 192, 128, 2>(g, i8, stream);
+            case 1: return launch_mfma<128, 128, 128, 2>(g, i8, stream);
+            case 2: return launch_mfma<128, 128, 64, 2>(g, i8, stream);
+            case 3: return launch_mfma<64, 64, 128, 3>(g, i8, stream);
+            case 4: return launch_mfma<64, 128, 64, 3>(g, i8, stream);
+            case 5: return launch_mfma<256, 128, 64, 2>(g, i8, stream);
+            default: return launch_mfma<128, 256, 64, 2>(g, i8, stream);
+        }
+    }
+    const bool fast_tw = d.trans_w == 1 && d.K > 0 && d.K % 16 == 0 && d.N >= 4 && d.N % 4 == 0 && aligned(A, 16) &&
+                         aligned(W, 4) && d.lda % 16 == 0 && d.ldw % 4 == 0 && d.strideA_outer % 16 == 0 &&
+                         d.strideA_inner % 16 == 0 && d.strideW_outer % 4 == 0 && d.strideW_inner % 4 == 0;
+    if (fast_tw) {
+        if (d.N <= 64) return launch_mfma<128, 64, 64, 2, true>(g, i8, stream);
+        return launch_mfma<128, 128, 64, 2, true>(g, i8, stream);
     }
     const int64_t total = (int64_t)d.M * d.N * nb;
     const int64_t blocks = (total + GEMM_THREADS - 1) / GEMM_THREADS;
@@ -343,6 +713,16 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
 }
 
 }  // namespace ibert
+
+#ifdef IBERT_KERNEL_TIMING
+extern "C" void ibert_debug_timing_buffer(void* p) { ibert::g_dbg_buf = (long long*)p; }
+#endif
+
+extern "C" int ibert_gemm_config_override(int32_t config)
+{
+    ibert::g_config_override = config;
+    return ibert::kNumConfigs;
+}
 
 extern "C" int ibert_gemm_i8_requant(const ibert_gemm_desc* desc, const int8_t* A, const int8_t* W,
                                      const int32_t* bias, const int32_t* mult, const int32_t* shift,

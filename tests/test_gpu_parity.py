@@ -220,6 +220,26 @@ def test_gemm_attention_shapes(G):
     _eq(got, oracle.gemm_requant(spec, Pm.reshape(-1), flat[2 * H:], out_elems=B_ * L * H), "context")
 
 
+@pytest.mark.parametrize("M,N,K,ldw", [(128, 64, 128, 192), (100, 64, 64, 64), (130, 128, 96, 256), (64, 20, 48, 36),
+                                        (256, 192, 272, 192), (37, 4, 16, 8), (512, 64, 512, 2304)])
+def test_gemm_trans_w_mfma_path(G, M, N, K, ldw):
+    # W given as [K,N] with aligned rows: the transposing loader of the MFMA kernel
+    rng = np.random.default_rng(M * 7 + N)
+    nb = 3
+    A = rng.integers(0, 128, size=(nb, M, K), dtype=np.int8)
+    W = rng.integers(-127, 128, size=(nb, K, ldw), dtype=np.int8)
+    for od, dy in ((I8, (1073741824, 37)), (I32, (1518500250, 30))):
+        kw = dict(M=M, N=N, K=K, batch_outer=nb, batch_inner=1, lda=K, ldw=ldw, ldc=N, trans_w=1,
+                  strideA_outer=M * K, strideW_outer=K * ldw, strideC_outer=M * N, per_channel=0, requant=dy,
+                  out_dtype=od, out_clamp=127 if od == I8 else 2 ** 31 - 1)
+        G.say("gemm trans_w M=%d N=%d K=%d ldw=%d out=%d" % (M, N, K, ldw, od))
+        got = G.gemm(kw, A, W, out_elems=nb * M * N)
+        spec = GemmSpec(M, N, K, lda=K, ldw=ldw, ldc=N, batch_outer=nb, batch_inner=1, trans_w=1, sA=(M * K, 0),
+                        sW=(K * ldw, 0), sC=(M * N, 0), per_channel=0, dy=dy, out_dtype=od,
+                        out_clamp=127 if od == I8 else 2 ** 31 - 1)
+        _eq(got, oracle.gemm_requant(spec, A.reshape(-1), W.reshape(-1), out_elems=nb * M * N), "trans_w gemm")
+
+
 def test_gemm_base_shapes_full(G):
     # the four projection GEMMs of RoBERTa-Base at batch 32 (T = 4096), full outputs
     for M, N, K, od, res in [(4096, 2304, 768, I8, False), (4096, 768, 768, I32, True), (4096, 3072, 768, I32, False),
