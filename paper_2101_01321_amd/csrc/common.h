@@ -57,6 +57,62 @@ __device__ __forceinline__ uint32_t pack4_i8(int32_t a, int32_t b, int32_t c, in
            ((uint32_t)(d & 0xff) << 24);
 }
 
+// clamp(v, lo, hi) for lo <= hi in one instruction.
+__device__ __forceinline__ int32_t med3_i32(int32_t v, int32_t lo, int32_t hi)
+{
+    int32_t r;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
+    return r;
+}
+
+// Full-rate 24-bit multiplies (low 32 bits of the product of the operands' low 24 bits), with explicit types.
+__device__ __forceinline__ uint32_t umul24(uint32_t a, uint32_t b) { return (uint32_t)__umul24(a, b); }
+__device__ __forceinline__ int32_t smul24(int32_t a, int32_t b) { return (int32_t)__mul24(a, b); }
+
+// a*b + c with 24-bit operands in one full-rate instruction (the compiler otherwise tends to pick a 64-bit
+// multiply-add for this pattern).
+__device__ __forceinline__ uint32_t umad24(uint32_t a, uint32_t b, uint32_t c)
+{
+    uint32_t r;
+    asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ __forceinline__ int32_t smad24(int32_t a, int32_t b, int32_t c)
+{
+    int32_t r;
+    asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// Four values already inside [-128,127] -> one dword, three byte permutes.
+__device__ __forceinline__ uint32_t pack4_perm(int32_t a, int32_t b, int32_t c, int32_t d)
+{
+    const uint32_t lo = __builtin_amdgcn_perm((uint32_t)b, (uint32_t)a, 0x0c0c0400u);   // a.b0, b.b0, 0, 0
+    const uint32_t hi = __builtin_amdgcn_perm((uint32_t)d, (uint32_t)c, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+}
+
+// Cross-lane moves inside a row of 16 lanes (DPP): butterfly partners for all-reduce.
+//   0xB1 quad_perm(1,0,3,2)  0x4E quad_perm(2,3,0,1)  0x141 row_half_mirror  0x140 row_mirror
+template <int CTRL>
+__device__ __forceinline__ int32_t dpp_mov(int32_t v)
+{
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
+}
+
+// All-reduce over groups of LPR consecutive lanes (LPR = 16, 32 or 64; groups are aligned).
+template <int LPR, typename Op>
+__device__ __forceinline__ int32_t group_allreduce(int32_t v, Op op)
+{
+    v = op(v, dpp_mov<0xB1>(v));
+    v = op(v, dpp_mov<0x4E>(v));
+    v = op(v, dpp_mov<0x141>(v));
+    v = op(v, dpp_mov<0x140>(v));
+    if (LPR > 16) v = op(v, __shfl_xor(v, 16, 64));
+    if (LPR > 32) v = op(v, __shfl_xor(v, 32, 64));
+    return v;
+}
+
 // Name of the kernel family chosen by the most recent launch_* call (for the optional profile).
 extern const char* g_last_kernel;
 

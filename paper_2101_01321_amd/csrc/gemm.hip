@@ -45,14 +45,6 @@ struct GemmArgs {
 #endif
 };
 
-// clamp(v, lo, hi) for lo <= hi in one instruction.
-__device__ __forceinline__ int32_t med3_i32(int32_t v, int32_t lo, int32_t hi)
-{
-    int32_t r;
-    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
-    return r;
-}
-
 // Requantize one accumulator and finish the output value (before the store).
 __device__ __forceinline__ int32_t finish(int32_t acc, int32_t m, int32_t s, bool has_res, int32_t res,
                                           const GemmArgs& g)

@@ -18,7 +18,18 @@ struct LayerNormArgs {
     const int32_t* gamma_q;
     const int32_t* beta_q;
     int32_t shift;
+    uint32_t magic_c;    // floor(2^32 / C) + 1 (0 for C == 1): reciprocal multiply for the divisions by C
 };
+
+// floor(u / C) for u < 2^31: est = mulhi(u, magic) is the quotient or one more (the excess is below
+// u / 2^32 < 1); one fix-up step from the sign of the remainder.
+__device__ __forceinline__ uint32_t udiv_c(uint32_t u, uint32_t C, uint32_t magic)
+{
+    if (magic == 0) return u;
+    const uint32_t q = __umulhi(u, magic);
+    const int32_t r = (int32_t)(u - q * C);
+    return r < 0 ? q - 1 : q;
+}
 
 // Alg. 4: Newton iteration for floor(sqrt(n)) from x0 = 2^ceil(Bits(n)/2); stops when the iterate
 // no longer decreases.  The loop runs to the stop rule (some inputs need more than four passes).
@@ -37,25 +48,25 @@ __device__ __forceinline__ uint32_t isqrt_newton(uint32_t n)
 template <int LPR>
 __device__ __forceinline__ int32_t group_sum_i32(int32_t v)
 {
-#pragma unroll
-    for (int off = 1; off < LPR; off <<= 1) v += __shfl_xor(v, off, 64);
-    return v;
+    return group_allreduce<LPR>(v, [](int32_t a, int32_t b) { return a + b; });
 }
 
+// 64-bit all-reduce built from 32-bit ones.
 template <int LPR>
 __device__ __forceinline__ uint64_t group_sum_u64(uint64_t v)
 {
-#pragma unroll
-    for (int off = 1; off < LPR; off <<= 1) {
-        const uint32_t lo = (uint32_t)__shfl_xor((int32_t)(uint32_t)v, off, 64);
-        const uint32_t hi = (uint32_t)__shfl_xor((int32_t)(uint32_t)(v >> 32), off, 64);
-        v += ((uint64_t)hi << 32) | lo;
-    }
-    return v;
+    // every lane value is below 2^38 here (<= 64 squares below 2^32); split into 19-bit limbs so that a sum of
+    // 64 limbs stays below 2^25 and plain 32-bit all-reduces are exact
+    const int32_t l0 = (int32_t)(v & 0x7ffff), l1 = (int32_t)((v >> 19) & 0x7ffff), l2 = (int32_t)(v >> 38);
+    const uint64_t s0 = (uint32_t)group_sum_i32<LPR>(l0), s1 = (uint32_t)group_sum_i32<LPR>(l1),
+                   s2 = (uint32_t)group_sum_i32<LPR>(l2);
+    return s0 + (s1 << 19) + (s2 << 38);
 }
 
 constexpr int LN_THREADS = 256;
 
+// ALIGNED: rows 16-byte (x) / 4-byte (y) aligned, C % 4 == 0, gamma/beta 16-byte aligned: every 4-element
+// chunk is either entirely inside the row or entirely outside, and moves as one vector.
 template <int LPR, int NCH, bool ALIGNED>
 __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArgs a)
 {
@@ -65,61 +76,98 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
     const bool live = row < a.rows;
     const int32_t* xr = a.x + (live ? row : 0) * a.ldx;
     const int32_t C = a.C;
+    const int32_t rnd = 1 << (a.shift - 1);
 
-    int32_t v[NCH][4];
-    int32_t sum = 0;
+    // gamma and beta are shared by every row of the workgroup: one coalesced copy into LDS
+    __shared__ __attribute__((aligned(16))) int32_t s_gamma[1024];
+    __shared__ __attribute__((aligned(16))) int32_t s_beta[1024];
+    if (ALIGNED) {
+        for (int i = threadIdx.x * 4; i < C; i += LN_THREADS * 4) {
+            *reinterpret_cast<int4*>(s_gamma + i) = *reinterpret_cast<const int4*>(a.gamma_q + i);
+            *reinterpret_cast<int4*>(s_beta + i) = *reinterpret_cast<const int4*>(a.beta_q + i);
+        }
+    }
+
+    int32_t v[NCH][4], gm[NCH][4], bt[NCH][4];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         const int col = (c * LPR + lane) * 4;
-        if (ALIGNED && live && col + 3 < C) {
-            const int4 t = *reinterpret_cast<const int4*>(xr + col);
+        if (ALIGNED) {
+            const int cc = col < C ? col : 0;          // out-of-row chunks re-read chunk 0 and are masked below
+            const int4 t = *reinterpret_cast<const int4*>(xr + cc);
             v[c][0] = t.x; v[c][1] = t.y; v[c][2] = t.z; v[c][3] = t.w;
         } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[c][e] = (live && col + e < C) ? xr[col + e] : 0;
         }
+    }
+    if (ALIGNED) __syncthreads();
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int col = (c * LPR + lane) * 4;
+        if (ALIGNED) {
+            const int cc = col < C ? col : 0;
+            const int4 g4 = *reinterpret_cast<const int4*>(s_gamma + cc);
+            const int4 b4 = *reinterpret_cast<const int4*>(s_beta + cc);
+            gm[c][0] = g4.x; gm[c][1] = g4.y; gm[c][2] = g4.z; gm[c][3] = g4.w;
+            bt[c][0] = b4.x + rnd; bt[c][1] = b4.y + rnd; bt[c][2] = b4.z + rnd; bt[c][3] = b4.w + rnd;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int ce = col + e < C ? col + e : C - 1;
+                gm[c][e] = a.gamma_q[ce];
+                bt[c][e] = a.beta_q[ce] + rnd;
+            }
+        }
+    }
+
+    // clamp on load, sum
+    int32_t sum = 0;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int col = (c * LPR + lane) * 4;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            v[c][e] = clamp_i32(v[c][e], -32767, 32767);
+            const bool in = ALIGNED ? col < C : col + e < C;
+            v[c][e] = in ? med3_i32(v[c][e], -32767, 32767) : 0;
             sum += v[c][e];                            // |sum| <= 1024 * 32767 < 2^25
         }
     }
     sum = group_sum_i32<LPR>(sum);
 
-    // mu = floor((sum + floor(C/2)) / C)
-    const int32_t num = sum + (C >> 1);
-    int32_t mu = num / C;
-    if (num - mu * C < 0) mu -= 1;
+    // mu = floor((sum + floor(C/2)) / C), computed on the non-negative number sum + C/2 + 32768 C
+    const uint32_t Cu = (uint32_t)C;
+    const int32_t mu = (int32_t)udiv_c((uint32_t)(sum + (C >> 1) + (C << 15)), Cu, a.magic_c) - 32768;
 
-    // ss = sum d^2 (each d^2 < 2^32, the total < 2^42)
+    // ss = sum d^2: |d| < 2^17, so d*d is a 24-bit multiply; each square is below 2^32, the total below 2^42
     uint64_t ss = 0;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         const int col = (c * LPR + lane) * 4;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int32_t d = v[c][e] - mu;
+            const bool in = ALIGNED ? col < C : col + e < C;
+            const int32_t d = in ? v[c][e] - mu : 0;
             v[c][e] = d;
-            const uint32_t ad = (uint32_t)(d < 0 ? -d : d);
-            if (col + e < C) ss += (uint64_t)ad * ad;
+            ss += (uint32_t)smul24(d, d);
         }
     }
     ss = group_sum_u64<LPR>(ss);
 
     // var = floor(ss / C) < 2^32, with two 32-bit divisions: ss = (t << 11) + low, t < 2^31.
-    const uint32_t Cu = (uint32_t)C;
     const uint32_t t = (uint32_t)(ss >> 11);
-    const uint32_t qa = t / Cu;
+    const uint32_t qa = udiv_c(t, Cu, a.magic_c);
     const uint32_t rem = (uint32_t)(ss - (((uint64_t)qa * Cu) << 11));   // < C * 2^11 + 2^11
-    const uint32_t var = (qa << 11) + rem / Cu;
+    const uint32_t var = (qa << 11) + udiv_c(rem, Cu, a.magic_c);
 
     uint32_t sigma = isqrt_newton(var);
     sigma = sigma < 1u ? 1u : sigma;
     const int32_t f = (int32_t)((1u << 24) / sigma);
     if (!live) return;
+    // d*f: |d| < 2^17 always; f < 2^23 unless sigma <= 2, where the full 32-bit multiply is used instead
+    const bool f24 = __builtin_amdgcn_ballot_w64(f >= (1 << 23)) == 0;
 
     int8_t* yr = a.y + row * a.ldy;
-    const int32_t rnd = 1 << (a.shift - 1);
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         const int col = (c * LPR + lane) * 4;
@@ -127,13 +175,12 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
         int32_t o[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int ce = col + e < C ? col + e : C - 1;
-            const int32_t n = (v[c][e] * f) >> 14;                     // |d*f| < 2^30
-            const int32_t acc = n * a.gamma_q[ce] + a.beta_q[ce] + rnd;  // < 2^31 by the preconditions
-            o[e] = clamp_i32(acc >> a.shift, -127, 127);
+            const int32_t n = (f24 ? smul24(v[c][e], f) : v[c][e] * f) >> 14;   // |d*f| < 2^30; |n| < 2^16
+            const int32_t acc = smad24(n, gm[c][e], bt[c][e]);                     // |gamma_q| < 2^14: 24-bit multiply
+            o[e] = med3_i32(acc >> a.shift, -127, 127);
         }
-        if (ALIGNED && col + 3 < C) {
-            *reinterpret_cast<uint32_t*>(yr + col) = pack4_i8(o[0], o[1], o[2], o[3]);
+        if (ALIGNED) {
+            *reinterpret_cast<uint32_t*>(yr + col) = pack4_perm(o[0], o[1], o[2], o[3]);
         } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
@@ -163,14 +210,22 @@ int launch_layernorm(const int32_t* x, int8_t* y, int64_t rows, int32_t C, int64
 {
     if (rows == 0) return IBERT_OK;
     if (rows > 0x7fffffffLL) return IBERT_ERR_SHAPE;
-    LayerNormArgs a{x, y, rows, C, ldx, ldy, gamma_q, beta_q, shift};
-    const bool al = aligned(x, 16) && ldx % 4 == 0 && aligned(y, 4) && ldy % 4 == 0;
-    // Few rows: spread each row over a whole wavefront; many rows: 16 lanes per row.
-    const bool wide = rows < 2048;
-    if (wide) {
+    const uint32_t magic = C == 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) / (uint32_t)C) + 1);
+    LayerNormArgs a{x, y, rows, C, ldx, ldy, gamma_q, beta_q, shift, magic};
+    const bool al = aligned(x, 16) && ldx % 4 == 0 && aligned(y, 4) && ldy % 4 == 0 && C % 4 == 0 &&
+                    aligned(gamma_q, 16) && aligned(beta_q, 16);
+    // Lanes per row: the per-row scalar work (mean, variance, square root, reciprocal) is repeated by every
+    // lane of a row, so short groups are cheaper, but the chip needs about two wavefronts per SIMD (2048 in
+    // all) to overlap the load, reduce and store phases of different rows.
+    if (rows < 2048) {
         if (C <= 256) launch_rows<64, 1>(a, al, stream);
         else if (C <= 512) launch_rows<64, 2>(a, al, stream);
         else launch_rows<64, 4>(a, al, stream);
+    } else if (rows < 16384) {
+        if (C <= 256) launch_rows<32, 2>(a, al, stream);
+        else if (C <= 512) launch_rows<32, 4>(a, al, stream);
+        else if (C <= 768) launch_rows<32, 6>(a, al, stream);
+        else launch_rows<32, 8>(a, al, stream);
     } else {
         if (C <= 256) launch_rows<16, 4>(a, al, stream);
         else if (C <= 512) launch_rows<16, 8>(a, al, stream);

@@ -18,6 +18,7 @@ struct SoftmaxArgs {
     uint32_t q_ln2, q_b, q_c;
     uint32_t magic;      // floor(2^32 / q_ln2) + 1  (0 stands for 2^32, i.e. q_ln2 == 1)
     uint32_t d_cap;      // 31 * q_ln2: differences at or beyond it contribute e = 0
+    uint32_t magic27;    // floor(2^27 / q_ln2) + 1, used by the 24-bit path
     int32_t k;           // output fractional bits
 };
 
@@ -36,6 +37,19 @@ __device__ __forceinline__ uint32_t iexp_from_diff(uint32_t d, const SoftmaxArgs
     return poly >> z;                                  // z <= 31
 }
 
+// The same value with full-rate 24-bit multiplies, valid when 8 < q_ln2 < 2080 and q_b^2 + q_c < 2^24
+// (host-checked): d <= 31 q_ln2 < 2^16, so with M = floor(2^27/q_ln2) + 1 the product d*M stays below 2^32 and
+// floor(d*M / 2^27) = floor(d / q_ln2) exactly (the excess d/2^27 is below 1/q_ln2 because 31 q_ln2^2 < 2^27);
+// q_b - r = q_b - d + z q_ln2 is one multiply-add; (q_b - r)^2 + q_c another.
+__device__ __forceinline__ uint32_t iexp_from_diff_fast(uint32_t d, const SoftmaxArgs& a)
+{
+    d = d < a.d_cap ? d : a.d_cap;
+    const uint32_t z = umul24(d, a.magic27) >> 27;
+    const uint32_t v = umad24(z, a.q_ln2, a.q_b - d);           // q_b - r, in (0, q_b]
+    const uint32_t poly = umad24(v, v, a.q_c);                  // I-Poly, Alg. 1
+    return poly >> z;
+}
+
 // y = min(cap, (e*Fz + 2^(30-k)) >> (31-k)),  Fz = floor(2^31 / sum)
 __device__ __forceinline__ uint32_t normalise(uint32_t e, uint32_t Fz, int32_t k)
 {
@@ -45,27 +59,20 @@ __device__ __forceinline__ uint32_t normalise(uint32_t e, uint32_t Fz, int32_t k
 template <int LPR>
 __device__ __forceinline__ int32_t group_max(int32_t v)
 {
-#pragma unroll
-    for (int off = 1; off < LPR; off <<= 1) {
-        const int32_t o = __shfl_xor(v, off, 64);
-        v = o > v ? o : v;
-    }
-    return v;
+    return group_allreduce<LPR>(v, [](int32_t x, int32_t y) { return x > y ? x : y; });
 }
 
 template <int LPR>
 __device__ __forceinline__ uint32_t group_sum(uint32_t v)
 {
-#pragma unroll
-    for (int off = 1; off < LPR; off <<= 1) v += (uint32_t)__shfl_xor((int32_t)v, off, 64);
-    return v;
+    return (uint32_t)group_allreduce<LPR>((int32_t)v, [](int32_t x, int32_t y) { return (int32_t)((uint32_t)x + (uint32_t)y); });
 }
 
 constexpr int SM_THREADS = 256;
 
 // LPR lanes per row, NCH chunks of 4 elements per lane.  ALIGNED: rows start 16-byte aligned (x) and
 // 4-byte aligned (int8 y) / 16-byte aligned (int32 y), so full chunks move as vectors.
-template <int LPR, int NCH, bool ALIGNED, bool OUT_I8>
+template <int LPR, int NCH, bool ALIGNED, bool OUT_I8, bool FAST>
 __global__ __launch_bounds__(SM_THREADS) void softmax_rows_kernel(SoftmaxArgs a)
 {
     constexpr int ROWS_PER_BLOCK = SM_THREADS / LPR;
@@ -101,7 +108,7 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_rows_kernel(SoftmaxArgs a)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const uint32_t d = (uint32_t)mx - (uint32_t)q[c][e];
-            const uint32_t v = iexp_from_diff(d, a);
+            const uint32_t v = FAST ? iexp_from_diff_fast(d, a) : iexp_from_diff(d, a);
             ex[c][e] = (col + e < a.cols) ? v : 0u;
             sum += ex[c][e];
         }
@@ -116,7 +123,8 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_rows_kernel(SoftmaxArgs a)
         uint32_t o[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            o[e] = normalise(ex[c][e], Fz, a.k);
+            // FAST: e < 2^24 and Fz <= 2^23 (sum >= q_b^2 + q_c >= 2^8), so the 24-bit multiply is exact
+            o[e] = FAST ? umad24(ex[c][e], Fz, 1u << (30 - a.k)) >> (31 - a.k) : normalise(ex[c][e], Fz, a.k);
             if (OUT_I8) o[e] = o[e] > 127u ? 127u : o[e];
         }
         if (OUT_I8) {
@@ -199,14 +207,21 @@ int check_softmax(const ibert_softmax_params& p, int32_t cols)
 }
 
 template <int LPR, int NCH>
-static void launch_rows(const SoftmaxArgs& a, bool al, bool i8, hipStream_t stream)
+static void launch_rows(const SoftmaxArgs& a, bool al, bool i8, bool fast, hipStream_t stream)
 {
     constexpr int rpb = SM_THREADS / LPR;
-    const unsigned blocks = (unsigned)((a.rows + rpb - 1) / rpb);
-    if (al && i8) hipLaunchKernelGGL((softmax_rows_kernel<LPR, NCH, true, true>), dim3(blocks), dim3(SM_THREADS), 0, stream, a);
-    else if (al) hipLaunchKernelGGL((softmax_rows_kernel<LPR, NCH, true, false>), dim3(blocks), dim3(SM_THREADS), 0, stream, a);
-    else if (i8) hipLaunchKernelGGL((softmax_rows_kernel<LPR, NCH, false, true>), dim3(blocks), dim3(SM_THREADS), 0, stream, a);
-    else hipLaunchKernelGGL((softmax_rows_kernel<LPR, NCH, false, false>), dim3(blocks), dim3(SM_THREADS), 0, stream, a);
+    const dim3 grid((unsigned)((a.rows + rpb - 1) / rpb)), block(SM_THREADS);
+    if (al && i8 && fast) {                 // the layer's case
+        hipLaunchKernelGGL((softmax_rows_kernel<LPR, NCH, true, true, true>), grid, block, 0, stream, a);
+    } else if (al && i8) {
+        hipLaunchKernelGGL((softmax_rows_kernel<LPR, NCH, true, true, false>), grid, block, 0, stream, a);
+    } else if (al) {
+        hipLaunchKernelGGL((softmax_rows_kernel<LPR, NCH, true, false, false>), grid, block, 0, stream, a);
+    } else if (i8) {
+        hipLaunchKernelGGL((softmax_rows_kernel<LPR, NCH, false, true, false>), grid, block, 0, stream, a);
+    } else {
+        hipLaunchKernelGGL((softmax_rows_kernel<LPR, NCH, false, false, false>), grid, block, 0, stream, a);
+    }
 }
 
 int launch_softmax(const int32_t* x, void* y, int64_t rows, int32_t cols, int64_t ldx, int64_t ldy,
@@ -218,17 +233,20 @@ int launch_softmax(const int32_t* x, void* y, int64_t rows, int32_t cols, int64_
     a.q_ln2 = (uint32_t)p.q_ln2; a.q_b = (uint32_t)p.q_b; a.q_c = (uint32_t)p.q_c;
     a.magic = p.q_ln2 == 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) / (uint32_t)p.q_ln2) + 1);
     a.d_cap = 31u * (uint32_t)p.q_ln2;                 // q_ln2 <= q_b < 2^16 by the preconditions
+    a.magic27 = (uint32_t)((1u << 27) / (uint32_t)p.q_ln2) + 1u;
     a.k = p.out_frac_bits;
     const bool i8 = p.out_dtype == IBERT_I8;
+    const int64_t poly_max = (int64_t)p.q_b * p.q_b + p.q_c;
+    const bool fast = p.q_ln2 > 8 && p.q_ln2 < 2080 && poly_max >= 256 && poly_max < (1 << 24);
     const bool al = aligned(x, 16) && ldx % 4 == 0 && (i8 ? (aligned(y, 4) && ldy % 4 == 0) : (aligned(y, 16) && ldy % 4 == 0));
     if (rows > 0x7fffffffLL) return IBERT_ERR_SHAPE;
 
-    if (cols <= 16 * 4) launch_rows<16, 1>(a, al, i8, stream);
-    else if (cols <= 16 * 8) launch_rows<16, 2>(a, al, i8, stream);
-    else if (cols <= 32 * 8) launch_rows<32, 2>(a, al, i8, stream);
-    else if (cols <= 64 * 8) launch_rows<64, 2>(a, al, i8, stream);
-    else if (cols <= 64 * 16) launch_rows<64, 4>(a, al, i8, stream);
-    else if (cols <= 64 * 32) launch_rows<64, 8>(a, al, i8, stream);
+    if (cols <= 16 * 4) launch_rows<16, 1>(a, al, i8, fast, stream);
+    else if (cols <= 16 * 8) launch_rows<16, 2>(a, al, i8, fast, stream);
+    else if (cols <= 32 * 8) launch_rows<32, 2>(a, al, i8, fast, stream);
+    else if (cols <= 64 * 8) launch_rows<64, 2>(a, al, i8, fast, stream);
+    else if (cols <= 64 * 16) launch_rows<64, 4>(a, al, i8, fast, stream);
+    else if (cols <= 64 * 32) launch_rows<64, 8>(a, al, i8, fast, stream);
     else {
         if (i8) hipLaunchKernelGGL(softmax_long_kernel<true>, dim3((unsigned)rows), dim3(SM_THREADS), 0, stream, a);
         else hipLaunchKernelGGL(softmax_long_kernel<false>, dim3((unsigned)rows), dim3(SM_THREADS), 0, stream, a);
