@@ -35,6 +35,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch every step from the host instead of a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cpu-seqs", type=int, default=8, help="sequences of the workload the CPU oracle runs")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 256 MiB device copies (reference for the FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -147,6 +149,13 @@ def main():
         e["GB/s"] = round(d["bytes"] / (us * 1e-6) / 1e9, 1)
         e["hbm_frac"] = round(d["bytes"] / (us * 1e-6) / PEAK_HBM, 4)
         step_table["S%d" % step_no] = e
+
+    if args.copy_calibration:
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     # ---- CPU oracle on a bounded sample of the same workload (reported baseline, not the target)
     cpu = None

@@ -277,7 +277,7 @@ typedef struct {
     float ms;            /* event-to-event time of the step's launch(es) */
     double ops;          /* algorithmic integer ops: 2*M*N*K*batch for MatMul steps, 0 otherwise */
     double bytes;        /* algorithmic bytes: operands read once + outputs written once */
-    char kernel[48];     /* name of the kernel family the step launched */
+    char kernel[96];     /* name of the kernel the step launched, as a profiler shows it (without namespace) */
 } ibert_profile_record;
 
 int ibert_profile_begin(int32_t capacity);

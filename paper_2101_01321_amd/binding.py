@@ -81,7 +81,7 @@ class LayerScales(C.Structure):
 
 class ProfileRecord(C.Structure):
     _fields_ = [("step", C.c_int32), ("ms", C.c_float), ("ops", C.c_double), ("bytes", C.c_double),
-                ("kernel", C.c_char * 48)]
+                ("kernel", C.c_char * 96)]
 
 
 # Every symbol include/ibert.h declares, with its ctypes signature.
