@@ -13,6 +13,9 @@ SOURCES = ["host.cpp", "layer.cpp", "gelu.hip", "softmax.hip", "layernorm.hip", 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-FP32 instruction forms are switched off for all device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# MFMA accumulators in ordinary vector registers (destination tied to the addend): with the accumulator-register
+# form the register allocator shuffles the accumulators between the two halves of the pipelined K step.
+SOURCE_FLAGS = {"gemm.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def build(verbose: bool = False, extra_flags=()) -> str:
@@ -24,7 +27,7 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     for src in SOURCES:
         obj = os.path.join(bdir, src + ".o")
         cmd = [hipcc, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj, "-I" + os.path.join(ROOT, "include"),
-               "-I" + CSRC] + FLAGS + list(extra_flags)
+               "-I" + CSRC] + FLAGS + SOURCE_FLAGS.get(src, []) + list(extra_flags)
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

@@ -125,7 +125,13 @@ struct EpiLayout {
 // TW = true: W is [K,N] (N contiguous).  Only the W loader differs: each lane fetches a 4 (k) x 4 (n) byte
 // block as four dwords, transposes it in registers with byte permutes and writes four dwords (4 consecutive
 // k of one n) into the same K-contiguous LDS layout the MFMA loop reads.
-template <int BM, int BN, int BK, int RING, bool OUT_I8, int KMODE, bool TW = false>
+//
+// DMA = true (whole tiles only, BK = 128): the tiles go from global memory straight into LDS
+// (global_load_lds_dwordx4: lane l of a wavefront writes bytes [16 l, 16 l + 16) of a 1 KB LDS block, so a
+// block is 8 tile rows and the lane fetches the chunk that the swizzle puts at its position).  No register
+// ring and no LDS write instructions; a K step is two phases of MFMAs, each of which also issues the
+// fragment reads of the next phase and (second phase) the loads of the step after next, one barrier per step.
+template <int BM, int BN, int BK, int RING, bool OUT_I8, int KMODE, bool TW = false, bool DMA = false>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
 {
     constexpr int CPR = BK / 16;                       // 16-byte chunks per tile row
@@ -271,6 +277,81 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
         ps[q] = g.per_channel ? g.shift[nn] : g.dy_s;
     }
 
+    if constexpr (DMA) {
+        static_assert(BK == 128 && !TW && KMODE == 0 && BM % 32 == 0 && BN % 32 == 0, "DMA loader: whole 1 KB blocks");
+        constexpr int NLA = BM / 32, NLW = BN / 32, NL = NLA + NLW;   // 1 KB blocks per wavefront and step
+        constexpr int NMF = FM * FN, NR = FM + FN;
+        constexpr int SPC = NMF / NR > 0 ? NMF / NR : 1;              // MFMAs between two fragment reads
+        static_assert(NR == NL && (NMF + SPC - 1) / SPC >= NR, "one read and one load per slot");
+        const int wv = __builtin_amdgcn_readfirstlane(wave);
+        const int lr8 = lane >> 3, lp = lane & 7;
+        const int lsw = lr8 ^ (wv & 1);                               // swz<8> of the lane's row (block index parity = wave parity)
+        const uint32_t voff_a = (uint32_t)lr8 * (uint32_t)g.lda + (uint32_t)((lp ^ lsw) << 4);
+        const uint32_t voff_w = (uint32_t)lr8 * (uint32_t)g.ldw + (uint32_t)((lp ^ lsw) << 4);
+        const int8_t* ga = A + (int64_t)(m0 + wv * 8) * g.lda;
+        const int8_t* gw = W + (int64_t)(n0 + wv * 8) * g.ldw;
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t*)lds + (uint32_t)wv * 1024u;
+
+        // block q of the step: rows [32 i + 8 wave, +8) of A (q < NLA) or of W
+        auto dma_one = [&](int q, int kt, int buf) {
+            const bool is_a = q < NLA;
+            const int i = is_a ? q : q - NLA;
+            const int8_t* sb = (is_a ? ga + (int64_t)i * 32 * g.lda : gw + (int64_t)i * 32 * g.ldw) + (int64_t)kt * BK;
+            const uint32_t la = lds0 + (uint32_t)(buf * STAGE + (is_a ? 0 : BM * BK) + i * 4096);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :: "s"(la), "v"(is_a ? voff_a : voff_w), "s"(sb) : "memory", "m0");
+        };
+        auto read_one = [&](int q, int buf, int s, v4i (&xa)[FM], v4i (&wb)[FN]) {
+            const int8_t* base = lds + buf * STAGE + (((s * 4 + fch) ^ rd_swz) << 4);
+            if (q < FM) xa[q] = *reinterpret_cast<const v4i*>(base + rd_a + q * 16 * BK);
+            else wb[q - FM] = *reinterpret_cast<const v4i*>(base + rd_w + (q - FM) * 16 * BK);
+        };
+        // One phase: the MFMAs of one 64-wide K slice (operands xa, wb); every SPC MFMAs one fragment of
+        // the next phase is read (into nxa, nwb) and one block of a later step is requested.
+        auto phase = [&](v4i (&xa)[FM], v4i (&wb)[FN], v4i (&nxa)[FM], v4i (&nwb)[FN], int rbuf, int rs,
+                         auto read_tag, int dkt, int dbuf, bool dm) {
+            constexpr bool RD = decltype(read_tag)::value;
+#pragma unroll
+            for (int i = 0; i < FN; ++i)
+#pragma unroll
+                for (int jj = 0; jj < FM; ++jj) {
+                    const int idx = i * FM + jj;
+                    if (idx % SPC == 0 && idx / SPC < NR) {
+                        if (RD) read_one(idx / SPC, rbuf, rs, nxa, nwb);
+                        if (dm) dma_one(idx / SPC, dkt, dbuf);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    acc[i][jj] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wb[i], xa[jj], acc[i][jj], 0, 0, 0);
+                }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+
+#pragma unroll
+        for (int q = 0; q < NL; ++q) dma_one(q, 0, 0);
+        if (nk > 1) {
+#pragma unroll
+            for (int q = 0; q < NL; ++q) dma_one(q, 1, 1);
+            __builtin_amdgcn_s_waitcnt((NL & 15) | (7 << 4) | (15 << 8) | ((NL >> 4) << 14));   // vmcnt(NL): step 0 has landed
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+        asm volatile("s_barrier" ::: "memory");
+        v4i xa0[FM], wb0[FN], xa1[FM], wb1[FN];
+#pragma unroll
+        for (int q = 0; q < NR; ++q) read_one(q, 0, 0, xa0, wb0);
+        IBERT_TS(1);
+        // One K step.  Phase 1: slice 0 (fragments already in registers) while slice 1 is read.  Then this
+        // wavefront's share of step kt+1 has landed and its reads of buffer `buf` are done; after the barrier
+        // that holds for the whole workgroup, so `buf` may be refilled and the other buffer read.  Phase 2:
+        // slice 1, while slice 0 of step kt+1 is read and step kt+2 is requested (uniform test per request).
+        for (int kt = 0; kt < nk; ++kt) {
+            const int buf = kt & 1;
+            phase(xa0, wb0, xa1, wb1, buf, 1, std::true_type{}, 0, 0, false);
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            // (the fragment reads past the last step fetch stale LDS bytes that nothing uses)
+            phase(xa1, wb1, xa0, wb0, buf ^ 1, 0, std::true_type{}, kt + 2, buf, kt + 2 < nk);
+        }
+    } else {
     // The loop body is branch-free apart from one uniform test around the MFMAs, so that the compiler can
     // count outstanding loads exactly (vmcnt) instead of draining them: loads past the last step re-read
     // the last step (never used), and the LDS write of a step past the end lands in the idle buffer.
@@ -306,6 +387,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
             }
             __syncthreads();
         }
+    }
+
     }
 
     IBERT_TS(2);
@@ -469,6 +552,53 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
         }
     };
 
+    // Whole tiles on the fast path skip the staging: a lane already holds four consecutive channels of one
+    // token per accumulator, so it requantizes them in place and stores them itself (4 bytes INT8, 16 bytes
+    // INT32; the four lanes that share a token write 16 or 64 contiguous bytes).  The chain per value is
+    // register-only -- constants of the lane's channel group are re-read from LDS once per MFMA block column.
+    auto finish_direct = [&](auto res_tag) {
+        constexpr bool RES = decltype(res_tag)::value;
+        char* const c_base = reinterpret_cast<char*>(g.C) +
+                             (c_off + (int64_t)(m0 + wm0 + frow) * g.ldc + n0 + wn0 + 4 * fch) * (OUT_I8 ? 1 : 4);
+        const uint32_t* const r_base = resl + (wm0 + frow) * G4 + (wn0 >> 2) + fch;
+#pragma unroll
+        for (int i = 0; i < FN; ++i) {
+            const int cl = wn0 + 16 * i + 4 * fch;
+            const v4i bb = *reinterpret_cast<const v4i*>(par + cl);
+            const v4i mm = *reinterpret_cast<const v4i*>(par + BN + cl);
+            const v4i ss = *reinterpret_cast<const v4i*>(par + 2 * BN + cl);
+            int64_t cc[4];
+            int32_t sh[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                cc[e] = (int64_t)bb[e] * mm[e] + ((int64_t)1 << ((ss[e] - 1) & 63));
+                sh[e] = (ss[e] - 32) & 31;
+            }
+#pragma unroll
+            for (int j = 0; j < FM; ++j) {
+                uint32_t pk = 0;
+                if (RES) pk = r_base[j * 16 * G4 + i * 4];
+                int32_t o[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int64_t p = (int64_t)acc[i][j][e] * mm[e] + cc[e];
+                    int32_t v = (int32_t)(p >> 32) >> sh[e];
+                    if (RES) {
+                        const int32_t r8 = (int32_t)(int8_t)(pk >> (8 * e));
+                        v += (int32_t)(((int64_t)r8 * g.res_m + g.res_rnd) >> g.res_s);
+                    }
+                    o[e] = med3_i32(v, clamp_lo, clamp_hi);
+                }
+                char* cp = c_base + ((uint32_t)(j * 16) * c_pitch + (uint32_t)(i * 16 * (OUT_I8 ? 1 : 4)));
+                if (OUT_I8) *reinterpret_cast<uint32_t*>(cp) = pack4_i8(o[0], o[1], o[2], o[3]);
+                else *reinterpret_cast<v4i*>(cp) = v4i{o[0], o[1], o[2], o[3]};
+            }
+        }
+    };
+    if (interior && fast) {
+        if (R) finish_direct(std::true_type{});
+        else finish_direct(std::false_type{});
+    } else
 #pragma unroll
     for (int jc = 0; jc < FM / JC; ++jc) {
         if (jc > 0) __syncthreads();                               // the previous chunk has been consumed
@@ -562,8 +692,12 @@ static const GemmConfig kConfigs[] = {
     {128, 128, 64, 2, 0.45},
     {64, 64, 128, 3, 0.30},
     {64, 128, 64, 3, 0.35},
-    {256, 128, 64, 2, 0.50},
-    {128, 256, 64, 2, 0.50},
+    {128, 96, 128, 2, 0.50},
+    {256, 192, 128, 1, 0.70},       // ring 1: direct-to-LDS loader (whole tiles only)
+    {128, 128, 128, 1, 0.60},
+    {256, 256, 128, 1, 0.75},
+    {128, 96, 128, 1, 0.45},
+    {256, 128, 128, 1, 0.60},
 };
 constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 #ifdef IBERT_KERNEL_TIMING
@@ -571,7 +705,7 @@ static long long* g_dbg_buf = nullptr;
 #endif
 static int g_config_override = -1;
 
-template <int BM, int BN, int BK, int RING, bool TW = false>
+template <int BM, int BN, int BK, int RING, bool TW = false, bool DMA = false>
 static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
 {
     g.tiles_m = (g.M + BM - 1) / BM;
@@ -583,7 +717,7 @@ static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
     static_assert(lds_bytes <= 163840, "LDS budget");
 #define IBERT_GEMM_LAUNCH(I8_, KT_)                                                                       \
     do {                                                                                                  \
-        auto kern = gemm_nt_mfma_kernel<BM, BN, BK, RING, I8_, KT_, TW>;                                      \
+        auto kern = gemm_nt_mfma_kernel<BM, BN, BK, RING, I8_, KT_, TW, DMA>;                                 \
         static bool attr_done = false;                                                                    \
         if (!attr_done) {                                                                                 \
             IBERT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                      \
@@ -594,8 +728,10 @@ static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
     } while (0)
     if (g.K % BK == 0) {
         if (i8) IBERT_GEMM_LAUNCH(true, 0); else IBERT_GEMM_LAUNCH(false, 0);
-    } else {
+    } else if constexpr (!DMA) {
         if (i8) IBERT_GEMM_LAUNCH(true, 1); else IBERT_GEMM_LAUNCH(false, 1);
+    } else {
+        return IBERT_ERR_SHAPE;                                    // never chosen for such K
     }
 #undef IBERT_GEMM_LAUNCH
     IBERT_LAUNCH_CHECK("gemm_nt_mfma_kernel");
@@ -603,8 +739,8 @@ static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
     static char label[2][2][96];
     char* l = label[i8 ? 1 : 0][g.K % BK == 0 ? 0 : 1];
     if (!l[0])
-        std::snprintf(l, sizeof label[0][0], "gemm_nt_mfma_kernel<%d, %d, %d, %d, %s, %d, %s>", BM, BN, BK, RING,
-                      i8 ? "true" : "false", g.K % BK == 0 ? 0 : 1, TW ? "true" : "false");
+        std::snprintf(l, sizeof label[0][0], "gemm_nt_mfma_kernel<%d, %d, %d, %d, %s, %d, %s, %s>", BM, BN, BK, RING,
+                      i8 ? "true" : "false", g.K % BK == 0 ? 0 : 1, TW ? "true" : "false", DMA ? "true" : "false");
     g_last_kernel = l;
     return IBERT_OK;
 }
@@ -633,16 +769,31 @@ static int launch_tail(GemmArgs& g, bool i8, hipStream_t stream)
     return IBERT_OK;
 }
 
-// Tile choice (measured on MI355X at RoBERTa-Base/Large shapes): these GEMMs are too short for one big
-// tile per CU -- ramp, barriers and the requantizing epilogue would not overlap with anything -- so prefer
-// 128x128 tiles with a 64-wide K step, of which three fit a CU at once, as long as that still gives every
-// CU something to do; below that, 64x64 tiles.
-static int choose_config(int64_t M, int64_t N, int64_t K, int64_t nb)
+// The direct-to-LDS loader handles whole tiles only, with row offsets that fit its 32-bit lane offsets.
+static bool dma_ok(const ibert_gemm_desc& d, int bm, int bn)
+{
+    return d.M % bm == 0 && d.N % bn == 0 && d.K % 128 == 0 && d.lda < (1 << 28) && d.ldw < (1 << 28);
+}
+
+// Tile choice, measured on MI355X at RoBERTa-Base/Large shapes (256 CUs).
+// Whole-tile problems with K a multiple of 128 take the direct-to-LDS loader: the biggest tile that still
+// gives (nearly) every CU a workgroup -- big wavefront tiles need fewer LDS bytes per MFMA, which is what
+// limits the loop -- and, when the problem is too small for that, 128x96 tiles, several of which share a CU
+// so that one workgroup's requantization overlaps another's MFMAs.
+// Everything else takes the register-ring loader: 128x128 tiles with a 64-wide K step while that gives every
+// CU something to do, below that 64x64 tiles.
+static int choose_config(const ibert_gemm_desc& d, int64_t nb)
 {
     if (g_config_override >= 0 && g_config_override < kNumConfigs) return g_config_override;
-    const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128) * nb;
+    auto tiles = [&](int bm, int bn) -> int64_t { return dma_ok(d, bm, bn) ? (int64_t)(d.M / bm) * (d.N / bn) * nb : 0; };
+    if (tiles(256, 256) >= 512) return 8;
+    if (tiles(256, 192) >= 224) return 6;
+    if (tiles(128, 96) >= 256) return 9;
+    if (tiles(256, 128) >= 448) return 10;
+    if (tiles(128, 128) >= 128) return 7;
+    const int64_t tiles128 = (((int64_t)d.M + 127) / 128) * (((int64_t)d.N + 127) / 128) * nb;
     if (tiles128 >= 384) return 2;
-    return K >= 512 ? 3 : 4;
+    return d.K >= 512 ? 3 : 4;
 }
 
 int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, const int32_t* bias,
@@ -679,15 +830,21 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
                       d.strideW_inner % 16 == 0;
     if (fast) {
         if (d.K % 16 != 0) return launch_tail(g, i8, stream);       // bytewise K tail
-        switch (choose_config(d.M, d.N, d.K, nb)) {
+        switch (choose_config(d, nb)) {
             case 0: return launch_mfma<256, 192, 128, 2>(g, i8, stream);
             case 1: return launch_mfma<128, 128, 128, 2>(g, i8, stream);
             case 2: return launch_mfma<128, 128, 64, 2>(g, i8, stream);
             case 3: return launch_mfma<64, 64, 128, 3>(g, i8, stream);
             case 4: return launch_mfma<64, 128, 64, 3>(g, i8, stream);
-            case 5: return launch_mfma<256, 128, 64, 2>(g, i8, stream);
-            default: return launch_mfma<128, 256, 64, 2>(g, i8, stream);
+            case 5: return launch_mfma<128, 96, 128, 2>(g, i8, stream);
+            case 6: if (dma_ok(d, 256, 192)) return launch_mfma<256, 192, 128, 1, false, true>(g, i8, stream); break;
+            case 7: if (dma_ok(d, 128, 128)) return launch_mfma<128, 128, 128, 1, false, true>(g, i8, stream); break;
+            case 8: if (dma_ok(d, 256, 256)) return launch_mfma<256, 256, 128, 1, false, true>(g, i8, stream); break;
+            case 9: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 1, false, true>(g, i8, stream); break;
+            case 10: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 1, false, true>(g, i8, stream); break;
+            default: break;
         }
+        return launch_mfma<128, 128, 64, 2>(g, i8, stream);
     }
     const bool fast_tw = d.trans_w == 1 && d.K > 0 && d.K % 16 == 0 && d.N >= 4 && d.N % 4 == 0 && aligned(A, 16) &&
                          aligned(W, 4) && d.lda % 16 == 0 && d.ldw % 4 == 0 && d.strideA_outer % 16 == 0 &&

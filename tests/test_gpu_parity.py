@@ -240,6 +240,21 @@ def test_gemm_trans_w_mfma_path(G, M, N, K, ldw):
         _eq(got, oracle.gemm_requant(spec, A.reshape(-1), W.reshape(-1), out_elems=nb * M * N), "trans_w gemm")
 
 
+@pytest.mark.parametrize("cfg,M,N,K", [(6, 512, 384, 128), (6, 256, 576, 256), (6, 768, 192, 768), (7, 128, 128, 128),
+                                       (7, 384, 256, 384), (7, 256, 640, 1152), (8, 512, 256, 256), (8, 256, 768, 640)])
+def test_gemm_direct_to_lds_tiles(G, cfg, M, N, K):
+    # the tile configurations whose loader writes LDS straight from global memory (whole tiles only), forced
+    # through the configuration override; 1, 2, odd and even numbers of K steps
+    from paper_2101_01321_amd import binding as B
+    assert B.lib().ibert_gemm_config_override(cfg) > cfg
+    try:
+        for out_dtype, pc, bias, res in [(I8, 1, True, False), (I32, 1, True, True), (I8, 0, False, True)]:
+            G.say("gemm direct-to-LDS cfg=%d M=%d N=%d K=%d out=%d" % (cfg, M, N, K, out_dtype))
+            _gemm_case(G, M, N, K, out_dtype, pc, bias, res, seed=cfg + M + N + K)
+    finally:
+        B.lib().ibert_gemm_config_override(-1)
+
+
 def test_gemm_base_shapes_full(G):
     # the four projection GEMMs of RoBERTa-Base at batch 32 (T = 4096), full outputs
     for M, N, K, od, res in [(4096, 2304, 768, I8, False), (4096, 768, 768, I32, True), (4096, 3072, 768, I32, False),
