@@ -145,6 +145,22 @@ typedef struct {
 int ibert_gelu_i(const int32_t* x, int8_t* y, int64_t n, const ibert_gelu_params* params, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * ibert_gemm_i8_gelu -- the FFN up-projection and its GELU in one call (Sec. 4.1: the MatMul result is
+ * requantized to the GELU input scale; Alg. 2 follows), bit-identical to
+ *     ibert_gemm_i8_requant(desc with out_dtype = IBERT_I32, out_clamp = gelu->q_max, no residual) -> f
+ *     ibert_gelu_i(f) -> C
+ * C: device int8, laid out by desc (ldc, batch strides); desc->out_dtype, out_clamp and residual_dy are ignored.
+ * When the problem fits a whole-tile MFMA configuration (M, N multiples of the tile, K a multiple of 128,
+ * 16-byte aligned A/W rows) GELU runs in the MatMul epilogue and the INT32 tensor f never exists.  Otherwise the
+ * two kernels run back to back through `scratch` (device int32, M*N*batch entries): that needs dense
+ * outputs (ldc = N, dense batch strides; else IBERT_ERR_NOT_IMPLEMENTED) and a non-NULL scratch
+ * (else IBERT_ERR_WORKSPACE).  scratch may always be passed; it is untouched on the one-kernel path.
+ * ---------------------------------------------------------------------------------------------- */
+int ibert_gemm_i8_gelu(const ibert_gemm_desc* desc, const int8_t* A, const int8_t* W, const int32_t* bias,
+                       const int32_t* mult, const int32_t* shift, const ibert_gelu_params* gelu, int8_t* C,
+                       int32_t* scratch, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
  * ibert_layernorm_i -- integer-only LayerNorm over the last axis (Sec. 3.6, Eq. 15, Alg. 4).
  * The paper specifies the integer square root and leaves the rest "straightforward"; reading:
  *   x_i  <- clamp(x_i, -(2^15-1), 2^15-1)
@@ -263,6 +279,12 @@ typedef struct {
 
 int ibert_layer_quant_from_scales(const ibert_layer_scales* scales, int32_t seq, int32_t head_dim,
                                   ibert_layer_quant* out);
+
+/* Kernel fusions inside ibert_encoder_layer_i / ibert_encoder_i.  Bit 0: steps 7 and 8 (FFN up-projection and
+ * GELU) run as one kernel where ibert_gemm_i8_gelu can do so; the workspace region f1 is then left untouched.
+ * Default: 1.  flags >= 0 sets the mask (unknown bits are dropped), a negative value only queries.  Returns the
+ * previous mask.  Outputs do not depend on the mask.  Not thread-safe. */
+int ibert_set_fusion(int32_t flags);
 
 /* ------------------------------------------------------------------------------------------------
  * Optional instrumentation for benchmarks (not part of the method): while a profile is open,

@@ -88,6 +88,8 @@ class ProfileRecord(C.Structure):
 SIGNATURES = {
     "ibert_gemm_i8_requant": (C.c_int, [C.POINTER(GemmDesc)] + [_P] * 8),
     "ibert_gemm_config_override": (C.c_int, [C.c_int32]),
+    "ibert_gemm_i8_gelu": (C.c_int, [C.POINTER(GemmDesc)] + [_P] * 5 + [C.POINTER(GeluParams)] + [_P] * 3),
+    "ibert_set_fusion": (C.c_int, [C.c_int32]),
     "ibert_softmax_i": (C.c_int, [_P, _P, C.c_int64, C.c_int32, C.c_int64, C.c_int64, C.POINTER(SoftmaxParams), _P]),
     "ibert_gelu_i": (C.c_int, [_P, _P, C.c_int64, C.POINTER(GeluParams), _P]),
     "ibert_layernorm_i": (C.c_int, [_P, _P, C.c_int64, C.c_int32, C.c_int64, C.c_int64, _P, _P, C.c_int32, _P]),
@@ -201,6 +203,15 @@ def ibert_layer_quant_from_scales(sc: dict, seq: int, head_dim: int) -> LayerQua
 def ibert_gemm_i8_requant(desc: GemmDesc, A, W, bias, mult, shift, residual, Cout, stream=None):
     _chk(lib().ibert_gemm_i8_requant(C.byref(desc), _dp(A), _dp(W), _dp(bias), _dp(mult), _dp(shift), _dp(residual),
                                      _dp(Cout), _stream(stream)), "ibert_gemm_i8_requant")
+
+
+def ibert_gemm_i8_gelu(desc: GemmDesc, A, W, bias, mult, shift, gelu: GeluParams, Cout, scratch, stream=None):
+    _chk(lib().ibert_gemm_i8_gelu(C.byref(desc), _dp(A), _dp(W), _dp(bias), _dp(mult), _dp(shift), C.byref(gelu),
+                                  _dp(Cout), _dp(scratch), _stream(stream)), "ibert_gemm_i8_gelu")
+
+
+def ibert_set_fusion(flags: int) -> int:
+    return int(lib().ibert_set_fusion(flags))
 
 
 def ibert_softmax_i(x, y, rows: int, cols: int, ldx: int, ldy: int, params: SoftmaxParams, stream=None):

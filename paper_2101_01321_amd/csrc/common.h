@@ -119,7 +119,10 @@ extern const char* g_last_kernel;
 // ---- internal launchers (validated arguments) -----------------------------------------------
 int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, const int32_t* bias,
                 const int32_t* mult, const int32_t* shift, const int8_t* residual, void* C,
-                hipStream_t stream);
+                hipStream_t stream, const ibert_gelu_params* gelu = nullptr);
+int launch_gemm_gelu(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, const int32_t* bias,
+                     const int32_t* mult, const int32_t* shift, const ibert_gelu_params& gelu, int8_t* C,
+                     int32_t* scratch, hipStream_t stream);
 int launch_softmax(const int32_t* x, void* y, int64_t rows, int32_t cols, int64_t ldx, int64_t ldy,
                    const ibert_softmax_params& p, hipStream_t stream);
 int launch_gelu(const int32_t* x, int8_t* y, int64_t n, const ibert_gelu_params& p, hipStream_t stream);

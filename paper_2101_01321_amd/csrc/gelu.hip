@@ -2,6 +2,7 @@
 // Element-wise and HBM-bound: 4 bytes in, 1 byte out per element.  Each lane streams 16-byte
 // chunks (four int32), several in flight, and writes one packed dword per chunk.
 #include "common.h"
+#include "gelu_math.h"
 
 namespace ibert {
 
@@ -9,40 +10,8 @@ struct GeluArgs {
     const int32_t* x;
     int8_t* y;
     int64_t n;
-    int32_t q_b, q_c, q_1, q_max;
-    int32_t m, s;
+    GeluConst c;
 };
-
-// One element, general parameters.  All products stay inside 32 bits by the host-checked preconditions
-// ((u+q_b)^2 + q_c and q*(erf+q_1) are bounded by q_max * (|poly| + |q_1|) < 2^31).
-__device__ __forceinline__ int32_t gelu_one(int32_t q, const GeluArgs& a)
-{
-    q = clamp_i32(q, -a.q_max, a.q_max);
-    int32_t u = q < 0 ? -q : q;
-    u = u > -a.q_b ? -a.q_b : u;                      // clip(|q|, max = -q_b)
-    const int32_t v = u + a.q_b;
-    // I-Poly, Alg. 1.  Unsigned arithmetic: the true values fit 32 bits, partial terms may wrap.
-    const uint32_t poly = (uint32_t)v * (uint32_t)v + (uint32_t)a.q_c;
-    const uint32_t erf = q < 0 ? 0u - poly : (q == 0 ? 0u : poly);          // sgn(q) * poly
-    const int32_t t = (int32_t)((uint32_t)q * (erf + (uint32_t)a.q_1));
-    return clamp_i64_to_i32(dyadic64(t, a.m, a.s), 127);
-}
-
-// One element when q_max, |q_b| and max|erf + q_1| are below 2^23 and the output shift is in [33, 62]: every
-// product is a full-rate 24-bit multiply, and the requantization is a multiply-high, an add and a shift
-// (floor((t m + 2^(s-1)) / 2^s) = (hi32(t m) + 2^(s-33)) >> (s-32), exact for s >= 33).
-// sgn(q)*poly needs no special case at q = 0 because t = q * (...) is zero there anyway.
-__device__ __forceinline__ int32_t gelu_one_fast(int32_t q, const GeluArgs& a, int32_t rnd, int32_t sh)
-{
-    q = med3_i32(q, -a.q_max, a.q_max);
-    const int32_t aq = max(q, -q);
-    const int32_t v = min(aq, -a.q_b) + a.q_b;        // in [q_b, 0]
-    const int32_t poly = smad24(v, v, a.q_c);         // I-Poly, Alg. 1
-    const int32_t sg = q >> 31;
-    const int32_t erf = (poly ^ sg) - sg;             // -poly for q < 0
-    const int32_t t = smul24(q, erf + a.q_1);
-    return med3_i32((__mulhi(t, a.m) + rnd) >> sh, -127, 127);
-}
 
 constexpr int GELU_THREADS = 256;
 constexpr int GELU_UNROLL = 4;                        // 16-byte chunks per lane
@@ -51,8 +20,8 @@ template <bool VEC, bool FAST>
 __global__ __launch_bounds__(GELU_THREADS) void gelu_kernel(GeluArgs a)
 {
     const int64_t block_base = (int64_t)blockIdx.x * (GELU_THREADS * GELU_UNROLL * 4);
-    const int32_t rnd = 1 << ((a.s - 33) & 31), sh = (a.s - 32) & 31;
-    auto one = [&](int32_t q) { return FAST ? gelu_one_fast(q, a, rnd, sh) : gelu_one(q, a); };
+    const int32_t rnd = 1 << ((a.c.s - 33) & 31), sh = (a.c.s - 32) & 31;
+    auto one = [&](int32_t q) { return FAST ? gelu_one_fast(q, a.c, rnd, sh) : gelu_one(q, a.c); };
     if (VEC) {
         int4 v[GELU_UNROLL];
         int64_t base[GELU_UNROLL];
@@ -94,17 +63,12 @@ int check_gelu(const ibert_gelu_params& p)
 int launch_gelu(const int32_t* x, int8_t* y, int64_t n, const ibert_gelu_params& p, hipStream_t stream)
 {
     if (n == 0) return IBERT_OK;
-    GeluArgs a{x, y, n, p.q_b, p.q_c, p.q_1, p.q_max, p.out.m, p.out.s};
+    GeluArgs a{x, y, n, GeluConst{p.q_b, p.q_c, p.q_1, p.q_max, p.out.m, p.out.s}};
     const int64_t per_block = (int64_t)GELU_THREADS * GELU_UNROLL * 4;
     const int64_t blocks = (n + per_block - 1) / per_block;
     if (blocks > 0x7fffffffLL) return IBERT_ERR_SHAPE;
     const bool vec = aligned(x, 16) && aligned(y, 4);
-    // 24-bit fast path: see gelu_one_fast
-    const int64_t top = (int64_t)p.q_b * p.q_b + p.q_c;
-    const int64_t a1 = top < 0 ? -top : top, a2 = p.q_c < 0 ? -(int64_t)p.q_c : p.q_c;
-    const int64_t wmax = (a1 > a2 ? a1 : a2) + (p.q_1 < 0 ? -(int64_t)p.q_1 : p.q_1);
-    const int64_t lim = 1 << 23;
-    const bool fast = p.q_max < lim && -(int64_t)p.q_b < lim && wmax < lim && p.out.s >= 33 && p.out.s <= 62;
+    const bool fast = gelu_fast_ok(p);                 // 24-bit fast path
     const dim3 grid((unsigned)blocks), block(GELU_THREADS);
     if (vec && fast) hipLaunchKernelGGL((gelu_kernel<true, true>), grid, block, 0, stream, a);
     else if (vec) hipLaunchKernelGGL((gelu_kernel<true, false>), grid, block, 0, stream, a);

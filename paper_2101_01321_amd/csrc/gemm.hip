@@ -14,6 +14,7 @@
 #include <type_traits>
 
 #include "common.h"
+#include "gelu_math.h"
 
 namespace ibert {
 
@@ -41,6 +42,8 @@ struct GemmArgs {
     int32_t res_fast;  // residual absent, or its shift is in [8, 62]: its requantized value fits 32 bits
     int64_t res_rnd;   // 2^(res_s - 1), or 0 when res_s == 0
     int32_t xcd_chunk; // tiles per XCD when the grid divides by 8, else 0 (no remap)
+    int32_t gelu_fast; // GELU epilogue: the 24-bit form applies
+    GeluConst gelu;    // GELU epilogue: constants (the clamp before it is out_clamp = q_max)
 #ifdef IBERT_KERNEL_TIMING
     long long* dbg;    // development only: per-wave phase timestamps
 #endif
@@ -131,9 +134,12 @@ struct EpiLayout {
 // block is 8 tile rows and the lane fetches the chunk that the swizzle puts at its position).  No register
 // ring and no LDS write instructions; a K step is two phases of MFMAs, each of which also issues the
 // fragment reads of the next phase and (second phase) the loads of the step after next, one barrier per step.
-template <int BM, int BN, int BK, int RING, bool OUT_I8, int KMODE, bool TW = false, bool DMA = false>
+// GELU = true (INT8 output): the requantized, clamped value is the GELU input; integer GELU (Alg. 2) and its
+// requantization to INT8 are applied before the store, so the INT32 tensor between the two never exists.
+template <int BM, int BN, int BK, int RING, bool OUT_I8, int KMODE, bool TW = false, bool DMA = false, bool GELU = false>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
 {
+    static_assert(!GELU || OUT_I8, "the GELU epilogue writes INT8");
     constexpr int CPR = BK / 16;                       // 16-byte chunks per tile row
     constexpr int RPP = GEMM_THREADS / CPR;            // tile rows loaded per pass of the workgroup
     constexpr int LA = BM / RPP, LW = BN / RPP;        // chunks per lane per K step
@@ -474,6 +480,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
         sh32[e] = (s4[e] - 32) & 31;
     }
     const int32_t clamp_lo = -g.out_clamp, clamp_hi = g.out_clamp;
+    const int32_t gelu_rnd = 1 << ((g.gelu.s - 33) & 31), gelu_sh = (g.gelu.s - 32) & 31;
+    auto post = [&](int32_t v) {                                   // v is already clamped to +-out_clamp
+        if constexpr (GELU) return g.gelu_fast ? gelu_one_fast(v, g.gelu, gelu_rnd, gelu_sh) : gelu_one(v, g.gelu);
+        else return v;
+    };
+    auto post_fast = [&](int32_t v) {                              // same, the caller has tested g.gelu_fast
+        if constexpr (GELU) return gelu_one_fast(v, g.gelu, gelu_rnd, gelu_sh);
+        else return v;
+    };
     auto requant4 = [&](const v4i& a4, const int32_t (&res)[4], bool has_res, auto fast_tag, int32_t (&o)[4]) {
         constexpr bool FAST = decltype(fast_tag)::value;
 #pragma unroll
@@ -482,13 +497,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
                 const int64_t p = (int64_t)a4[e] * m4[e] + c0[e];                                       // |p| < 2^63
                 int32_t v = (int32_t)(p >> 32) >> sh32[e];                                              // |v| <= 2^30
                 if (has_res) v += (int32_t)(((int64_t)res[e] * g.res_m + g.res_rnd) >> g.res_s);       // |.| < 2^30
-                o[e] = med3_i32(v, clamp_lo, clamp_hi);
+                o[e] = post(med3_i32(v, clamp_lo, clamp_hi));
             } else {
                 const int32_t a = a4[e] + b4[e];
                 const int sh = s4[e] & 63;
                 int64_t v = ((int64_t)a * m4[e] + (sh > 0 ? (int64_t)1 << (sh - 1) : 0)) >> sh;
                 if (has_res) v += ((int64_t)res[e] * g.res_m + g.res_rnd) >> g.res_s;
-                o[e] = clamp_i64_to_i32(v, g.out_clamp);
+                o[e] = post(clamp_i64_to_i32(v, g.out_clamp));
             }
         }
     };
@@ -556,8 +571,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
     // token per accumulator, so it requantizes them in place and stores them itself (4 bytes INT8, 16 bytes
     // INT32; the four lanes that share a token write 16 or 64 contiguous bytes).  The chain per value is
     // register-only -- constants of the lane's channel group are re-read from LDS once per MFMA block column.
-    auto finish_direct = [&](auto res_tag) {
-        constexpr bool RES = decltype(res_tag)::value;
+    auto finish_direct = [&](auto res_tag, auto gf_tag) {
+        constexpr bool RES = decltype(res_tag)::value, GF = decltype(gf_tag)::value;
         char* const c_base = reinterpret_cast<char*>(g.C) +
                              (c_off + (int64_t)(m0 + wm0 + frow) * g.ldc + n0 + wn0 + 4 * fch) * (OUT_I8 ? 1 : 4);
         const uint32_t* const r_base = resl + (wm0 + frow) * G4 + (wn0 >> 2) + fch;
@@ -587,7 +602,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
                         const int32_t r8 = (int32_t)(int8_t)(pk >> (8 * e));
                         v += (int32_t)(((int64_t)r8 * g.res_m + g.res_rnd) >> g.res_s);
                     }
-                    o[e] = med3_i32(v, clamp_lo, clamp_hi);
+                    v = med3_i32(v, clamp_lo, clamp_hi);
+                    o[e] = GF ? post_fast(v) : post(v);
                 }
                 char* cp = c_base + ((uint32_t)(j * 16) * c_pitch + (uint32_t)(i * 16 * (OUT_I8 ? 1 : 4)));
                 if (OUT_I8) *reinterpret_cast<uint32_t*>(cp) = pack4_i8(o[0], o[1], o[2], o[3]);
@@ -596,8 +612,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
         }
     };
     if (interior && fast) {
-        if (R) finish_direct(std::true_type{});
-        else finish_direct(std::false_type{});
+        if (GELU && g.gelu_fast) finish_direct(std::false_type{}, std::true_type{});      // GELU excludes a residual
+        else if (R) finish_direct(std::true_type{}, std::false_type{});
+        else finish_direct(std::false_type{}, std::false_type{});
     } else
 #pragma unroll
     for (int jc = 0; jc < FM / JC; ++jc) {
@@ -705,7 +722,7 @@ static long long* g_dbg_buf = nullptr;
 #endif
 static int g_config_override = -1;
 
-template <int BM, int BN, int BK, int RING, bool TW = false, bool DMA = false>
+template <int BM, int BN, int BK, int RING, bool TW = false, bool DMA = false, bool GELU = false>
 static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
 {
     g.tiles_m = (g.M + BM - 1) / BM;
@@ -717,7 +734,7 @@ static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
     static_assert(lds_bytes <= 163840, "LDS budget");
 #define IBERT_GEMM_LAUNCH(I8_, KT_)                                                                       \
     do {                                                                                                  \
-        auto kern = gemm_nt_mfma_kernel<BM, BN, BK, RING, I8_, KT_, TW, DMA>;                                 \
+        auto kern = gemm_nt_mfma_kernel<BM, BN, BK, RING, I8_, KT_, TW, DMA, GELU && I8_>;                    \
         static bool attr_done = false;                                                                    \
         if (!attr_done) {                                                                                 \
             IBERT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                      \
@@ -726,7 +743,10 @@ static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
         }                                                                                                 \
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(GEMM_THREADS), lds_bytes, stream, g);       \
     } while (0)
-    if (g.K % BK == 0) {
+    if constexpr (GELU) {
+        if (!i8 || g.K % BK != 0) return IBERT_ERR_NOT_IMPLEMENTED;
+        IBERT_GEMM_LAUNCH(true, 0);
+    } else if (g.K % BK == 0) {
         if (i8) IBERT_GEMM_LAUNCH(true, 0); else IBERT_GEMM_LAUNCH(false, 0);
     } else if constexpr (!DMA) {
         if (i8) IBERT_GEMM_LAUNCH(true, 1); else IBERT_GEMM_LAUNCH(false, 1);
@@ -739,8 +759,9 @@ static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
     static char label[2][2][96];
     char* l = label[i8 ? 1 : 0][g.K % BK == 0 ? 0 : 1];
     if (!l[0])
-        std::snprintf(l, sizeof label[0][0], "gemm_nt_mfma_kernel<%d, %d, %d, %d, %s, %d, %s, %s>", BM, BN, BK, RING,
-                      i8 ? "true" : "false", g.K % BK == 0 ? 0 : 1, TW ? "true" : "false", DMA ? "true" : "false");
+        std::snprintf(l, sizeof label[0][0], "gemm_nt_mfma_kernel<%d, %d, %d, %d, %s, %d, %s, %s, %s>", BM, BN, BK, RING,
+                      i8 ? "true" : "false", g.K % BK == 0 ? 0 : 1, TW ? "true" : "false", DMA ? "true" : "false",
+                      GELU ? "true" : "false");
     g_last_kernel = l;
     return IBERT_OK;
 }
@@ -796,8 +817,11 @@ static int choose_config(const ibert_gemm_desc& d, int64_t nb)
     return d.K >= 512 ? 3 : 4;
 }
 
+// gelu != nullptr asks for the GELU epilogue (INT8 output, no residual; out_clamp must be gelu->q_max): only the
+// direct-to-LDS tiles carry it, any other problem returns IBERT_ERR_NOT_IMPLEMENTED without launching.
 int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, const int32_t* bias,
-                const int32_t* mult, const int32_t* shift, const int8_t* residual, void* C, hipStream_t stream)
+                const int32_t* mult, const int32_t* shift, const int8_t* residual, void* C, hipStream_t stream,
+                const ibert_gelu_params* gelu)
 {
     const int64_t nb = (int64_t)d.batch_outer * d.batch_inner;
     if (nb == 0 || d.M == 0 || d.N == 0) return IBERT_OK;
@@ -822,15 +846,35 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
     g.res_fast = (!residual || (d.residual_dy.s >= 8 && d.residual_dy.s <= 62)) ? 1 : 0;
     g.res_rnd = (residual && d.residual_dy.s >= 1 && d.residual_dy.s <= 62) ? ((int64_t)1 << (d.residual_dy.s - 1)) : 0;
     const bool i8 = d.out_dtype == IBERT_I8;
+    g.gelu_fast = 0;
+    g.gelu = GeluConst{0, 0, 0, 0, 0, 0};
+    if (gelu) {
+        if (!i8 || residual || d.out_clamp != gelu->q_max) return IBERT_ERR_NOT_IMPLEMENTED;
+        g.gelu = GeluConst{gelu->q_b, gelu->q_c, gelu->q_1, gelu->q_max, gelu->out.m, gelu->out.s};
+        g.gelu_fast = gelu_fast_ok(*gelu) ? 1 : 0;
+    }
     g.c_vec = aligned(C, i8 ? 4 : 16) && d.ldc % 4 == 0 && d.strideC_outer % 4 == 0 && d.strideC_inner % 4 == 0;
     g.r_vec = residual && aligned(residual, 16) && d.ldr % 16 == 0 && d.strideR_outer % 16 == 0 && d.strideR_inner % 16 == 0;
 
     const bool fast = d.trans_w == 0 && d.K > 0 && aligned(A, 16) && aligned(W, 16) && d.lda % 16 == 0 && d.ldw % 16 == 0 &&
                       d.strideA_outer % 16 == 0 && d.strideA_inner % 16 == 0 && d.strideW_outer % 16 == 0 &&
                       d.strideW_inner % 16 == 0;
+    if (gelu && !(fast && d.K % 16 == 0)) return IBERT_ERR_NOT_IMPLEMENTED;
     if (fast) {
         if (d.K % 16 != 0) return launch_tail(g, i8, stream);       // bytewise K tail
-        switch (choose_config(d, nb)) {
+        const int cfg = choose_config(d, nb);
+        if (gelu) {
+            switch (cfg) {
+                case 6: if (dma_ok(d, 256, 192)) return launch_mfma<256, 192, 128, 1, false, true, true>(g, i8, stream); break;
+                case 7: if (dma_ok(d, 128, 128)) return launch_mfma<128, 128, 128, 1, false, true, true>(g, i8, stream); break;
+                case 8: if (dma_ok(d, 256, 256)) return launch_mfma<256, 256, 128, 1, false, true, true>(g, i8, stream); break;
+                case 9: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 1, false, true, true>(g, i8, stream); break;
+                case 10: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 1, false, true, true>(g, i8, stream); break;
+                default: break;
+            }
+            return IBERT_ERR_NOT_IMPLEMENTED;
+        }
+        switch (cfg) {
             case 0: return launch_mfma<256, 192, 128, 2>(g, i8, stream);
             case 1: return launch_mfma<128, 128, 128, 2>(g, i8, stream);
             case 2: return launch_mfma<128, 128, 64, 2>(g, i8, stream);
@@ -868,6 +912,28 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
     return IBERT_OK;
 }
 
+// MatMul + GELU.  One kernel when a direct-to-LDS tile fits the problem; otherwise the MatMul writes its INT32
+// result (clamped to +-q_max) to `scratch` and the element-wise GELU kernel follows, which needs dense outputs.
+int launch_gemm_gelu(const ibert_gemm_desc& d0, const int8_t* A, const int8_t* W, const int32_t* bias,
+                     const int32_t* mult, const int32_t* shift, const ibert_gelu_params& gelu, int8_t* C,
+                     int32_t* scratch, hipStream_t stream)
+{
+    ibert_gemm_desc d = d0;
+    d.out_dtype = IBERT_I8;
+    d.out_clamp = gelu.q_max;
+    int rc = launch_gemm(d, A, W, bias, mult, shift, nullptr, C, stream, &gelu);
+    if (rc != IBERT_ERR_NOT_IMPLEMENTED) return rc;
+    const int64_t nb = (int64_t)d.batch_outer * d.batch_inner;
+    const bool dense = d.ldc == d.N && (d.batch_inner == 1 || d.strideC_inner == (int64_t)d.M * d.N) &&
+                       (d.batch_outer == 1 || d.strideC_outer == (int64_t)d.batch_inner * d.M * d.N);
+    if (!dense) return IBERT_ERR_NOT_IMPLEMENTED;
+    if (!scratch) return IBERT_ERR_WORKSPACE;
+    d.out_dtype = IBERT_I32;
+    rc = launch_gemm(d, A, W, bias, mult, shift, nullptr, scratch, stream);
+    if (rc) return rc;
+    return launch_gelu(scratch, C, nb * d.M * d.N, gelu, stream);
+}
+
 }  // namespace ibert
 
 #ifdef IBERT_KERNEL_TIMING
@@ -888,4 +954,19 @@ extern "C" int ibert_gemm_i8_requant(const ibert_gemm_desc* desc, const int8_t* 
     const int rc = ibert::check_gemm(*desc, A, W, mult, shift, residual, C);
     if (rc) return rc;
     return ibert::launch_gemm(*desc, A, W, bias, mult, shift, residual, C, (hipStream_t)stream);
+}
+
+extern "C" int ibert_gemm_i8_gelu(const ibert_gemm_desc* desc, const int8_t* A, const int8_t* W, const int32_t* bias,
+                                  const int32_t* mult, const int32_t* shift, const ibert_gelu_params* gelu,
+                                  int8_t* C, int32_t* scratch, void* stream)
+{
+    if (!desc || !gelu) return IBERT_ERR_NULL;
+    int rc = ibert::check_gelu(*gelu);
+    if (rc) return rc;
+    ibert_gemm_desc d = *desc;
+    d.out_dtype = IBERT_I32;                       // range checks of the MatMul part: an INT32 result clamped to q_max
+    d.out_clamp = gelu->q_max;
+    rc = ibert::check_gemm(d, A, W, mult, shift, nullptr, C);
+    if (rc) return rc;
+    return ibert::launch_gemm_gelu(*desc, A, W, bias, mult, shift, *gelu, C, scratch, (hipStream_t)stream);
 }

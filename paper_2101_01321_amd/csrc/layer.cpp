@@ -43,6 +43,9 @@ static double gemm_bytes(double M, double N, double K, double batch, double out_
            (w_shared ? N * K : 0.0) + 12.0 * N;
 }
 
+// Fusions the layer applies (bit 0: GELU inside the FFN up-projection).  Results do not depend on it.
+static int32_t g_fusion = 1;
+
 static int layout(int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn,
                   ibert_layer_workspace_layout* o)
 {
@@ -144,15 +147,33 @@ static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, c
     std::memset(&d, 0, sizeof d);
     d.M = (int32_t)T; d.N = (int32_t)F; d.K = (int32_t)H; d.batch_outer = d.batch_inner = 1;
     d.lda = H; d.ldw = H; d.ldc = F; d.per_channel = 1; d.out_dtype = IBERT_I32; d.out_clamp = q.gelu.q_max;
-    prof_before(stream);
-    RUN_GEMM(h1, w.w_1, w.b_1, w.m_1, w.s_1, nullptr, f1);
-    prof_after(stream, 7, 2.0 * T * F * H, gemm_bytes(T, F, H, 1, 4, false, true));
+    bool fused78 = false;
+    if (g_fusion & 1) {
+        // 7+8 in one kernel when a tile fits: f1 is then never written
+        rc = check_gemm(d, h1, w.w_1, w.m_1, w.s_1, nullptr, g);
+        if (rc) return rc;
+        prof_before(stream);
+        ibert_gemm_desc df = d;
+        df.out_dtype = IBERT_I8;                                   // what the kernel stores; the clamp stays q_max
+        rc = launch_gemm(df, h1, w.w_1, w.b_1, w.m_1, w.s_1, nullptr, g, stream, &q.gelu);
+        if (rc == IBERT_OK) {
+            fused78 = true;
+            prof_after(stream, 7, 2.0 * T * F * H, gemm_bytes(T, F, H, 1, 1, false, true));
+        } else if (rc != IBERT_ERR_NOT_IMPLEMENTED) {
+            return rc;
+        }
+    }
+    if (!fused78) {
+        prof_before(stream);
+        RUN_GEMM(h1, w.w_1, w.b_1, w.m_1, w.s_1, nullptr, f1);
+        prof_after(stream, 7, 2.0 * T * F * H, gemm_bytes(T, F, H, 1, 4, false, true));
 
-    // 8: GELU
-    prof_before(stream);
-    rc = launch_gelu(f1, g, T * F, q.gelu, stream);
-    if (rc) return rc;
-    prof_after(stream, 8, 0.0, 5.0 * T * F);
+        // 8: GELU
+        prof_before(stream);
+        rc = launch_gelu(f1, g, T * F, q.gelu, stream);
+        if (rc) return rc;
+        prof_after(stream, 8, 0.0, 5.0 * T * F);
+    }
 
     // 9: FFN down-projection + residual h1
     std::memset(&d, 0, sizeof d);
@@ -194,6 +215,13 @@ static int check_layer(const ibert_layer_weights& w, const ibert_layer_quant& q,
 }  // namespace ibert
 
 extern "C" {
+
+int ibert_set_fusion(int32_t flags)
+{
+    const int32_t old = ibert::g_fusion;
+    if (flags >= 0) ibert::g_fusion = flags & 1;
+    return old;
+}
 
 int ibert_profile_begin(int32_t capacity)
 {

@@ -45,6 +45,24 @@ def gemm(desc_kwargs, A, W, bias=None, mult=None, shift=None, residual=None, out
     return tC[offsets.get("C", 0):].cpu().numpy()
 
 
+def gemm_gelu(desc_kwargs, A, W, bias, mult, shift, gelu_params, out_elems, with_scratch=True):
+    """Fused MatMul + GELU call (dense INT8 output).  Returns (output, scratch-or-None) as numpy."""
+    d = B.GemmDesc()
+    for k, v in desc_kwargs.items():
+        setattr(d, k, B.Dyadic(*v) if k in ("requant", "residual_dy") else v)
+    tA, tW = to_dev(A, np.int8).reshape(-1), to_dev(W, np.int8).reshape(-1)
+    tb = None if bias is None else to_dev(bias, np.int32)
+    tm = None if mult is None else to_dev(mult, np.int32)
+    ts = None if shift is None else to_dev(shift, np.int32)
+    tC = torch.full((out_elems + 16,), 77, dtype=torch.int8, device=DEV)
+    tS = torch.full((out_elems,), -5, dtype=torch.int32, device=DEV) if with_scratch else None
+    B.ibert_gemm_i8_gelu(d, tA, tW, tb, tm, ts, gelu_params, tC, tS)
+    torch.cuda.synchronize()
+    out = tC.cpu().numpy()
+    assert np.all(out[out_elems:] == 77), "wrote past the end"
+    return out[:out_elems], (None if tS is None else tS.cpu().numpy())
+
+
 def softmax(x, params, cols=None, ldx=None, ldy=None, x_off=0, y_off=0):
     x = np.ascontiguousarray(x, np.int32)
     rows = x.shape[0]

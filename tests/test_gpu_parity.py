@@ -255,6 +255,38 @@ def test_gemm_direct_to_lds_tiles(G, cfg, M, N, K):
         B.lib().ibert_gemm_config_override(-1)
 
 
+@pytest.mark.parametrize("cfg,M,N,K", [(-1, 4096, 3072, 768), (6, 512, 384, 256), (7, 256, 384, 128), (8, 256, 512, 384),
+                                       (9, 384, 288, 256), (10, 512, 256, 128), (-1, 100, 72, 48), (-1, 130, 64, 128)])
+@pytest.mark.parametrize("S_in,S_out", [(2.0 ** -7, 8.0 / 127), (0.011, 0.02)])
+def test_gemm_gelu_equals_matmul_then_gelu(G, cfg, M, N, K, S_in, S_out):
+    # steps 7+8 in one call: every tile configuration that carries the GELU epilogue, the built-in choice at the
+    # full Base shape, and two shapes that fall back to the two-kernel route through the scratch buffer
+    from paper_2101_01321_amd import binding as B
+    if (M, S_in) == (4096, 0.011):
+        pytest.skip("full shape is run once")
+    gp, op = B.ibert_gelu_params_from_scale(S_in, S_out), P.gelu_params(S_in, S_out)
+    A, W, sw, b = synth.gemm_operands(M, N, K, layer=M + K)
+    mult, shift = B.ibert_channel_dyadics_from_scales(0.03, sw, S_in)     # accumulators land on the GELU input scale
+    kw = dict(M=M, N=N, K=K, batch_outer=1, batch_inner=1, lda=K, ldw=K, ldc=N, per_channel=1, out_dtype=I8, out_clamp=5)
+    spec = GemmSpec(M, N, K, per_channel=1, dy=(1, 0), out_dtype=I32, out_clamp=gp.q_max)
+    f = oracle.gemm_requant(spec, A, W, b, mult, shift, None)
+    want = oracle.gelu(f.reshape(-1), op)
+    assert want.min() < 0 < want.max() and len(np.unique(want)) > 20     # not a degenerate case
+    B.lib().ibert_gemm_config_override(cfg)
+    try:
+        G.say("gemm+gelu cfg=%d M=%d N=%d K=%d S_in=%g" % (cfg, M, N, K, S_in))
+        got, scratch = G.gemm_gelu(kw, A, W, b, mult, shift, gp, M * N)
+    finally:
+        B.lib().ibert_gemm_config_override(-1)
+    _eq(got, want, "gemm+gelu")
+    one_kernel = M % 128 == 0 and K % 128 == 0
+    assert np.all(scratch == -5) == one_kernel                              # scratch untouched iff GELU ran in the epilogue
+    if not one_kernel:
+        _eq(scratch, f.reshape(-1), "scratch holds the MatMul result")
+        with pytest.raises(B.IbertError):
+            G.gemm_gelu(kw, A, W, b, mult, shift, gp, M * N, with_scratch=False)
+
+
 def test_gemm_base_shapes_full(G):
     # the four projection GEMMs of RoBERTa-Base at batch 32 (T = 4096), full outputs
     for M, N, K, od, res in [(4096, 2304, 768, I8, False), (4096, 768, 768, I32, True), (4096, 3072, 768, I32, False),
@@ -264,7 +296,17 @@ def test_gemm_base_shapes_full(G):
 
 
 # ------------------------------------------------------------------------------------------- layer / encoder
-def _layer_case(G, cfg, n_layers=1):
+def _layer_case(G, cfg, n_layers=1, fusion=0):
+    import torch
+    from paper_2101_01321_amd import binding as B
+    B.ibert_set_fusion(fusion)
+    try:
+        return _layer_case_body(G, cfg, n_layers, fusion)
+    finally:
+        B.ibert_set_fusion(1)
+
+
+def _layer_case_body(G, cfg, n_layers, fusion):
     import torch
     x_q, S_x, _ = synth.input_activations(cfg)
     model = G.DeviceModel(cfg, S_x, n_layers=n_layers)
@@ -279,6 +321,8 @@ def _layer_case(G, cfg, n_layers=1):
         torch.cuda.synchronize()
         got_inter = model.intermediates()
         for k in ("qkv", "scores", "probs", "ctx", "r1", "h1", "f1", "g", "r2"):
+            if k == "f1" and (fusion & 1):
+                continue                                     # not materialised when GELU runs in the MatMul epilogue
             _eq(got_inter[k], inter[k], "%s layer %d %s" % (cfg.name, l, k))
         _eq(ty.cpu().numpy(), want, "%s layer %d output" % (cfg.name, l))
         cur, tx = want, ty
@@ -287,6 +331,14 @@ def _layer_case(G, cfg, n_layers=1):
 
 def test_layer_tiny_every_intermediate(G):
     _layer_case(G, synth.CONFIGS["tiny"])
+    _layer_case(G, synth.CONFIGS["tiny"], fusion=1)
+
+
+def test_layer_whole_tile_shape_fused_and_unfused(G):
+    # hidden/ffn/tokens that fit the whole-tile MatMul configurations, so that fusion=1 really runs the fused kernel
+    cfg = synth.EncoderConfig("tiles", 256, 4, 1024, 128, 16, 1)
+    _layer_case(G, cfg, fusion=0)
+    _layer_case(G, cfg, fusion=1)
 
 
 def test_layer_ragged_every_intermediate(G):
