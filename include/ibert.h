@@ -280,9 +280,30 @@ typedef struct {
 int ibert_layer_quant_from_scales(const ibert_layer_scales* scales, int32_t seq, int32_t head_dim,
                                   ibert_layer_quant* out);
 
-/* Kernel fusions inside ibert_encoder_layer_i / ibert_encoder_i.  Bit 0: steps 7 and 8 (FFN up-projection and
- * GELU) run as one kernel where ibert_gemm_i8_gelu can do so; the workspace region f1 is then left untouched.
- * Default: 1.  flags >= 0 sets the mask (unknown bits are dropped), a negative value only queries.  Returns the
+/* ------------------------------------------------------------------------------------------------
+ * ibert_attention_i -- the self-attention core of the layer (Fig. 1 right; Sec. 4.1; Alg. 3), steps 2-4 of
+ * ibert_encoder_layer_i, bit-identical to
+ *     scores = ibert_gemm_i8_requant(Q_h, K_h; scores_dy, INT32)          per (batch, head): [seq, seq]
+ *     probs  = ibert_softmax_i(scores; softmax)                            INT8
+ *     ctx    = ibert_gemm_i8_requant(probs, V_h as [K,N]; ctx_dy, INT8, clamp 127), written into [T, hidden]
+ * qkv: device int8 [batch*seq, 3*hidden] (Q | K | V, the heads of each side by side); ctx: device int8
+ * [batch*seq, hidden].  softmax->out_dtype must be IBERT_I8.
+ * With seq = 128 and hidden/heads = 64 (qkv 16-byte aligned, ctx 4-byte aligned) the three steps run as one kernel
+ * and scores/probs are never stored -- unless bit 1 of the fusion mask is clear.  Any other shape takes the
+ * three-kernel route through `scratch` (device, 256-byte aligned, ibert_attention_scratch_bytes() bytes;
+ * IBERT_ERR_WORKSPACE if it is NULL, small or misaligned).  scratch may always be passed.
+ * ---------------------------------------------------------------------------------------------- */
+size_t ibert_attention_scratch_bytes(int32_t batch, int32_t seq, int32_t heads);
+int ibert_attention_i(const int8_t* qkv, int8_t* ctx, int32_t batch, int32_t seq, int32_t hidden, int32_t heads,
+                      const ibert_dyadic* scores_dy, const ibert_softmax_params* softmax, const ibert_dyadic* ctx_dy,
+                      void* scratch, size_t scratch_bytes, void* stream);
+
+/* Kernel fusions inside ibert_encoder_layer_i / ibert_encoder_i (and ibert_attention_i).
+ *   bit 0: steps 7 and 8 (FFN up-projection and GELU) run as one kernel where ibert_gemm_i8_gelu can do so; the
+ *          workspace region f1 is then left untouched;
+ *   bit 1: steps 2, 3 and 4 run as one kernel where ibert_attention_i can do so; the workspace regions scores
+ *          and probs are then left untouched (profile records: one, numbered 2).
+ * Default: 3.  flags >= 0 sets the mask (unknown bits are dropped), a negative value only queries.  Returns the
  * previous mask.  Outputs do not depend on the mask.  Not thread-safe. */
 int ibert_set_fusion(int32_t flags);
 

@@ -90,6 +90,9 @@ SIGNATURES = {
     "ibert_gemm_config_override": (C.c_int, [C.c_int32]),
     "ibert_gemm_i8_gelu": (C.c_int, [C.POINTER(GemmDesc)] + [_P] * 5 + [C.POINTER(GeluParams)] + [_P] * 3),
     "ibert_set_fusion": (C.c_int, [C.c_int32]),
+    "ibert_attention_scratch_bytes": (C.c_size_t, [C.c_int32] * 3),
+    "ibert_attention_i": (C.c_int, [_P, _P] + [C.c_int32] * 4 + [C.POINTER(Dyadic), C.POINTER(SoftmaxParams),
+                                                                 C.POINTER(Dyadic), _P, C.c_size_t, _P]),
     "ibert_softmax_i": (C.c_int, [_P, _P, C.c_int64, C.c_int32, C.c_int64, C.c_int64, C.POINTER(SoftmaxParams), _P]),
     "ibert_gelu_i": (C.c_int, [_P, _P, C.c_int64, C.POINTER(GeluParams), _P]),
     "ibert_layernorm_i": (C.c_int, [_P, _P, C.c_int64, C.c_int32, C.c_int64, C.c_int64, _P, _P, C.c_int32, _P]),
@@ -208,6 +211,17 @@ def ibert_gemm_i8_requant(desc: GemmDesc, A, W, bias, mult, shift, residual, Cou
 def ibert_gemm_i8_gelu(desc: GemmDesc, A, W, bias, mult, shift, gelu: GeluParams, Cout, scratch, stream=None):
     _chk(lib().ibert_gemm_i8_gelu(C.byref(desc), _dp(A), _dp(W), _dp(bias), _dp(mult), _dp(shift), C.byref(gelu),
                                   _dp(Cout), _dp(scratch), _stream(stream)), "ibert_gemm_i8_gelu")
+
+
+def ibert_attention_scratch_bytes(batch: int, seq: int, heads: int) -> int:
+    return int(lib().ibert_attention_scratch_bytes(batch, seq, heads))
+
+
+def ibert_attention_i(qkv, ctx, batch, seq, hidden, heads, scores_dy: Dyadic, softmax: SoftmaxParams, ctx_dy: Dyadic,
+                      scratch=None, stream=None):
+    nbytes = 0 if scratch is None else scratch.numel() * scratch.element_size()
+    _chk(lib().ibert_attention_i(_dp(qkv), _dp(ctx), batch, seq, hidden, heads, C.byref(scores_dy), C.byref(softmax),
+                                 C.byref(ctx_dy), _dp(scratch), nbytes, _stream(stream)), "ibert_attention_i")
 
 
 def ibert_set_fusion(flags: int) -> int:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libibert.so")
-SOURCES = ["host.cpp", "layer.cpp", "gelu.hip", "softmax.hip", "layernorm.hip", "gemm.hip"]
+SOURCES = ["host.cpp", "layer.cpp", "gelu.hip", "softmax.hip", "layernorm.hip", "attention.hip", "gemm.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-FP32 instruction forms are switched off for all device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

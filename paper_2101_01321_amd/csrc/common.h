@@ -123,6 +123,9 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
 int launch_gemm_gelu(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, const int32_t* bias,
                      const int32_t* mult, const int32_t* shift, const ibert_gelu_params& gelu, int8_t* C,
                      int32_t* scratch, hipStream_t stream);
+bool attention_fused_ok(const int8_t* qkv, const int8_t* ctx, int32_t seq, int32_t hidden, int32_t heads);
+int launch_attention(const int8_t* qkv, int8_t* ctx, int32_t batch, int32_t seq, int32_t hidden, int32_t heads,
+                     ibert_dyadic scores_dy, const ibert_softmax_params& sp, ibert_dyadic ctx_dy, hipStream_t stream);
 int launch_softmax(const int32_t* x, void* y, int64_t rows, int32_t cols, int64_t ldx, int64_t ldy,
                    const ibert_softmax_params& p, hipStream_t stream);
 int launch_gelu(const int32_t* x, int8_t* y, int64_t n, const ibert_gelu_params& p, hipStream_t stream);

@@ -43,8 +43,9 @@ static double gemm_bytes(double M, double N, double K, double batch, double out_
            (w_shared ? N * K : 0.0) + 12.0 * N;
 }
 
-// Fusions the layer applies (bit 0: GELU inside the FFN up-projection).  Results do not depend on it.
-static int32_t g_fusion = 1;
+// Fusions the layer applies (bit 0: GELU inside the FFN up-projection; bit 1: scores, Softmax and context in one
+// kernel).  Results do not depend on it.
+static int32_t g_fusion = 3;
 
 static int layout(int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn,
                   ibert_layer_workspace_layout* o)
@@ -63,6 +64,73 @@ static int layout(int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int
     o->r2 = p;     p += align_up(T * H * 4);
     o->total = p;
     return IBERT_OK;
+}
+
+// Steps 2-4 (scores, Softmax, context) as three kernels through the INT32 scores and INT8 probabilities buffers.
+static int run_attention_unfused(const int8_t* qkv, int32_t* scores, int8_t* probs, int8_t* ctx, int64_t B, int64_t L,
+                                 int64_t H, int64_t nh, const ibert_dyadic& scores_dy, const ibert_softmax_params& softmax,
+                                 const ibert_dyadic& ctx_dy, hipStream_t stream)
+{
+    const int64_t dh = H / nh;
+    ibert_gemm_desc d;
+    int rc;
+#define RUN_GEMM(A_, W_, b_, m_, s_, R_, C_)                                             \
+    do {                                                                                 \
+        rc = check_gemm(d, A_, W_, m_, s_, R_, C_);                                      \
+        if (rc) return rc;                                                               \
+        rc = launch_gemm(d, A_, W_, b_, m_, s_, R_, C_, stream);                         \
+        if (rc) return rc;                                                               \
+    } while (0)
+    // 2: attention scores Q_h K_h^T per (batch, head); 1/sqrt(d) is inside scores_dy
+    std::memset(&d, 0, sizeof d);
+    d.M = (int32_t)L; d.N = (int32_t)L; d.K = (int32_t)dh; d.batch_outer = (int32_t)B; d.batch_inner = (int32_t)nh;
+    d.lda = 3 * H; d.ldw = 3 * H; d.ldc = L;
+    d.strideA_outer = L * 3 * H; d.strideA_inner = dh;
+    d.strideW_outer = L * 3 * H; d.strideW_inner = dh;
+    d.strideC_outer = nh * L * L; d.strideC_inner = L * L;
+    d.per_channel = 0; d.requant = scores_dy; d.out_dtype = IBERT_I32; d.out_clamp = 2147483647;
+    prof_before(stream);
+    RUN_GEMM(qkv, qkv + H, nullptr, nullptr, nullptr, nullptr, scores);
+    prof_after(stream, 2, 2.0 * B * nh * L * L * dh, gemm_bytes(L, L, dh, B * nh, 4, false, false));
+
+    // 3: softmax over the key axis
+    prof_before(stream);
+    rc = launch_softmax(scores, probs, B * nh * L, (int32_t)L, L, L, softmax, stream);
+    if (rc) return rc;
+    prof_after(stream, 3, 0.0, 5.0 * B * nh * L * L);
+
+    // 4: context P V_h, scattered back into [T, H]
+    std::memset(&d, 0, sizeof d);
+    d.M = (int32_t)L; d.N = (int32_t)dh; d.K = (int32_t)L; d.batch_outer = (int32_t)B; d.batch_inner = (int32_t)nh;
+    d.lda = L; d.ldw = 3 * H; d.ldc = H; d.trans_w = 1;
+    d.strideA_outer = nh * L * L; d.strideA_inner = L * L;
+    d.strideW_outer = L * 3 * H; d.strideW_inner = dh;
+    d.strideC_outer = L * H; d.strideC_inner = dh;
+    d.per_channel = 0; d.requant = ctx_dy; d.out_dtype = IBERT_I8; d.out_clamp = 127;
+    prof_before(stream);
+    RUN_GEMM(probs, qkv + 2 * H, nullptr, nullptr, nullptr, nullptr, ctx);
+    prof_after(stream, 4, 2.0 * B * nh * L * dh * L, gemm_bytes(L, dh, L, B * nh, 1, false, false));
+
+    return IBERT_OK;
+#undef RUN_GEMM
+}
+
+// Steps 2-4: one kernel where the shape allows it (and `fused` asks for it), else the three-kernel route.
+static int run_attention(const int8_t* qkv, int32_t* scores, int8_t* probs, int8_t* ctx, int64_t B, int64_t L, int64_t H,
+                         int64_t nh, const ibert_dyadic& scores_dy, const ibert_softmax_params& softmax,
+                         const ibert_dyadic& ctx_dy, bool fused, hipStream_t stream)
+{
+    if (fused && attention_fused_ok(qkv, ctx, (int32_t)L, (int32_t)H, (int32_t)nh)) {
+        prof_before(stream);
+        const int rc = launch_attention(qkv, ctx, (int32_t)B, (int32_t)L, (int32_t)H, (int32_t)nh, scores_dy, softmax,
+                                        ctx_dy, stream);
+        if (rc) return rc;
+        // both MatMuls; bytes: Q, K, V read once, the context written once
+        prof_after(stream, 2, 4.0 * B * nh * L * L * (H / nh), 4.0 * B * L * H);
+        return IBERT_OK;
+    }
+    if (!scores || !probs) return IBERT_ERR_WORKSPACE;
+    return run_attention_unfused(qkv, scores, probs, ctx, B, L, H, nh, scores_dy, softmax, ctx_dy, stream);
 }
 
 static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, const int8_t* x, int8_t* y,
@@ -98,35 +166,9 @@ static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, c
     RUN_GEMM(x, w.w_qkv, w.b_qkv, w.m_qkv, w.s_qkv, nullptr, qkv);
     prof_after(stream, 1, 2.0 * T * 3 * H * H, gemm_bytes(T, 3 * H, H, 1, 1, false, true));
 
-    // 2: attention scores Q_h K_h^T per (batch, head); 1/sqrt(d) is inside scores_dy
-    std::memset(&d, 0, sizeof d);
-    d.M = (int32_t)L; d.N = (int32_t)L; d.K = (int32_t)dh; d.batch_outer = (int32_t)B; d.batch_inner = (int32_t)nh;
-    d.lda = 3 * H; d.ldw = 3 * H; d.ldc = L;
-    d.strideA_outer = L * 3 * H; d.strideA_inner = dh;
-    d.strideW_outer = L * 3 * H; d.strideW_inner = dh;
-    d.strideC_outer = nh * L * L; d.strideC_inner = L * L;
-    d.per_channel = 0; d.requant = q.scores_dy; d.out_dtype = IBERT_I32; d.out_clamp = 2147483647;
-    prof_before(stream);
-    RUN_GEMM(qkv, qkv + H, nullptr, nullptr, nullptr, nullptr, scores);
-    prof_after(stream, 2, 2.0 * B * nh * L * L * dh, gemm_bytes(L, L, dh, B * nh, 4, false, false));
-
-    // 3: softmax over the key axis
-    prof_before(stream);
-    rc = launch_softmax(scores, probs, B * nh * L, (int32_t)L, L, L, q.softmax, stream);
+    // 2-4: attention scores, Softmax, context
+    rc = run_attention(qkv, scores, probs, ctx, B, L, H, nh, q.scores_dy, q.softmax, q.ctx_dy, (g_fusion & 2) != 0, stream);
     if (rc) return rc;
-    prof_after(stream, 3, 0.0, 5.0 * B * nh * L * L);
-
-    // 4: context P V_h, scattered back into [T, H]
-    std::memset(&d, 0, sizeof d);
-    d.M = (int32_t)L; d.N = (int32_t)dh; d.K = (int32_t)L; d.batch_outer = (int32_t)B; d.batch_inner = (int32_t)nh;
-    d.lda = L; d.ldw = 3 * H; d.ldc = H; d.trans_w = 1;
-    d.strideA_outer = nh * L * L; d.strideA_inner = L * L;
-    d.strideW_outer = L * 3 * H; d.strideW_inner = dh;
-    d.strideC_outer = L * H; d.strideC_inner = dh;
-    d.per_channel = 0; d.requant = q.ctx_dy; d.out_dtype = IBERT_I8; d.out_clamp = 127;
-    prof_before(stream);
-    RUN_GEMM(probs, qkv + 2 * H, nullptr, nullptr, nullptr, nullptr, ctx);
-    prof_after(stream, 4, 2.0 * B * nh * L * dh * L, gemm_bytes(L, dh, L, B * nh, 1, false, false));
 
     // 5: output projection + residual x, INT32 at the LayerNorm input scale
     std::memset(&d, 0, sizeof d);
@@ -219,8 +261,39 @@ extern "C" {
 int ibert_set_fusion(int32_t flags)
 {
     const int32_t old = ibert::g_fusion;
-    if (flags >= 0) ibert::g_fusion = flags & 1;
+    if (flags >= 0) ibert::g_fusion = flags & 3;
     return old;
+}
+
+size_t ibert_attention_scratch_bytes(int32_t batch, int32_t seq, int32_t heads)
+{
+    if (batch < 0 || seq < 0 || heads < 0) return 0;
+    const size_t n = (size_t)batch * heads * seq * seq;
+    return ibert::align_up(n * 4) + ibert::align_up(n);
+}
+
+int ibert_attention_i(const int8_t* qkv, int8_t* ctx, int32_t batch, int32_t seq, int32_t hidden, int32_t heads,
+                      const ibert_dyadic* scores_dy, const ibert_softmax_params* softmax, const ibert_dyadic* ctx_dy,
+                      void* scratch, size_t scratch_bytes, void* stream)
+{
+    using namespace ibert;
+    if (!scores_dy || !softmax || !ctx_dy) return IBERT_ERR_NULL;
+    if (batch < 0 || seq < 1 || hidden < 1 || heads < 1 || hidden % heads) return IBERT_ERR_SHAPE;
+    if (!dyadic_ok(*scores_dy) || !dyadic_ok(*ctx_dy) || softmax->out_dtype != IBERT_I8) return IBERT_ERR_PARAM_RANGE;
+    const int rc = check_softmax(*softmax, seq);
+    if (rc) return rc;
+    if (batch == 0) return IBERT_OK;
+    if (!qkv || !ctx) return IBERT_ERR_NULL;
+    int32_t* scores = nullptr;
+    int8_t* probs = nullptr;
+    if (scratch) {
+        if (scratch_bytes < ibert_attention_scratch_bytes(batch, seq, heads) || ((uintptr_t)scratch & 255)) return IBERT_ERR_WORKSPACE;
+        const size_t n = (size_t)batch * heads * seq * seq;
+        scores = static_cast<int32_t*>(scratch);
+        probs = static_cast<int8_t*>(scratch) + align_up(n * 4);
+    }
+    return run_attention(qkv, scores, probs, ctx, batch, seq, hidden, heads, *scores_dy, *softmax, *ctx_dy,
+                         (g_fusion & 2) != 0, (hipStream_t)stream);
 }
 
 int ibert_profile_begin(int32_t capacity)

@@ -6,6 +6,7 @@
 // rows are short (cols <= 128 -> 4 rows per wave), which keeps all 64 lanes loading.
 // Long rows (cols > 64*4*NCH_MAX) fall back to one workgroup per row with three passes.
 #include "common.h"
+#include "softmax_math.h"
 
 namespace ibert {
 
@@ -15,46 +16,8 @@ struct SoftmaxArgs {
     int64_t rows;
     int32_t cols;
     int64_t ldx, ldy;
-    uint32_t q_ln2, q_b, q_c;
-    uint32_t magic;      // floor(2^32 / q_ln2) + 1  (0 stands for 2^32, i.e. q_ln2 == 1)
-    uint32_t d_cap;      // 31 * q_ln2: differences at or beyond it contribute e = 0
-    uint32_t magic27;    // floor(2^27 / q_ln2) + 1, used by the 24-bit path
-    int32_t k;           // output fractional bits
+    SoftmaxConst c;
 };
-
-// e = I-Exp(-(d)) for a non-negative difference d = max - q (Alg. 3):
-//   z = floor(d / q_ln2), r = d - z q_ln2, e = ((q_b - r)^2 + q_c) >> z.
-// d is first capped at 31*q_ln2 (z = 31 already shifts every 31-bit polynomial value to zero).
-// floor(d/q_ln2) uses a reciprocal multiply: est = mulhi(d, magic) is z or z+1; one fix-up step.
-__device__ __forceinline__ uint32_t iexp_from_diff(uint32_t d, const SoftmaxArgs& a)
-{
-    d = d < a.d_cap ? d : a.d_cap;
-    uint32_t z = a.magic ? __umulhi(d, a.magic) : d;
-    int32_t r = (int32_t)(d - z * a.q_ln2);
-    if (r < 0) { r += (int32_t)a.q_ln2; z -= 1; }
-    const uint32_t v = a.q_b - (uint32_t)r;            // may be "negative": squared below, mod 2^32 is exact
-    const uint32_t poly = v * v + a.q_c;               // I-Poly, Alg. 1 (true value < 2^31)
-    return poly >> z;                                  // z <= 31
-}
-
-// The same value with full-rate 24-bit multiplies, valid when 8 < q_ln2 < 2080 and q_b^2 + q_c < 2^24
-// (host-checked): d <= 31 q_ln2 < 2^16, so with M = floor(2^27/q_ln2) + 1 the product d*M stays below 2^32 and
-// floor(d*M / 2^27) = floor(d / q_ln2) exactly (the excess d/2^27 is below 1/q_ln2 because 31 q_ln2^2 < 2^27);
-// q_b - r = q_b - d + z q_ln2 is one multiply-add; (q_b - r)^2 + q_c another.
-__device__ __forceinline__ uint32_t iexp_from_diff_fast(uint32_t d, const SoftmaxArgs& a)
-{
-    d = d < a.d_cap ? d : a.d_cap;
-    const uint32_t z = umul24(d, a.magic27) >> 27;
-    const uint32_t v = umad24(z, a.q_ln2, a.q_b - d);           // q_b - r, in (0, q_b]
-    const uint32_t poly = umad24(v, v, a.q_c);                  // I-Poly, Alg. 1
-    return poly >> z;
-}
-
-// y = min(cap, (e*Fz + 2^(30-k)) >> (31-k)),  Fz = floor(2^31 / sum)
-__device__ __forceinline__ uint32_t normalise(uint32_t e, uint32_t Fz, int32_t k)
-{
-    return (e * Fz + (1u << (30 - k))) >> (31 - k);
-}
 
 template <int LPR>
 __device__ __forceinline__ int32_t group_max(int32_t v)
@@ -108,7 +71,7 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_rows_kernel(SoftmaxArgs a)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const uint32_t d = (uint32_t)mx - (uint32_t)q[c][e];
-            const uint32_t v = FAST ? iexp_from_diff_fast(d, a) : iexp_from_diff(d, a);
+            const uint32_t v = FAST ? iexp_from_diff_fast(d, a.c) : iexp_from_diff(d, a.c);
             ex[c][e] = (col + e < a.cols) ? v : 0u;
             sum += ex[c][e];
         }
@@ -124,7 +87,7 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_rows_kernel(SoftmaxArgs a)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             // FAST: e < 2^24 and Fz <= 2^23 (sum >= q_b^2 + q_c >= 2^8), so the 24-bit multiply is exact
-            o[e] = FAST ? umad24(ex[c][e], Fz, 1u << (30 - a.k)) >> (31 - a.k) : normalise(ex[c][e], Fz, a.k);
+            o[e] = FAST ? umad24(ex[c][e], Fz, 1u << (30 - a.c.k)) >> (31 - a.c.k) : normalise(ex[c][e], Fz, a.c.k);
             if (OUT_I8) o[e] = o[e] > 127u ? 127u : o[e];
         }
         if (OUT_I8) {
@@ -169,7 +132,7 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_long_kernel(SoftmaxArgs a)
     for (int w = 1; w < SM_THREADS / 64; ++w) mx = s_max[w] > mx ? s_max[w] : mx;
 
     uint32_t sum = 0;
-    for (int j = threadIdx.x; j < a.cols; j += SM_THREADS) sum += iexp_from_diff((uint32_t)mx - (uint32_t)xr[j], a);
+    for (int j = threadIdx.x; j < a.cols; j += SM_THREADS) sum += iexp_from_diff((uint32_t)mx - (uint32_t)xr[j], a.c);
     sum = group_sum<64>(sum);
     if (lane == 0) s_sum[wave] = sum;
     __syncthreads();
@@ -179,7 +142,7 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_long_kernel(SoftmaxArgs a)
     const uint32_t Fz = 0x80000000u / sum;
 
     for (int j = threadIdx.x; j < a.cols; j += SM_THREADS) {
-        uint32_t o = normalise(iexp_from_diff((uint32_t)mx - (uint32_t)xr[j], a), Fz, a.k);
+        uint32_t o = normalise(iexp_from_diff((uint32_t)mx - (uint32_t)xr[j], a.c), Fz, a.c.k);
         if (OUT_I8) {
             o = o > 127u ? 127u : o;
             (reinterpret_cast<int8_t*>(a.y) + row * a.ldy)[j] = (int8_t)o;
@@ -230,14 +193,9 @@ int launch_softmax(const int32_t* x, void* y, int64_t rows, int32_t cols, int64_
     if (rows == 0) return IBERT_OK;
     SoftmaxArgs a;
     a.x = x; a.y = y; a.rows = rows; a.cols = cols; a.ldx = ldx; a.ldy = ldy;
-    a.q_ln2 = (uint32_t)p.q_ln2; a.q_b = (uint32_t)p.q_b; a.q_c = (uint32_t)p.q_c;
-    a.magic = p.q_ln2 == 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) / (uint32_t)p.q_ln2) + 1);
-    a.d_cap = 31u * (uint32_t)p.q_ln2;                 // q_ln2 <= q_b < 2^16 by the preconditions
-    a.magic27 = (uint32_t)((1u << 27) / (uint32_t)p.q_ln2) + 1u;
-    a.k = p.out_frac_bits;
+    a.c = softmax_const(p);
     const bool i8 = p.out_dtype == IBERT_I8;
-    const int64_t poly_max = (int64_t)p.q_b * p.q_b + p.q_c;
-    const bool fast = p.q_ln2 > 8 && p.q_ln2 < 2080 && poly_max >= 256 && poly_max < (1 << 24);
+    const bool fast = softmax_fast_ok(p);
     const bool al = aligned(x, 16) && ldx % 4 == 0 && (i8 ? (aligned(y, 4) && ldy % 4 == 0) : (aligned(y, 16) && ldy % 4 == 0));
     if (rows > 0x7fffffffLL) return IBERT_ERR_SHAPE;
 

@@ -63,6 +63,20 @@ def gemm_gelu(desc_kwargs, A, W, bias, mult, shift, gelu_params, out_elems, with
     return out[:out_elems], (None if tS is None else tS.cpu().numpy())
 
 
+def attention(qkv, batch, seq, hidden, heads, scores_dy, softmax_params, ctx_dy, with_scratch=True):
+    """Steps 2-4 through ibert_attention_i.  qkv: int8 [batch*seq, 3*hidden]; returns ctx int8 [batch*seq, hidden]."""
+    tq = to_dev(qkv, np.int8)
+    tc = torch.full((batch * seq * hidden + 16,), 77, dtype=torch.int8, device=DEV)
+    ts = None
+    if with_scratch:
+        ts = torch.zeros(B.ibert_attention_scratch_bytes(batch, seq, heads), dtype=torch.uint8, device=DEV)
+    B.ibert_attention_i(tq, tc, batch, seq, hidden, heads, B.Dyadic(*scores_dy), softmax_params, B.Dyadic(*ctx_dy), ts)
+    torch.cuda.synchronize()
+    out = tc.cpu().numpy()
+    assert np.all(out[batch * seq * hidden:] == 77), "wrote past the end"
+    return out[:batch * seq * hidden].reshape(batch * seq, hidden)
+
+
 def softmax(x, params, cols=None, ldx=None, ldy=None, x_off=0, y_off=0):
     x = np.ascontiguousarray(x, np.int32)
     rows = x.shape[0]
