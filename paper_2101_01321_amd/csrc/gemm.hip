@@ -112,12 +112,12 @@ __device__ __forceinline__ v4i load_chunk(const int8_t* p, int k, int K)
 // residual tile.  JC (MFMA block rows per chunk) is the largest power-of-two divisor of BM/32 that fits the
 // budget: the main loop's own allocation for small tiles (several workgroups share a CU), up to 160 KB
 // for big ones (one workgroup per CU anyway).
-template <int BM, int BN, int BK>
+template <int BM, int BN, int BK, int NSTG = 2>
 struct EpiLayout {
     static constexpr int SP = BN + 4;
     static constexpr int FM = BM / 32;
     static constexpr int FIXED = 3 * BN + BM * BN / 4;
-    static constexpr int MAIN = 2 * (BM + BN) * BK / 4;
+    static constexpr int MAIN = NSTG * (BM + BN) * BK / 4;
     static constexpr int BUDGET = MAIN * 4 >= 65536 ? 40000 : MAIN;
     static constexpr int fit(int jc) { return 32 * jc * SP + FIXED <= BUDGET; }
     static constexpr int JC = fit(FM) ? FM : (FM >= 2 && fit(FM / 2) ? FM / 2 : (FM >= 4 && fit(FM / 4) ? FM / 4 : 1));
@@ -332,30 +332,46 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
             __builtin_amdgcn_sched_barrier(0);
         };
 
+        // RING = LDS stages.  Steps 0 .. RING-1 are requested up front; step kt+RING is requested in the
+        // second phase of step kt, into the stage step kt has just left.  Loads complete in order, so "step s
+        // has landed" is a wait that leaves the loads of the younger steps outstanding.
+        constexpr int NSTG = RING;
+        static_assert(NSTG >= 2 && NSTG <= 4, "stage count");
+        constexpr auto vm = [](int n) { return ((n > 63 ? 63 : n) & 15) | (7 << 4) | (15 << 8) | (((n > 63 ? 63 : n) >> 4) << 14); };
+        auto wait_landed = [&](int younger) {                          // younger: steps requested after the awaited one
+            if (younger <= 0) __builtin_amdgcn_s_waitcnt(vm(0));
+            else if (younger == 1) __builtin_amdgcn_s_waitcnt(vm(NL));
+            else if (younger == 2) __builtin_amdgcn_s_waitcnt(vm(2 * NL));
+            else __builtin_amdgcn_s_waitcnt(vm(3 * NL));               // RING <= 4: never more than three
+        };
+        const int npro = nk < NSTG ? nk : NSTG;
 #pragma unroll
-        for (int q = 0; q < NL; ++q) dma_one(q, 0, 0);
-        if (nk > 1) {
+        for (int st = 0; st < NSTG; ++st)
+            if (st < npro) {
 #pragma unroll
-            for (int q = 0; q < NL; ++q) dma_one(q, 1, 1);
-            __builtin_amdgcn_s_waitcnt((NL & 15) | (7 << 4) | (15 << 8) | ((NL >> 4) << 14));   // vmcnt(NL): step 0 has landed
-        } else {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        }
+                for (int q = 0; q < NL; ++q) dma_one(q, st, st);
+            }
+        wait_landed(npro - 1);
         asm volatile("s_barrier" ::: "memory");
         v4i xa0[FM], wb0[FN], xa1[FM], wb1[FN];
 #pragma unroll
         for (int q = 0; q < NR; ++q) read_one(q, 0, 0, xa0, wb0);
         IBERT_TS(1);
         // One K step.  Phase 1: slice 0 (fragments already in registers) while slice 1 is read.  Then this
-        // wavefront's share of step kt+1 has landed and its reads of buffer `buf` are done; after the barrier
-        // that holds for the whole workgroup, so `buf` may be refilled and the other buffer read.  Phase 2:
-        // slice 1, while slice 0 of step kt+1 is read and step kt+2 is requested (uniform test per request).
+        // wavefront's share of step kt+1 has landed and its reads of stage `buf` are done; after the barrier
+        // that holds for the whole workgroup, so `buf` may be refilled and the next stage read.  Phase 2:
+        // slice 1, while slice 0 of step kt+1 is read and step kt+RING is requested (uniform test per request).
+        int buf = 0;
         for (int kt = 0; kt < nk; ++kt) {
-            const int buf = kt & 1;
+            const int nbuf = buf + 1 == NSTG ? 0 : buf + 1;
             phase(xa0, wb0, xa1, wb1, buf, 1, std::true_type{}, 0, 0, false);
-            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            // steps requested after kt+1 so far: kt+2 .. min(kt+RING-1, nk-1)
+            const int hi = kt + NSTG - 1 < nk - 1 ? kt + NSTG - 1 : nk - 1;
+            wait_landed(hi - (kt + 1));
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
             // (the fragment reads past the last step fetch stale LDS bytes that nothing uses)
-            phase(xa1, wb1, xa0, wb0, buf ^ 1, 0, std::true_type{}, kt + 2, buf, kt + 2 < nk);
+            phase(xa1, wb1, xa0, wb0, nbuf, 0, std::true_type{}, kt + NSTG, buf, kt + NSTG < nk);
+            buf = nbuf;
         }
     } else {
     // The loop body is branch-free apart from one uniform test around the MFMAs, so that the compiler can
@@ -406,7 +422,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
     // keeps the code small.  The finishing loop must never wait on memory -- a wait for a load would also
     // wait for the previous store to be acknowledged (one counter covers both), a full round trip per row --
     // so per-channel constants sit in registers and the residual tile is parked in LDS beforehand.
-    using EL = EpiLayout<BM, BN, BK>;
+    using EL = EpiLayout<BM, BN, BK, (DMA ? RING : 2)>;
     constexpr int SP = EL::SP, JC = EL::JC;
     constexpr int G4 = BN / 4;                                     // 4-channel groups per row
     constexpr int RPS = GEMM_THREADS / G4;                         // rows finished per pass of the workgroup
@@ -710,11 +726,14 @@ static const GemmConfig kConfigs[] = {
     {64, 64, 128, 3, 0.30},
     {64, 128, 64, 3, 0.35},
     {128, 96, 128, 2, 0.50},
-    {256, 192, 128, 1, 0.70},       // ring 1: direct-to-LDS loader (whole tiles only)
-    {128, 128, 128, 1, 0.60},
-    {256, 256, 128, 1, 0.75},
-    {128, 96, 128, 1, 0.45},
-    {256, 128, 128, 1, 0.60},
+    {256, 192, 128, 2, 0.70},       // from here on: direct-to-LDS loader (whole tiles only), ring = LDS stages
+    {128, 128, 128, 2, 0.60},
+    {256, 256, 128, 2, 0.75},
+    {128, 96, 128, 2, 0.45},
+    {256, 128, 128, 2, 0.60},
+    {128, 96, 128, 4, 0.55},
+    {128, 128, 128, 4, 0.60},
+    {256, 128, 128, 3, 0.60},
 };
 constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 #ifdef IBERT_KERNEL_TIMING
@@ -730,7 +749,7 @@ static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
     const int64_t blocks = (int64_t)g.tiles_m * g.tiles_n * g.nbatch;
     if (blocks > 0x7fffffffLL) return IBERT_ERR_SHAPE;
     g.xcd_chunk = (blocks % 8 == 0 && blocks >= 16) ? (int32_t)(blocks / 8) : 0;
-    constexpr size_t lds_bytes = EpiLayout<BM, BN, BK>::LDS_BYTES;
+    constexpr size_t lds_bytes = EpiLayout<BM, BN, BK, (DMA ? RING : 2)>::LDS_BYTES;
     static_assert(lds_bytes <= 163840, "LDS budget");
 #define IBERT_GEMM_LAUNCH(I8_, KT_)                                                                       \
     do {                                                                                                  \
@@ -865,11 +884,11 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
         const int cfg = choose_config(d, nb);
         if (gelu) {
             switch (cfg) {
-                case 6: if (dma_ok(d, 256, 192)) return launch_mfma<256, 192, 128, 1, false, true, true>(g, i8, stream); break;
-                case 7: if (dma_ok(d, 128, 128)) return launch_mfma<128, 128, 128, 1, false, true, true>(g, i8, stream); break;
-                case 8: if (dma_ok(d, 256, 256)) return launch_mfma<256, 256, 128, 1, false, true, true>(g, i8, stream); break;
-                case 9: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 1, false, true, true>(g, i8, stream); break;
-                case 10: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 1, false, true, true>(g, i8, stream); break;
+                case 6: if (dma_ok(d, 256, 192)) return launch_mfma<256, 192, 128, 2, false, true, true>(g, i8, stream); break;
+                case 7: if (dma_ok(d, 128, 128)) return launch_mfma<128, 128, 128, 2, false, true, true>(g, i8, stream); break;
+                case 8: if (dma_ok(d, 256, 256)) return launch_mfma<256, 256, 128, 2, false, true, true>(g, i8, stream); break;
+                case 9: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 2, false, true, true>(g, i8, stream); break;
+                case 10: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 2, false, true, true>(g, i8, stream); break;
                 default: break;
             }
             return IBERT_ERR_NOT_IMPLEMENTED;
@@ -881,11 +900,14 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
             case 3: return launch_mfma<64, 64, 128, 3>(g, i8, stream);
             case 4: return launch_mfma<64, 128, 64, 3>(g, i8, stream);
             case 5: return launch_mfma<128, 96, 128, 2>(g, i8, stream);
-            case 6: if (dma_ok(d, 256, 192)) return launch_mfma<256, 192, 128, 1, false, true>(g, i8, stream); break;
-            case 7: if (dma_ok(d, 128, 128)) return launch_mfma<128, 128, 128, 1, false, true>(g, i8, stream); break;
-            case 8: if (dma_ok(d, 256, 256)) return launch_mfma<256, 256, 128, 1, false, true>(g, i8, stream); break;
-            case 9: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 1, false, true>(g, i8, stream); break;
-            case 10: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 1, false, true>(g, i8, stream); break;
+            case 6: if (dma_ok(d, 256, 192)) return launch_mfma<256, 192, 128, 2, false, true>(g, i8, stream); break;
+            case 7: if (dma_ok(d, 128, 128)) return launch_mfma<128, 128, 128, 2, false, true>(g, i8, stream); break;
+            case 8: if (dma_ok(d, 256, 256)) return launch_mfma<256, 256, 128, 2, false, true>(g, i8, stream); break;
+            case 9: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 2, false, true>(g, i8, stream); break;
+            case 10: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 2, false, true>(g, i8, stream); break;
+            case 11: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 4, false, true>(g, i8, stream); break;
+            case 12: if (dma_ok(d, 128, 128)) return launch_mfma<128, 128, 128, 4, false, true>(g, i8, stream); break;
+            case 13: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 3, false, true>(g, i8, stream); break;
             default: break;
         }
         return launch_mfma<128, 128, 64, 2>(g, i8, stream);
