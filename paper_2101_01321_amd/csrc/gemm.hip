@@ -314,9 +314,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
         };
         // One phase: the MFMAs of one 64-wide K slice (operands xa, wb); every SPC MFMAs one fragment of
         // the next phase is read (into nxa, nwb) and one block of a later step is requested.
+        // The blocks requested are [Q0, Q1) of step dkt (if dm), one per slot.
         auto phase = [&](v4i (&xa)[FM], v4i (&wb)[FN], v4i (&nxa)[FM], v4i (&nwb)[FN], int rbuf, int rs,
-                         auto read_tag, int dkt, int dbuf, bool dm) {
+                         auto read_tag, int dkt, int dbuf, bool dm, auto q0_tag, auto q1_tag) {
             constexpr bool RD = decltype(read_tag)::value;
+            constexpr int Q0 = decltype(q0_tag)::value, Q1 = decltype(q1_tag)::value;
 #pragma unroll
             for (int i = 0; i < FN; ++i)
 #pragma unroll
@@ -324,7 +326,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
                     const int idx = i * FM + jj;
                     if (idx % SPC == 0 && idx / SPC < NR) {
                         if (RD) read_one(idx / SPC, rbuf, rs, nxa, nwb);
-                        if (dm) dma_one(idx / SPC, dkt, dbuf);
+                        if (Q0 + idx / SPC < Q1 && dm) dma_one(Q0 + idx / SPC, dkt, dbuf);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                     acc[i][jj] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wb[i], xa[jj], acc[i][jj], 0, 0, 0);
@@ -332,9 +334,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
             __builtin_amdgcn_sched_barrier(0);
         };
 
-        // RING = LDS stages.  Steps 0 .. RING-1 are requested up front; step kt+RING is requested in the
-        // second phase of step kt, into the stage step kt has just left.  Loads complete in order, so "step s
-        // has landed" is a wait that leaves the loads of the younger steps outstanding.
+        // RING = LDS stages.  Steps 0 .. RING-1 are requested up front; step kt+RING is requested into the stage
+        // step kt has just left: all of it in the second phase of step kt with two stages, and with three or more
+        // (there is time) half there and half in the first phase of step kt+1, because a wavefront that waits
+        // for the address unit to take a request issues no MFMA meanwhile, and the four wavefronts ask at once.
+        // Loads complete in order, so "step s has landed" is a wait that leaves the loads of the younger steps
+        // outstanding.
         constexpr int NSTG = RING;
         static_assert(NSTG >= 2 && NSTG <= 4, "stage count");
         constexpr auto vm = [](int n) { return ((n > 63 ? 63 : n) & 15) | (7 << 4) | (15 << 8) | (((n > 63 ? 63 : n) >> 4) << 14); };
@@ -364,13 +369,34 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
         int buf = 0;
         for (int kt = 0; kt < nk; ++kt) {
             const int nbuf = buf + 1 == NSTG ? 0 : buf + 1;
-            phase(xa0, wb0, xa1, wb1, buf, 1, std::true_type{}, 0, 0, false);
+#ifdef IBERT_KERNEL_TIMING
+            const long long tt0 = __builtin_readcyclecounter();
+#endif
+            constexpr int QH = NSTG >= 3 ? (NL + 1) / 2 : NL;          // blocks requested in the second phase
+            const int pbuf = buf == 0 ? NSTG - 1 : buf - 1;
+            phase(xa0, wb0, xa1, wb1, buf, 1, std::true_type{}, kt - 1 + NSTG, pbuf, kt >= 1 && kt - 1 + NSTG < nk,
+                  std::integral_constant<int, QH>{}, std::integral_constant<int, NL>{});
+#ifdef IBERT_KERNEL_TIMING
+            const long long tt1 = __builtin_readcyclecounter();
+#endif
             // steps requested after kt+1 so far: kt+2 .. min(kt+RING-1, nk-1)
             const int hi = kt + NSTG - 1 < nk - 1 ? kt + NSTG - 1 : nk - 1;
             wait_landed(hi - (kt + 1));
+#ifdef IBERT_KERNEL_TIMING
+            const long long tt2 = __builtin_readcyclecounter();
+#endif
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#ifdef IBERT_KERNEL_TIMING
+            const long long tt3 = __builtin_readcyclecounter();
+#endif
             // (the fragment reads past the last step fetch stale LDS bytes that nothing uses)
-            phase(xa1, wb1, xa0, wb0, nbuf, 0, std::true_type{}, kt + NSTG, buf, kt + NSTG < nk);
+            phase(xa1, wb1, xa0, wb0, nbuf, 0, std::true_type{}, kt + NSTG, buf, kt + NSTG < nk,
+                  std::integral_constant<int, 0>{}, std::integral_constant<int, QH>{});
+#ifdef IBERT_KERNEL_TIMING
+            tstamp[5] += tt1 - tt0;                                    // phase 1
+            tstamp[6] += tt2 - tt1;                                    // wait for the next step's loads
+            tstamp[7] += tt3 - tt2;                                    // LDS reads + barrier
+#endif
             buf = nbuf;
         }
     } else {
@@ -731,9 +757,8 @@ static const GemmConfig kConfigs[] = {
     {256, 256, 128, 2, 0.75},
     {128, 96, 128, 2, 0.45},
     {256, 128, 128, 2, 0.60},
-    {128, 96, 128, 4, 0.55},
-    {128, 128, 128, 4, 0.60},
-    {256, 128, 128, 3, 0.60},
+    {128, 96, 128, 3, 0.55},
+    {128, 128, 128, 3, 0.60},
 };
 constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 #ifdef IBERT_KERNEL_TIMING
@@ -828,9 +853,10 @@ static int choose_config(const ibert_gemm_desc& d, int64_t nb)
     auto tiles = [&](int bm, int bn) -> int64_t { return dma_ok(d, bm, bn) ? (int64_t)(d.M / bm) * (d.N / bn) * nb : 0; };
     if (tiles(256, 256) >= 512) return 8;
     if (tiles(256, 192) >= 224) return 6;
-    if (tiles(128, 96) >= 256) return 9;
+    // (one workgroup per CU and a long K: a third LDS stage lets the requests spread over the whole step)
+    if (tiles(128, 96) >= 256) return tiles(128, 96) <= 256 && d.K >= 2048 ? 11 : 9;
     if (tiles(256, 128) >= 448) return 10;
-    if (tiles(128, 128) >= 128) return 7;
+    if (tiles(128, 128) >= 128) return tiles(128, 128) <= 256 && d.K >= 2048 ? 12 : 7;
     const int64_t tiles128 = (((int64_t)d.M + 127) / 128) * (((int64_t)d.N + 127) / 128) * nb;
     if (tiles128 >= 384) return 2;
     return d.K >= 512 ? 3 : 4;
@@ -905,9 +931,8 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
             case 8: if (dma_ok(d, 256, 256)) return launch_mfma<256, 256, 128, 2, false, true>(g, i8, stream); break;
             case 9: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 2, false, true>(g, i8, stream); break;
             case 10: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 2, false, true>(g, i8, stream); break;
-            case 11: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 4, false, true>(g, i8, stream); break;
-            case 12: if (dma_ok(d, 128, 128)) return launch_mfma<128, 128, 128, 4, false, true>(g, i8, stream); break;
-            case 13: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 3, false, true>(g, i8, stream); break;
+            case 11: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 3, false, true>(g, i8, stream); break;
+            case 12: if (dma_ok(d, 128, 128)) return launch_mfma<128, 128, 128, 3, false, true>(g, i8, stream); break;
             default: break;
         }
         return launch_mfma<128, 128, 64, 2>(g, i8, stream);

@@ -290,11 +290,10 @@ def test_gemm_trans_w_mfma_path(G, M, N, K, ldw):
 @pytest.mark.parametrize("cfg,M,N,K", [(6, 512, 384, 128), (6, 256, 576, 256), (6, 768, 192, 768), (7, 128, 128, 128),
                                        (7, 384, 256, 384), (7, 256, 640, 1152), (8, 512, 256, 256), (8, 256, 768, 640),
                                        (9, 256, 288, 384), (10, 512, 384, 512),
-                                       # deeper LDS rings: every step count around the ring depth
-                                       (11, 256, 192, 128), (11, 128, 288, 256), (11, 256, 96, 384), (11, 128, 192, 512),
-                                       (11, 384, 96, 640), (11, 128, 96, 1408), (12, 256, 128, 128), (12, 128, 256, 384),
-                                       (12, 128, 128, 512), (12, 256, 256, 896), (13, 256, 256, 128), (13, 512, 128, 256),
-                                       (13, 256, 128, 384), (13, 256, 384, 1024)])
+                                       # three LDS stages: every step count around the ring depth
+                                       (11, 128, 96, 128), (11, 256, 96, 256), (11, 128, 192, 384), (11, 128, 96, 512),
+                                       (11, 256, 192, 1280), (12, 128, 128, 128), (12, 128, 128, 256), (12, 256, 128, 384),
+                                       (12, 128, 256, 512), (12, 128, 256, 1024)])
 def test_gemm_direct_to_lds_tiles(G, cfg, M, N, K):
     # the tile configurations whose loader writes LDS straight from global memory (whole tiles only), forced
     # through the configuration override; 1, 2, odd and even numbers of K steps
