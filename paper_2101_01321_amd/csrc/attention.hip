@@ -43,16 +43,20 @@ __device__ __forceinline__ int vt_offset(int c, int n)
 
 __device__ __forceinline__ int swz64(int row) { return (row >> 1) & 3; }      // chunk swizzle of 64-byte rows
 
-// DY(x; m, s) for |x| < 2^24 when 33 <= s <= 62: x m + 2^(s-1) fits 63 bits, and floor-division by 2^s is the
-// high dword shifted by s - 32.  rnd = 2^(s-1), sh = s - 32.
+// DY(x; m, s) for |x| < 2^21 when 21 <= s <= 62: x m + 2^(s-1) fits 63 bits and the result fits 32 (it is below
+// 2^(52-s)), so the floor-division by 2^s is bits [s, s+32) of the 64-bit sum: the high dword shifted by s - 32, or
+// for s < 32 a funnel shift of the two dwords.  rnd = 2^(s-1).
 __device__ __forceinline__ int32_t dyadic_hi(int32_t x, int32_t m, int64_t rnd, int32_t sh)
 {
     const int64_t p = (int64_t)x * m + rnd;
-    return (int32_t)(p >> 32) >> sh;
+    const int32_t hi = (int32_t)(p >> 32);
+    const int32_t a = hi >> ((sh - 32) & 31);
+    const int32_t b = (int32_t)__builtin_amdgcn_alignbit((uint32_t)hi, (uint32_t)p, (uint32_t)(sh & 31));
+    return sh >= 32 ? a : b;
 }
 
-// FAST: the 24-bit Softmax forms apply.  RQ: both requantization shifts are in [33, 62] (accumulators are below
-// 2^21 in magnitude: 64 or 128 products of INT8 pairs), so dyadic_hi applies; |scores| then stays below 2^20 and
+// FAST: the 24-bit Softmax forms apply.  RQ: both requantization shifts are in [21, 62] (accumulators are below
+// 2^21 in magnitude: 64 or 128 products of INT8 pairs), so dyadic_hi applies; |scores| then stays below 2^31 and
 // needs no clamp.
 template <bool FAST, bool RQ>
 __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttentionArgs a)
@@ -113,7 +117,6 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttentionArgs a)
     const int qrow = wave * 16 + frow;                     // query row inside the block
     const v4i qf = *reinterpret_cast<const v4i*>(qs + qrow * 64 + ((fch ^ swz64(qrow)) << 4));
     const int64_t s_rnd = (int64_t)1 << ((a.s_s - 1) & 63), c_rnd = (int64_t)1 << ((a.c_s - 1) & 63);
-    const int32_t s_sh = (a.s_s - 32) & 31, c_sh = (a.c_s - 32) & 31;
     int32_t sc[8][4];                                      // sc[i][r]: key 16 i + 4 fch + r
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -122,7 +125,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttentionArgs a)
         const v4i acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(kf, qf, v4i{0, 0, 0, 0}, 0, 0, 0);
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            sc[i][r] = RQ ? dyadic_hi(acc[r], a.s_m, s_rnd, s_sh) : clamp_i64_to_i32(dyadic64(acc[r], a.s_m, a.s_s), 2147483647);
+            sc[i][r] = RQ ? dyadic_hi(acc[r], a.s_m, s_rnd, a.s_s) : clamp_i64_to_i32(dyadic64(acc[r], a.s_m, a.s_s), 2147483647);
     }
 
     // ---- softmax over the 128 keys of the lane's query (four lanes share a query) ---------------
@@ -178,7 +181,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttentionArgs a)
         int32_t o[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            o[r] = RQ ? med3_i32(dyadic_hi(acc[r], a.c_m, c_rnd, c_sh), -127, 127) : clamp_i64_to_i32(dyadic64(acc[r], a.c_m, a.c_s), 127);
+            o[r] = RQ ? med3_i32(dyadic_hi(acc[r], a.c_m, c_rnd, a.c_s), -127, 127) : clamp_i64_to_i32(dyadic64(acc[r], a.c_m, a.c_s), 127);
         *reinterpret_cast<uint32_t*>(out + 16 * cb) = pack4_i8(o[0], o[1], o[2], o[3]);
     }
 }
@@ -201,7 +204,7 @@ int launch_attention(const int8_t* qkv, int8_t* ctx, int32_t batch, int32_t seq,
     a.ld_qkv = 3 * (int64_t)hidden; a.ld_ctx = hidden;
     a.s_m = scores_dy.m; a.s_s = scores_dy.s; a.c_m = ctx_dy.m; a.c_s = ctx_dy.s;
     a.sm = softmax_const(sp);
-    const bool rq = a.s_s >= 33 && a.s_s <= 62 && a.c_s >= 33 && a.c_s <= 62;
+    const bool rq = a.s_s >= 21 && a.s_s <= 62 && a.c_s >= 21 && a.c_s <= 62;
     const dim3 grid((unsigned)blocks), block(ATT_THREADS);
     if (softmax_fast_ok(sp)) {
         if (rq) hipLaunchKernelGGL((attention_kernel<true, true>), grid, block, 0, stream, a);
