@@ -25,6 +25,7 @@ struct AttentionArgs {
     const int8_t* qkv;     // [batch*seq, 3*hidden]: Q | K | V, heads side by side
     int8_t* ctx;           // [batch*seq, hidden]
     int32_t heads;
+    int32_t xcd_chunk;     // workgroups per XCD when the grid divides by 8, else 0
     int64_t ld_qkv, ld_ctx;
     int32_t s_m, s_s;      // scores requantization
     int32_t c_m, c_s;      // context requantization
@@ -66,8 +67,13 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttentionArgs a)
     __shared__ __attribute__((aligned(16))) int8_t vt[ATT_DH * ATT_L];        // V_h transposed
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int qblk = blockIdx.x & 1;                       // which half of the queries
-    const int bh = blockIdx.x >> 1;
+    // Workgroups are dealt round-robin to the 8 XCDs.  The two halves of a head's queries read the same K and V,
+    // and neighbouring heads share 128-byte lines of the packed QKV rows: give each XCD a contiguous run of
+    // (batch, head, half) so that those re-reads hit its own L2.
+    int bid = blockIdx.x;
+    if (a.xcd_chunk > 0) bid = (bid & 7) * a.xcd_chunk + (bid >> 3);
+    const int qblk = bid & 1;                              // which half of the queries
+    const int bh = bid >> 1;
     const int b = bh / a.heads, h = bh - b * a.heads;
     const int hidden = a.heads * ATT_DH;
     const int8_t* base = a.qkv + (int64_t)b * ATT_L * a.ld_qkv + h * ATT_DH;
@@ -201,6 +207,7 @@ int launch_attention(const int8_t* qkv, int8_t* ctx, int32_t batch, int32_t seq,
     if (blocks > 0x7fffffffLL) return IBERT_ERR_SHAPE;
     AttentionArgs a;
     a.qkv = qkv; a.ctx = ctx; a.heads = heads;
+    a.xcd_chunk = blocks % 8 == 0 ? (int32_t)(blocks / 8) : 0;
     a.ld_qkv = 3 * (int64_t)hidden; a.ld_ctx = hidden;
     a.s_m = scores_dy.m; a.s_s = scores_dy.s; a.c_m = ctx_dy.m; a.c_s = ctx_dy.s;
     a.sm = softmax_const(sp);

@@ -31,18 +31,17 @@ __device__ __forceinline__ uint32_t udiv_c(uint32_t u, uint32_t C, uint32_t magi
     return r < 0 ? q - 1 : q;
 }
 
-// Alg. 4: Newton iteration for floor(sqrt(n)) from x0 = 2^ceil(Bits(n)/2); stops when the iterate
-// no longer decreases.  The loop runs to the stop rule (some inputs need more than four passes).
-__device__ __forceinline__ uint32_t isqrt_newton(uint32_t n)
+// floor(sqrt(n)), the value the Newton iteration of Alg. 4 ends on (started at or above the root, its integer
+// iterates decrease to exactly the floor of the root).  Here: a single-precision estimate -- n rounded to 24 bits
+// and a correctly rounded root are together less than 0.01 away from the true root, so the truncated estimate is
+// off by at most one -- and one exact correction step in integers.
+__device__ __forceinline__ uint32_t isqrt_floor(uint32_t n)
 {
-    if (n == 0) return 0;
-    const int bits = 32 - __clz((int)n);
-    uint32_t x = 1u << ((bits + 1) >> 1);            // <= 2^16
-    for (;;) {
-        const uint32_t y = (x + n / x) >> 1;
-        if (y >= x) return x;
-        x = y;
-    }
+    uint32_t x = (uint32_t)__fsqrt_rn((float)n);
+    x = x > 65535u ? 65535u : x;                       // keeps the squares below inside 32 bits
+    if (x * x > n) return x - 1;
+    if (x < 65535u && (x + 1) * (x + 1) <= n) return x + 1;
+    return x;
 }
 
 template <int LPR>
@@ -160,7 +159,7 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
     const uint32_t rem = (uint32_t)(ss - (((uint64_t)qa * Cu) << 11));   // < C * 2^11 + 2^11
     const uint32_t var = (qa << 11) + udiv_c(rem, Cu, a.magic_c);
 
-    uint32_t sigma = isqrt_newton(var);
+    uint32_t sigma = isqrt_floor(var);
     sigma = sigma < 1u ? 1u : sigma;
     const int32_t f = (int32_t)((1u << 24) / sigma);
     if (!live) return;

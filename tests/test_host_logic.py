@@ -166,3 +166,20 @@ def test_entry_points_reject_bad_arguments_before_touching_the_gpu():
     assert L.ibert_encoder_layer_i(C.byref(w), C.byref(q), dummy, 512, 1, 128, 256, 4, 1024, dummy * 1, 16, None) == -5
     assert L.ibert_encoder_layer_i(None, C.byref(q), dummy, 512, 1, 128, 256, 4, 1024, dummy, 1 << 30, None) == -1
     assert L.ibert_encoder_layer_i(C.byref(w), C.byref(q), dummy, 512, 1, 128, 256, 4, 1024, 256, 1 << 30, None) == -1
+
+
+def test_single_precision_root_estimate_is_off_by_at_most_one():
+    # the LayerNorm kernel takes floor(sqrt(n)) from a correctly rounded single-precision root of n (itself
+    # rounded to single precision) plus one integer correction step; the recipe is replayed here in numpy
+    # (float32 sqrt is correctly rounded there too) on every n next to a perfect square and on random n
+    import math
+    k = np.arange(1, 65536, dtype=np.uint64)
+    n = np.unique(np.concatenate([k * k - 1, k * k, k * k + 1, np.array([0, 1, 2, 3, 2 ** 32 - 1], np.uint64),
+                                  np.random.default_rng(4).integers(0, 2 ** 32, size=400000, dtype=np.uint64)]))
+    n = n[n < 2 ** 32]
+    x = np.sqrt(n.astype(np.float32)).astype(np.uint64)
+    x = np.minimum(x, 65535)
+    x = np.where(x * x > n, x - 1, np.where((x < 65535) & ((x + 1) * (x + 1) <= n), x + 1, x))
+    want = np.array([math.isqrt(int(v)) for v in n[::97]], np.uint64)
+    assert np.array_equal(x[::97], want)
+    assert np.all(x * x <= n) and np.all((x + 1) * (x + 1) > n)            # the defining property, on all of them
