@@ -24,6 +24,22 @@ sys.path.insert(0, ROOT)
 
 PEAK_INT8_OPS = 5.0e15      # dense INT8 MFMA, op/s
 PEAK_HBM = 8.0e12           # B/s
+# HBM-side bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; separate runs of this script,
+# summarised in profiles/): kernel name as the library reports it -> {"read": B, "written": B}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "bench_base_b32_traffic.json")
+
+
+def measured_traffic(kernel, config):
+    """Fabric bytes (read + written) one launch of `kernel` moves, from the committed counter summary; None if absent."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            table = json.load(f)
+    except OSError:
+        return None
+    if table.get("config") != config:
+        return None
+    e = table.get("kernels", {}).get(kernel)
+    return None if e is None else e["read"] + e["written"]
 
 
 def main():
@@ -113,6 +129,11 @@ def main():
         for _ in range(args.steps):
             forward()
         recs = B.ibert_profile_end(cap)
+    # Every record carries what its two event records cost on the GPU queue.  That constant is taken from the
+    # timed region: the bracketed times of one forward minus the replayed forward itself, shared equally by its
+    # records -- so the per-step times below add up to ms_per_step.
+    overhead_ms = max(0.0, (sum(r[1] for r in recs) / args.steps - ms_per_step) / (len(recs) / args.steps)) if recs else 0.0
+    recs = [(s_, max(ms - overhead_ms, 1e-6), o_, b_, k_) for s_, ms, o_, b_, k_ in recs]
     per_step = {}
     for step_no, ms, ops, nbytes, kernel in recs:
         d = per_step.setdefault(step_no, {"ms": 0.0, "n": 0, "ops": ops, "bytes": nbytes, "kernel": kernel})
@@ -136,8 +157,10 @@ def main():
         achieved = dom["bytes"] / dom["launches"] / avg_s / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
                     "frac": achieved * 1e9 / PEAK_HBM, "traffic": None}
+    roofline["traffic"] = measured_traffic(dom_name, args.config)
     roofline.update({"kernel": dom_name, "steps": sorted(dom["steps"]), "avg_launch_us": avg_s * 1e6,
-                     "launches": dom["launches"]})
+                     "launches": dom["launches"], "algorithmic_bytes": dom["bytes"] / dom["launches"],
+                     "event_overhead_us": overhead_ms * 1e3})
     step_table = {}
     for step_no in sorted(per_step):
         d = per_step[step_no]

@@ -317,7 +317,7 @@ int ibert_set_fusion(int32_t flags);
  * ---------------------------------------------------------------------------------------------- */
 typedef struct {
     int32_t step;        /* 1..10, the step numbers of ibert_encoder_layer_i */
-    float ms;            /* event-to-event time of the step's launch(es) */
+    float ms;            /* event-to-event time of the step's launch(es); includes what the two event records cost */
     double ops;          /* algorithmic integer ops: 2*M*N*K*batch for MatMul steps, 0 otherwise */
     double bytes;        /* algorithmic bytes: operands read once + outputs written once */
     char kernel[96];     /* name of the kernel the step launched, as a profiler shows it (without namespace) */
