@@ -847,11 +847,12 @@ static bool dma_ok(const ibert_gemm_desc& d, int bm, int bn)
 // so that one workgroup's requantization overlaps another's MFMAs.
 // Everything else takes the register-ring loader: 128x128 tiles with a 64-wide K step while that gives every
 // CU something to do, below that 64x64 tiles.
-static int choose_config(const ibert_gemm_desc& d, int64_t nb)
+static int choose_config(const ibert_gemm_desc& d, int64_t nb, bool gelu)
 {
     if (g_config_override >= 0 && g_config_override < kNumConfigs) return g_config_override;
     auto tiles = [&](int bm, int bn) -> int64_t { return dma_ok(d, bm, bn) ? (int64_t)(d.M / bm) * (d.N / bn) * nb : 0; };
-    if (tiles(256, 256) >= 512) return 8;
+    // (256x256 pays only when K is long enough to amortise its 256-value-per-lane epilogue, and never with GELU in it)
+    if (tiles(256, 256) >= 512 && d.K >= 8192 && !gelu) return 8;
     if (tiles(256, 192) >= 224) return 6;
     // (one workgroup per CU and a long K: a third LDS stage lets the requests spread over the whole step)
     if (tiles(128, 96) >= 256) return tiles(128, 96) <= 256 && d.K >= 2048 ? 11 : 9;
@@ -907,7 +908,7 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
     if (gelu && !(fast && d.K % 16 == 0)) return IBERT_ERR_NOT_IMPLEMENTED;
     if (fast) {
         if (d.K % 16 != 0) return launch_tail(g, i8, stream);       // bytewise K tail
-        const int cfg = choose_config(d, nb);
+        const int cfg = choose_config(d, nb, gelu != nullptr);
         if (gelu) {
             switch (cfg) {
                 case 6: if (dma_ok(d, 256, 192)) return launch_mfma<256, 192, 128, 2, false, true, true>(g, i8, stream); break;
