@@ -288,8 +288,8 @@ int ibert_layer_quant_from_scales(const ibert_layer_scales* scales, int32_t seq,
  *     ctx    = ibert_gemm_i8_requant(probs, V_h as [K,N]; ctx_dy, INT8, clamp 127), written into [T, hidden]
  * qkv: device int8 [batch*seq, 3*hidden] (Q | K | V, the heads of each side by side); ctx: device int8
  * [batch*seq, hidden].  softmax->out_dtype must be IBERT_I8.
- * With seq = 128 and hidden/heads = 64 (qkv 16-byte aligned, ctx 4-byte aligned) the three steps run as one kernel
- * and scores/probs are never stored -- unless bit 1 of the fusion mask is clear.  Any other shape takes the
+ * With seq in {128, 256, 384, 512} and hidden/heads = 64 (qkv 16-byte aligned, ctx 4-byte aligned) the three steps
+ * run as one kernel and scores/probs are never stored -- unless bit 1 of the fusion mask is clear.  Any other shape takes the
  * three-kernel route through `scratch` (device, 256-byte aligned, ibert_attention_scratch_bytes() bytes;
  * IBERT_ERR_WORKSPACE if it is NULL, small or misaligned).  scratch may always be passed.
  * ---------------------------------------------------------------------------------------------- */

@@ -240,8 +240,12 @@ def _attention_oracle(qkv, B_, L, H, nh, scores_dy, op, ctx_dy):
     (1, 2, 128, 2.0 ** -5, (1187698534, 20), (1518500250, 33)),        # below the fast range: general form
     (3, 2, 128, 2.0 ** -2, (1518500250, 41), (1073741824, 37)),       # q_ln2 = 2: the general Softmax path
     (2, 2, 128, 2.0 ** -9, (1518500250, 30), (1073741824, 35)),       # wide logits, context clamps at 127
+    (1, 2, 256, 2.0 ** -6, (1518500250, 36), (1073741824, 37)),       # longer rows, still one kernel
+    (1, 3, 384, 2.0 ** -6, (1187698534, 28), (1073741824, 37)),
+    (2, 2, 512, 2.0 ** -6, (1187698534, 28), (1518500250, 38)),
+    (1, 1, 512, 2.0 ** -2, (1518500250, 41), (60000, 22)),       # general Softmax and requantization forms at L = 512
     (2, 3, 72, 2.0 ** -6, (1518500250, 36), (1073741824, 37)),        # other lengths: three kernels through scratch
-    (1, 2, 256, 2.0 ** -6, (1518500250, 36), (1073741824, 37)),
+    (1, 2, 192, 2.0 ** -6, (1518500250, 36), (1073741824, 37)),
 ])
 def test_attention_equals_scores_softmax_context(G, B_, nh, L, S, sdy, cdy):
     from paper_2101_01321_amd import binding as B
@@ -256,7 +260,7 @@ def test_attention_equals_scores_softmax_context(G, B_, nh, L, S, sdy, cdy):
     assert len(np.unique(want)) > 10
     G.say("attention B=%d heads=%d L=%d S=%g" % (B_, nh, L, S))
     _eq(G.attention(qkv, B_, L, H, nh, sdy, sp, cdy), want, "attention")
-    if L == 128:
+    if L in (128, 256, 384, 512):
         G.say("attention, one-kernel form without scratch")
         _eq(G.attention(qkv, B_, L, H, nh, sdy, sp, cdy, with_scratch=False), want, "attention (no scratch)")
         old = B.ibert_set_fusion(0)
@@ -378,7 +382,7 @@ def _layer_case_body(G, cfg, n_layers, fusion):
         for k in ("qkv", "scores", "probs", "ctx", "r1", "h1", "f1", "g", "r2"):
             if k == "f1" and (fusion & 1):
                 continue                                     # not materialised when GELU runs in the MatMul epilogue
-            if k in ("scores", "probs") and (fusion & 2) and cfg.seq == 128 and cfg.hidden == 64 * cfg.heads:
+            if k in ("scores", "probs") and (fusion & 2) and cfg.seq in (128, 256, 384, 512) and cfg.hidden == 64 * cfg.heads:
                 continue                                     # nor these when attention is one kernel
             _eq(got_inter[k], inter[k], "%s layer %d %s" % (cfg.name, l, k))
         _eq(ty.cpu().numpy(), want, "%s layer %d output" % (cfg.name, l))
