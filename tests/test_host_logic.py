@@ -168,6 +168,50 @@ def test_entry_points_reject_bad_arguments_before_touching_the_gpu():
     assert L.ibert_encoder_layer_i(C.byref(w), C.byref(q), dummy, 512, 1, 128, 256, 4, 1024, 256, 1 << 30, None) == -1
 
 
+def test_fused_entry_points_reject_bad_arguments_before_touching_the_gpu():
+    L = B.lib()
+    sp = B.ibert_softmax_params_from_scale(2.0 ** -6, 128)
+    gp = B.ibert_gelu_params_from_scale(2.0 ** -7, 0.05)
+    dy = B.Dyadic(1518500250, 36)
+    dummy = 256
+    att = lambda qkv, ctx, b, l, h, nh, s_dy, smp, c_dy, scr, nbytes: L.ibert_attention_i(qkv, ctx, b, l, h, nh, s_dy, smp, c_dy, scr, nbytes, None)
+    assert att(dummy, dummy, 1, 128, 768, 12, None, C.byref(sp), C.byref(dy), None, 0) == -1
+    assert att(dummy, dummy, 1, 128, 768, 5, C.byref(dy), C.byref(sp), C.byref(dy), None, 0) == -2          # heads must divide hidden
+    assert att(dummy, dummy, -1, 128, 768, 12, C.byref(dy), C.byref(sp), C.byref(dy), None, 0) == -2
+    assert att(dummy, dummy, 1, 128, 768, 12, C.byref(B.Dyadic(1, 63)), C.byref(sp), C.byref(dy), None, 0) == -3
+    sp32 = B.ibert_softmax_params_from_scale(2.0 ** -6, 128, 24, B.I32)
+    assert att(dummy, dummy, 1, 128, 768, 12, C.byref(dy), C.byref(sp32), C.byref(dy), None, 0) == -3       # probabilities must be INT8
+    assert att(None, None, 0, 128, 768, 12, C.byref(dy), C.byref(sp), C.byref(dy), None, 0) == 0            # empty batch
+    assert att(None, dummy, 1, 128, 768, 12, C.byref(dy), C.byref(sp), C.byref(dy), None, 0) == -1
+    # a length the one-kernel form does not cover needs the scratch buffer, big enough and 256-byte aligned
+    need = L.ibert_attention_scratch_bytes(1, 72, 12)
+    assert need >= 5 * 12 * 72 * 72 and need % 256 == 0
+    sp72 = B.ibert_softmax_params_from_scale(2.0 ** -6, 72)
+    assert att(dummy, dummy, 1, 72, 768, 12, C.byref(dy), C.byref(sp72), C.byref(dy), None, 0) == -5
+    assert att(dummy, dummy, 1, 72, 768, 12, C.byref(dy), C.byref(sp72), C.byref(dy), 512, need - 1) == -5
+    assert att(dummy, dummy, 1, 72, 768, 12, C.byref(dy), C.byref(sp72), C.byref(dy), 512 + 16, need) == -5
+    # MatMul + GELU
+    d = B.GemmDesc()
+    d.M, d.N, d.K, d.batch_outer, d.batch_inner = 4, 4, 4, 1, 1
+    d.lda = d.ldw = d.ldc = 4
+    d.per_channel, d.requant, d.out_dtype = 0, B.Dyadic(1, 0), B.I8
+    gg = lambda desc, A, W, gelu, Cc, scr: L.ibert_gemm_i8_gelu(desc, A, W, None, None, None, gelu, Cc, scr, None)
+    assert gg(None, dummy, dummy, C.byref(gp), dummy, None) == -1
+    assert gg(C.byref(d), dummy, dummy, None, dummy, None) == -1
+    assert gg(C.byref(d), None, dummy, C.byref(gp), dummy, None) == -1
+    bad = B.GeluParams(-161, -28366, -28366, 10 ** 6, B.Dyadic(-5, 3))
+    assert gg(C.byref(d), dummy, dummy, C.byref(bad), dummy, None) == -3
+    d.lda = 3
+    assert gg(C.byref(d), dummy, dummy, C.byref(gp), dummy, None) == -2
+    d.lda, d.M = 4, 0
+    assert gg(C.byref(d), None, None, C.byref(gp), None, None) == 0                                        # empty problem
+    # the fusion mask: query, set, unknown bits dropped
+    old = L.ibert_set_fusion(-1)
+    assert L.ibert_set_fusion(0) == old and L.ibert_set_fusion(-1) == 0
+    assert L.ibert_set_fusion(0xff) == 0 and L.ibert_set_fusion(-1) == 3
+    L.ibert_set_fusion(old)
+
+
 def test_single_precision_root_estimate_is_off_by_at_most_one():
     # the LayerNorm kernel takes floor(sqrt(n)) from a correctly rounded single-precision root of n (itself
     # rounded to single precision) plus one integer correction step; the recipe is replayed here in numpy
