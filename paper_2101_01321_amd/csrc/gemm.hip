@@ -39,10 +39,12 @@ struct GemmArgs {
     int32_t res_m, res_s;
     int32_t c_vec;     // output rows allow one vector store per lane (4 bytes INT8, 16 bytes INT32)
     int32_t r_vec;     // residual rows allow 16-byte loads
+    int32_t c_vec16;   // INT8 output rows allow 16-byte stores
     int32_t res_fast;  // residual absent, or its shift is in [8, 62]: its requantized value fits 32 bits
     int64_t res_rnd;   // 2^(res_s - 1), or 0 when res_s == 0
     int32_t xcd_chunk; // tiles per XCD when the grid divides by 8, else 0 (no remap)
     int32_t gelu_fast; // GELU epilogue: the 24-bit form applies
+    int32_t gelu_lut_lo, gelu_lut_n;   // GELU epilogue: table of the values at lo .. lo + n - 1 behind the tile's LDS (n = 0: none)
     GeluConst gelu;    // GELU epilogue: constants (the clamp before it is out_clamp = q_max)
 #ifdef IBERT_KERNEL_TIMING
     long long* dbg;    // development only: per-wave phase timestamps
@@ -356,6 +358,18 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
 #pragma unroll
                 for (int q = 0; q < NL; ++q) dma_one(q, st, st);
             }
+        if constexpr (GELU) {
+            // While the first loads are in flight: tabulate GELU (with its output requantization) over the interval
+            // outside of which it is constant -- below q_b the result is DY(0), from the first saturated value up
+            // it stays saturated -- so that the epilogue replaces ~17 instructions per value by a clamp and a byte
+            // read.  Every workgroup builds its own copy with the very function the table stands for.
+            int8_t* lut = lds + EpiLayout<BM, BN, BK, RING>::LDS_BYTES;
+            const int32_t rnd = 1 << ((g.gelu.s - 33) & 31), sh = (g.gelu.s - 32) & 31;
+            for (int e = tid; e < g.gelu_lut_n; e += GEMM_THREADS) {
+                const int32_t q = g.gelu_lut_lo + e;
+                lut[e] = (int8_t)(g.gelu_fast ? gelu_one_fast(q, g.gelu, rnd, sh) : gelu_one(q, g.gelu));
+            }
+        }
         wait_landed(npro - 1);
         asm volatile("s_barrier" ::: "memory");
         v4i xa0[FM], wb0[FN], xa1[FM], wb1[FN];
@@ -613,12 +627,22 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
     // token per accumulator, so it requantizes them in place and stores them itself (4 bytes INT8, 16 bytes
     // INT32; the four lanes that share a token write 16 or 64 contiguous bytes).  The chain per value is
     // register-only -- constants of the lane's channel group are re-read from LDS once per MFMA block column.
-    auto finish_direct = [&](auto res_tag, auto gf_tag) {
-        constexpr bool RES = decltype(res_tag)::value, GF = decltype(gf_tag)::value;
+    auto finish_direct = [&](auto res_tag, auto gf_tag, auto lut_tag) {
+        constexpr bool RES = decltype(res_tag)::value, GF = decltype(gf_tag)::value, LUT = decltype(lut_tag)::value;
+        const int8_t* const lut = lds + EL::LDS_BYTES;
+        const int32_t lut_hi = g.gelu_lut_n - 1;
+        // INT8 tiles go through LDS once more, packed: a lane's own store would be 4 bytes in each of 16 rows per
+        // instruction, which the address unit takes an order of magnitude longer over than whole rows.
+        constexpr int SPB = BN + 16;                               // staged row pitch in bytes (16-byte aligned rows)
+        // (measured: a gain of 1.5-2 us on the QKV projections; with GELU in the epilogue the big one-per-CU tiles
+        // gain nothing from it and 256x128 loses, so those keep the lane's own stores)
+        constexpr bool OST = OUT_I8 && !GELU && BM * SPB <= 32 * JC * SP * 4;   // fits the staging area in front of the constants
+        const bool use_ost = OST && g.c_vec16;
+        int8_t* const ostage = lds;
         char* const c_base = reinterpret_cast<char*>(g.C) +
                              (c_off + (int64_t)(m0 + wm0 + frow) * g.ldc + n0 + wn0 + 4 * fch) * (OUT_I8 ? 1 : 4);
         const uint32_t* const r_base = resl + (wm0 + frow) * G4 + (wn0 >> 2) + fch;
-#pragma unroll
+#pragma clang loop unroll(full)
         for (int i = 0; i < FN; ++i) {
             const int cl = wn0 + 16 * i + 4 * fch;
             const v4i bb = *reinterpret_cast<const v4i*>(par + cl);
@@ -631,7 +655,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
                 cc[e] = (int64_t)bb[e] * mm[e] + ((int64_t)1 << ((ss[e] - 1) & 63));
                 sh[e] = (ss[e] - 32) & 31;
             }
-#pragma unroll
+#pragma clang loop unroll(full)
             for (int j = 0; j < FM; ++j) {
                 uint32_t pk = 0;
                 if (RES) pk = r_base[j * 16 * G4 + i * 4];
@@ -645,18 +669,40 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
                         v += (int32_t)(((int64_t)r8 * g.res_m + g.res_rnd) >> g.res_s);
                     }
                     v = med3_i32(v, clamp_lo, clamp_hi);
-                    o[e] = GF ? post_fast(v) : post(v);
+                    if (LUT) o[e] = lut[med3_i32(v - g.gelu_lut_lo, 0, lut_hi)];
+                    else o[e] = GF ? post_fast(v) : post(v);
                 }
                 char* cp = c_base + ((uint32_t)(j * 16) * c_pitch + (uint32_t)(i * 16 * (OUT_I8 ? 1 : 4)));
-                if (OUT_I8) *reinterpret_cast<uint32_t*>(cp) = pack4_i8(o[0], o[1], o[2], o[3]);
-                else *reinterpret_cast<v4i*>(cp) = v4i{o[0], o[1], o[2], o[3]};
+                if (OUT_I8) {
+                    const uint32_t pk4 = pack4_i8(o[0], o[1], o[2], o[3]);
+                    if (use_ost) *reinterpret_cast<uint32_t*>(ostage + (wm0 + 16 * j + frow) * SPB + wn0 + 16 * i + 4 * fch) = pk4;
+                    else *reinterpret_cast<uint32_t*>(cp) = pk4;
+                } else {
+                    *reinterpret_cast<v4i*>(cp) = v4i{o[0], o[1], o[2], o[3]};
+                }
+            }
+        }
+        if (use_ost) {
+            __syncthreads();
+            constexpr int C16 = BN / 16, CH = BM * C16;            // 16-byte chunks per row, per tile
+            char* const ct = reinterpret_cast<char*>(g.C) + c_off + (int64_t)m0 * g.ldc + n0;
+#pragma unroll
+            for (int q0 = 0; q0 < CH; q0 += GEMM_THREADS) {
+                const int q = q0 + tid;
+                if (CH % GEMM_THREADS == 0 || q < CH) {
+                    const int row = q / C16, c16 = q - row * C16;
+                    *reinterpret_cast<v4i*>(ct + (uint32_t)row * c_pitch + c16 * 16) =
+                        *reinterpret_cast<const v4i*>(ostage + row * SPB + c16 * 16);
+                }
             }
         }
     };
     if (interior && fast) {
-        if (GELU && g.gelu_fast) finish_direct(std::false_type{}, std::true_type{});      // GELU excludes a residual
-        else if (R) finish_direct(std::true_type{}, std::false_type{});
-        else finish_direct(std::false_type{}, std::false_type{});
+        // (GELU excludes a residual; without a table -- it did not fit, or the parameters are unusual -- the
+        // arithmetic form runs, with the choice between its two variants made per value)
+        if (GELU && g.gelu_lut_n > 0) finish_direct(std::false_type{}, std::false_type{}, std::true_type{});
+        else if (R && !GELU) finish_direct(std::true_type{}, std::false_type{}, std::false_type{});
+        else finish_direct(std::false_type{}, std::false_type{}, std::false_type{});
     } else
 #pragma unroll
     for (int jc = 0; jc < FM / JC; ++jc) {
@@ -774,16 +820,24 @@ static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
     const int64_t blocks = (int64_t)g.tiles_m * g.tiles_n * g.nbatch;
     if (blocks > 0x7fffffffLL) return IBERT_ERR_SHAPE;
     g.xcd_chunk = (blocks % 8 == 0 && blocks >= 16) ? (int32_t)(blocks / 8) : 0;
-    constexpr size_t lds_bytes = EpiLayout<BM, BN, BK, (DMA ? RING : 2)>::LDS_BYTES;
-    static_assert(lds_bytes <= 163840, "LDS budget");
+    constexpr size_t lds_tile = EpiLayout<BM, BN, BK, (DMA ? RING : 2)>::LDS_BYTES;
+    static_assert(lds_tile <= 163840, "LDS budget");
+    size_t lds_bytes = lds_tile;
+    if (GELU) {
+        // the GELU table rides behind the tile's LDS if it fits the CU's 160 KB (and, for tiles that share a CU,
+        // stays small enough not to cost a resident workgroup)
+        const size_t room = lds_tile >= 81920 ? 160000 - lds_tile : (163840 / 2 - lds_tile);
+        if (g.gelu_lut_n > 0 && (size_t)g.gelu_lut_n <= room) lds_bytes += ((size_t)g.gelu_lut_n + 255) & ~(size_t)255;
+        else g.gelu_lut_n = 0;
+    }
 #define IBERT_GEMM_LAUNCH(I8_, KT_)                                                                       \
     do {                                                                                                  \
         auto kern = gemm_nt_mfma_kernel<BM, BN, BK, RING, I8_, KT_, TW, DMA, GELU && I8_>;                    \
-        static bool attr_done = false;                                                                    \
-        if (!attr_done) {                                                                                 \
+        static size_t attr_bytes = 0;                                                                     \
+        if (lds_bytes > attr_bytes) {                                                                     \
             IBERT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                      \
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes)); \
-            attr_done = true;                                                                             \
+            attr_bytes = lds_bytes;                                                                       \
         }                                                                                                 \
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(GEMM_THREADS), lds_bytes, stream, g);       \
     } while (0)
@@ -832,6 +886,42 @@ static int launch_tail(GemmArgs& g, bool i8, hipStream_t stream)
     IBERT_LAUNCH_CHECK("gemm_nt_mfma_kernel");
     g_last_kernel = i8 ? "gemm_nt_mfma_kernel<128, 128, 128, 2, true, 2, false>" : "gemm_nt_mfma_kernel<128, 128, 128, 2, false, 2, false>";
     return IBERT_OK;
+}
+
+// GELU with its requantization, on the host (the arithmetic of gelu_one in 64 bits; the preconditions keep every
+// value inside 32).  Used only to find where the function saturates.
+static int32_t gelu_host(int64_t q, const ibert_gelu_params& p)
+{
+    q = q < -p.q_max ? -p.q_max : (q > p.q_max ? p.q_max : q);
+    int64_t u = q < 0 ? -q : q;
+    u = u > -(int64_t)p.q_b ? -(int64_t)p.q_b : u;
+    const int64_t v = u + p.q_b, poly = v * v + p.q_c;
+    const int64_t erf = q < 0 ? -poly : (q == 0 ? 0 : poly);
+    const int64_t t = q * (erf + p.q_1);
+    const int sh = p.out.s;
+    const __int128 prod = (__int128)t * p.out.m + (sh > 0 ? ((__int128)1 << (sh - 1)) : 0);
+    const int64_t y = (int64_t)(prod >> sh);
+    return (int32_t)(y < -127 ? -127 : (y > 127 ? 127 : y));
+}
+
+// The interval [lo, lo + n) outside of which GELU-with-requantization is constant on [-q_max, q_max]: at and below
+// q_b the polynomial argument is clipped, erf = -q_c, and with q_1 = q_c (c = 1 in Eq. 8-9) the product is zero;
+// at and above -q_b the product is linear in q, so the clamped output is monotone and constant from its first
+// saturated value on.  n = 0 when the parameters do not have that shape.
+static void gelu_table_range(const ibert_gelu_params& p, int32_t* lo, int32_t* n)
+{
+    *lo = 0; *n = 0;
+    if (p.q_1 != p.q_c || p.q_b >= 0 || p.q_max < -(int64_t)p.q_b) return;
+    const int32_t top = gelu_host(p.q_max, p);
+    int64_t a = -(int64_t)p.q_b, b = p.q_max;                     // first q in [a, b] with the value of q_max
+    while (a < b) {
+        const int64_t mid = a + (b - a) / 2;
+        if (gelu_host(mid, p) == top) b = mid; else a = mid + 1;
+    }
+    const int64_t count = a - p.q_b + 1;
+    if (count > (1 << 17)) return;
+    *lo = p.q_b;
+    *n = (int32_t)count;
 }
 
 // The direct-to-LDS loader handles whole tiles only, with row offsets that fit its 32-bit lane offsets.
@@ -894,12 +984,15 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
     const bool i8 = d.out_dtype == IBERT_I8;
     g.gelu_fast = 0;
     g.gelu = GeluConst{0, 0, 0, 0, 0, 0};
+    g.gelu_lut_lo = g.gelu_lut_n = 0;
     if (gelu) {
         if (!i8 || residual || d.out_clamp != gelu->q_max) return IBERT_ERR_NOT_IMPLEMENTED;
         g.gelu = GeluConst{gelu->q_b, gelu->q_c, gelu->q_1, gelu->q_max, gelu->out.m, gelu->out.s};
         g.gelu_fast = gelu_fast_ok(*gelu) ? 1 : 0;
+        gelu_table_range(*gelu, &g.gelu_lut_lo, &g.gelu_lut_n);
     }
     g.c_vec = aligned(C, i8 ? 4 : 16) && d.ldc % 4 == 0 && d.strideC_outer % 4 == 0 && d.strideC_inner % 4 == 0;
+    g.c_vec16 = i8 && aligned(C, 16) && d.ldc % 16 == 0 && d.strideC_outer % 16 == 0 && d.strideC_inner % 16 == 0;
     g.r_vec = residual && aligned(residual, 16) && d.ldr % 16 == 0 && d.strideR_outer % 16 == 0 && d.strideR_inner % 16 == 0;
 
     const bool fast = d.trans_w == 0 && d.K > 0 && aligned(A, 16) && aligned(W, 16) && d.lda % 16 == 0 && d.ldw % 16 == 0 &&
@@ -913,7 +1006,6 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
             switch (cfg) {
                 case 6: if (dma_ok(d, 256, 192)) return launch_mfma<256, 192, 128, 2, false, true, true>(g, i8, stream); break;
                 case 7: if (dma_ok(d, 128, 128)) return launch_mfma<128, 128, 128, 2, false, true, true>(g, i8, stream); break;
-                case 8: if (dma_ok(d, 256, 256)) return launch_mfma<256, 256, 128, 2, false, true, true>(g, i8, stream); break;
                 case 9: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 2, false, true, true>(g, i8, stream); break;
                 case 10: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 2, false, true, true>(g, i8, stream); break;
                 default: break;

@@ -314,7 +314,7 @@ def test_gemm_direct_to_lds_tiles(G, cfg, M, N, K):
         B.lib().ibert_gemm_config_override(-1)
 
 
-@pytest.mark.parametrize("cfg,M,N,K", [(-1, 4096, 3072, 768), (6, 512, 384, 256), (7, 256, 384, 128), (8, 256, 512, 384),
+@pytest.mark.parametrize("cfg,M,N,K", [(-1, 4096, 3072, 768), (6, 512, 384, 256), (7, 256, 384, 128), (10, 256, 384, 384),
                                        (9, 384, 288, 256), (10, 512, 256, 128), (-1, 100, 72, 48), (-1, 130, 64, 128)])
 @pytest.mark.parametrize("S_in,S_out", [(2.0 ** -7, 8.0 / 127), (0.011, 0.02)])
 def test_gemm_gelu_equals_matmul_then_gelu(G, cfg, M, N, K, S_in, S_out):
@@ -344,6 +344,39 @@ def test_gemm_gelu_equals_matmul_then_gelu(G, cfg, M, N, K, S_in, S_out):
         _eq(scratch, f.reshape(-1), "scratch holds the MatMul result")
         with pytest.raises(B.IbertError):
             G.gemm_gelu(kw, A, W, b, mult, shift, gp, M * N, with_scratch=False)
+
+
+@pytest.mark.parametrize("cfg", [6, 9])
+@pytest.mark.parametrize("S_in,S_out", [(2.0 ** -7, 8.0 / 127), (2.0 ** -6, 0.748), (0.011, 0.02)])
+def test_gemm_gelu_every_gelu_input_value(G, cfg, S_in, S_out):
+    # the fused epilogue reads GELU from a table outside of which the function is constant: drive the MatMul so that
+    # its requantized outputs walk through every integer from below -q_max to above +q_max
+    from paper_2101_01321_amd import binding as B
+    gp, op = B.ibert_gelu_params_from_scale(S_in, S_out), P.gelu_params(S_in, S_out)
+    M, N, K = 768, 384, 128
+    A = np.zeros((M, K), np.int8)
+    W = np.zeros((N, K), np.int8)
+    W[:, 0] = 127
+    W[:, 1] = 127
+    A[:, 0] = np.arange(M) % 255 - 127                      # acc = 127 a0 + 16129 c + bias, c in {-1, 0, 1}
+    A[:, 1] = 127 * np.where(np.arange(M) < 765, np.arange(M) // 255 - 1, 0)
+    bias = (np.arange(N) % 128 - 64).astype(np.int32)       # fills the gaps of 127 between products
+    mult = np.full(N, 2 ** 30, np.int32)
+    shift = np.full(N, 30, np.int32)                        # DY(acc; 2^30, 30) = acc
+    kw = dict(M=M, N=N, K=K, batch_outer=1, batch_inner=1, lda=K, ldw=K, ldc=N, per_channel=1, out_dtype=I8, out_clamp=5)
+    f = oracle.gemm_requant(GemmSpec(M, N, K, per_channel=1, dy=(1, 0), out_dtype=I32, out_clamp=gp.q_max), A, W, bias, mult, shift, None)
+    hit = np.unique(f)
+    span = min(gp.q_max, 32000)
+    assert hit.min() <= -span and hit.max() >= span and np.all(np.diff(hit) == 1)      # every integer in between
+    want = oracle.gelu(f.reshape(-1), op)
+    B.lib().ibert_gemm_config_override(cfg)
+    try:
+        G.say("gemm+gelu sweep cfg=%d S_in=%g" % (cfg, S_in))
+        got, scratch = G.gemm_gelu(kw, A, W, bias, mult, shift, gp, M * N)
+    finally:
+        B.lib().ibert_gemm_config_override(-1)
+    assert np.all(scratch == -5)                             # one kernel
+    _eq(got, want, "gemm+gelu sweep")
 
 
 def test_gemm_base_shapes_full(G):
