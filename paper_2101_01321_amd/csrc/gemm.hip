@@ -2,14 +2,17 @@
 // optional residual and clamp fused into the epilogue.
 //
 // Fast path (W is [N,K], rows 16-byte aligned): LDS-staged tiles feeding v_mfma_i32_16x16x64_i8.
-//   * The weight rows are fed as the MFMA "A" operand and the activation rows as the "B" operand, so
-//     that each lane ends up with four consecutive output channels n of one token m: the epilogue
-//     packs them into one dword (INT8 out) or one 16-byte store (INT32 out).
+//   * The weight rows are fed as the first MFMA operand and the activation rows as the second, so that
+//     each lane ends up with four consecutive output channels n of one token m: the epilogue packs
+//     them into one dword (INT8 out) or one 16-byte store (INT32 out).
 //   * Both operands are K-contiguous in memory; a lane's MFMA operand is 16 consecutive K bytes, one
-//     ds_read_b128.  LDS rows are 64 bytes with the 16-byte chunk index XOR-swizzled by the row so that
-//     the 16 rows a quarter-wave reads in one instruction fall into distinct banks.
+//     ds_read_b128.  LDS rows are BK bytes (64 or 128) with the 16-byte chunk index XOR-swizzled by the row
+//     so that the rows a group of lanes reads in one cycle fall into distinct banks.
+//   * Two tile loaders: global memory straight into LDS (whole tiles, K a multiple of 128), or through a ring
+//     of registers (everything else that is 16-byte aligned, and W given as [K,N] with aligned rows).
 //   * Integer accumulation is exact, so any consistent K order gives the oracle's bits.
-// Generic path (W is [K,N], or unaligned operands): one output element per lane, byte loads.
+//   * The epilogue can also apply integer GELU (Alg. 2) to its own INT8 output.
+// Generic path (unaligned operands): one output element per lane, byte loads.
 #include <cstdio>
 #include <type_traits>
 
@@ -65,11 +68,10 @@ __device__ __forceinline__ int32_t finish(int32_t acc, int32_t m, int32_t s, boo
 //
 // One workgroup = 4 wavefronts (2 x 2) computes a BM x BN tile; each wavefront owns (BM/2) x (BN/2),
 // i.e. (BM/32) x (BN/32) MFMA blocks of 16x16, accumulators in registers.
-// K is walked in steps of BK bytes.  Global loads for step s are issued R steps ahead into a ring of
-// register slots (the grid is about one workgroup per CU, so latency is hidden by depth, not by
-// occupancy); one step before use they are written to the other half of a double-buffered LDS tile.
-// Inside a step the operand fragments of the next 64-wide K slice are read from LDS while the
-// MFMAs of the current slice issue.
+// K is walked in steps of BK bytes.  Register-ring loader: global loads for step s are issued RING steps
+// ahead into a ring of register slots; one step before use they are written to the other half of a
+// double-buffered LDS tile; inside a step the operand fragments of the next 64-wide K slice are read from
+// LDS while the MFMAs of the current slice issue.  The direct-to-LDS loader is described at the kernel.
 // ---------------------------------------------------------------------------------------------
 constexpr int GEMM_THREADS = 256;
 
@@ -789,22 +791,22 @@ int check_gemm(const ibert_gemm_desc& d, const void* A, const void* W, const voi
 // Tile configurations of the MFMA kernel.
 struct GemmConfig {
     int bm, bn, bk, ring;
-    double eff;           // fraction of the MFMA rate the main loop sustains (measured)
+    bool direct;          // direct-to-LDS loader (whole tiles only; ring = LDS stages) or register ring
 };
-static const GemmConfig kConfigs[] = {
-    {256, 192, 128, 2, 0.60},
-    {128, 128, 128, 2, 0.45},
-    {128, 128, 64, 2, 0.45},
-    {64, 64, 128, 3, 0.30},
-    {64, 128, 64, 3, 0.35},
-    {128, 96, 128, 2, 0.50},
-    {256, 192, 128, 2, 0.70},       // from here on: direct-to-LDS loader (whole tiles only), ring = LDS stages
-    {128, 128, 128, 2, 0.60},
-    {256, 256, 128, 2, 0.75},
-    {128, 96, 128, 2, 0.45},
-    {256, 128, 128, 2, 0.60},
-    {128, 96, 128, 3, 0.55},
-    {128, 128, 128, 3, 0.60},
+static const GemmConfig kConfigs[] = {      // index = configuration number of ibert_gemm_config_override
+    {256, 192, 128, 2, false},
+    {128, 128, 128, 2, false},
+    {128, 128, 64, 2, false},
+    {64, 64, 128, 3, false},
+    {64, 128, 64, 3, false},
+    {128, 96, 128, 2, false},
+    {256, 192, 128, 2, true},
+    {128, 128, 128, 2, true},
+    {256, 256, 128, 2, true},
+    {128, 96, 128, 2, true},
+    {256, 128, 128, 2, true},
+    {128, 96, 128, 3, true},
+    {128, 128, 128, 3, true},
 };
 constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 #ifdef IBERT_KERNEL_TIMING
