@@ -346,6 +346,35 @@ def test_gemm_gelu_equals_matmul_then_gelu(G, cfg, M, N, K, S_in, S_out):
             G.gemm_gelu(kw, A, W, b, mult, shift, gp, M * N, with_scratch=False)
 
 
+@pytest.mark.parametrize("cfg,M,N,K", [(6, 256, 192, 256), (9, 128, 192, 384), (7, 128, 128, 128), (11, 128, 96, 640)])
+def test_gemm_direct_to_lds_tiles_batched(G, cfg, M, N, K):
+    # whole-tile configurations on a batched problem: 2 x 3 batch elements, W shared along the outer batch axis,
+    # odd workgroup counts (no XCD run) and even ones
+    from paper_2101_01321_amd import binding as B
+    rng = np.random.default_rng(cfg * 1000 + M + K)
+    bo, bi = 2, 3
+    A = rng.integers(-127, 128, size=(bo * bi, M, K), dtype=np.int8)
+    W = rng.integers(-127, 128, size=(bi, N, K), dtype=np.int8)
+    R = rng.integers(-127, 128, size=(bo * bi, M, N), dtype=np.int8)
+    B.lib().ibert_gemm_config_override(cfg)
+    try:
+        for od, dy, res in ((I8, (1518500250, 44), None), (I32, (1518500250, 38), R)):
+            kw = dict(M=M, N=N, K=K, batch_outer=bo, batch_inner=bi, lda=K, ldw=K, ldc=N, ldr=N,
+                      strideA_outer=bi * M * K, strideA_inner=M * K, strideW_outer=0, strideW_inner=N * K,
+                      strideC_outer=bi * M * N, strideC_inner=M * N, strideR_outer=bi * M * N, strideR_inner=M * N,
+                      per_channel=0, requant=dy, out_dtype=od, out_clamp=127 if od == I8 else 32767, residual_dy=(1717986918, 33))
+            G.say("gemm direct-to-LDS batched cfg=%d M=%d N=%d K=%d out=%d" % (cfg, M, N, K, od))
+            got = G.gemm(kw, A, W, residual=res, out_elems=bo * bi * M * N)
+            spec = GemmSpec(M, N, K, lda=K, ldw=K, ldc=N, ldr=N, batch_outer=bo, batch_inner=bi, sA=(bi * M * K, M * K),
+                            sW=(0, N * K), sC=(bi * M * N, M * N), sR=(bi * M * N, M * N), per_channel=0, dy=dy, out_dtype=od,
+                            out_clamp=127 if od == I8 else 32767, res_dy=(1717986918, 33))
+            want = oracle.gemm_requant(spec, A.reshape(-1), W.reshape(-1), None, None, None,
+                                       None if res is None else res.reshape(-1), out_elems=bo * bi * M * N)
+            _eq(got, want, "batched direct-to-LDS gemm")
+    finally:
+        B.lib().ibert_gemm_config_override(-1)
+
+
 @pytest.mark.parametrize("cfg", [6, 9])
 @pytest.mark.parametrize("S_in,S_out", [(2.0 ** -7, 8.0 / 127), (2.0 ** -6, 0.748), (0.011, 0.02)])
 def test_gemm_gelu_every_gelu_input_value(G, cfg, S_in, S_out):
