@@ -75,15 +75,16 @@ __device__ __forceinline__ int32_t finish(int32_t acc, int32_t m, int32_t s, boo
 // ---------------------------------------------------------------------------------------------
 constexpr int GEMM_THREADS = 256;
 
-// XOR swizzle of the 16-byte chunk index by the LDS row, chosen so that the 16 rows a quarter-wave
-// reads (same logical chunk) and the rows a quarter-wave writes land on distinct 16-byte bank groups,
-// for both a 128-byte and a 256-byte bank window.  CPR = chunks per row.
+// XOR swizzle of the 16-byte chunk index by the LDS row, so that the 16 rows whose same logical chunk the lanes
+// of an operand read fetch (row stride = BK bytes) land on distinct 16-byte bank groups: chunk ^ row for 128-byte
+// rows, chunk ^ (row / 2) for 64-byte rows (two rows share a 128-byte bank window).  Measured on the LDS of this
+// chip: 128 B/clk for these, 96 with a further row bit folded in, 64 without a swizzle.  CPR = chunks per row.
 template <int CPR>
 __device__ __forceinline__ int swz(int row)
 {
     if (CPR == 16) return row & 15;
-    if (CPR == 8) return (row & 7) ^ ((row >> 3) & 1);
-    return ((row >> 1) & 3) ^ ((row >> 3) & 1);
+    if (CPR == 8) return row & 7;
+    return (row >> 1) & 3;
 }
 
 // One 16-byte chunk of a tile row.  p points at the chunk (column k of the row).
@@ -295,7 +296,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
         static_assert(NR == NL && (NMF + SPC - 1) / SPC >= NR, "one read and one load per slot");
         const int wv = __builtin_amdgcn_readfirstlane(wave);
         const int lr8 = lane >> 3, lp = lane & 7;
-        const int lsw = lr8 ^ (wv & 1);                               // swz<8> of the lane's row (block index parity = wave parity)
+        const int lsw = lr8;                                          // swz<8> of the lane's row (blocks are 8 rows)
         const uint32_t voff_a = (uint32_t)lr8 * (uint32_t)g.lda + (uint32_t)((lp ^ lsw) << 4);
         const uint32_t voff_w = (uint32_t)lr8 * (uint32_t)g.ldw + (uint32_t)((lp ^ lsw) << 4);
         const int8_t* ga = A + (int64_t)(m0 + wv * 8) * g.lda;
