@@ -115,6 +115,14 @@ def lib():
         L.orc_encoder_layer.restype = C.c_int
         L.orc_encoder_layer.argtypes = [C.POINTER(LayerWeightsT), C.POINTER(LayerQuantT), _P, _P,
                                         C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(LayerDumpT)]
+        L.orc_encoder_layer_masked.restype = C.c_int
+        L.orc_encoder_layer_masked.argtypes = [C.POINTER(LayerWeightsT), C.POINTER(LayerQuantT), _P, _P,
+                                               C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _P, C.POINTER(LayerDumpT)]
+        L.orc_mask_scores.restype = C.c_int
+        L.orc_mask_scores.argtypes = [_P, C.c_int, C.c_int, C.c_int, _P]
+        L.orc_embedding.restype = C.c_int
+        L.orc_embedding.argtypes = [_P, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, _P, _P, C.c_int32, C.c_int32,
+                                    C.c_int32, C.c_int32, _P, _P, C.c_int, _P, _P]
         L.orc_num_threads.restype = C.c_int
         _lib = L
     return _lib
@@ -282,8 +290,9 @@ _W_DTYPES = {"w_qkv": np.int8, "w_o": np.int8, "w_1": np.int8, "w_2": np.int8}
 
 
 def encoder_layer(weights: dict, quant: LayerQuantT, x: np.ndarray, batch: int, seq: int, hidden: int,
-                  heads: int, ffn: int, dump: bool = False):
-    """weights: dict field -> numpy array (see LayerWeightsT).  Returns y, or (y, dict of intermediates)."""
+                  heads: int, ffn: int, dump: bool = False, key_lens=None):
+    """weights: dict field -> numpy array (see LayerWeightsT).  Returns y, or (y, dict of intermediates).
+    key_lens: optional int32 [batch], keys at or past it are padding (orc_mask_scores)."""
     keep = {}
     w = LayerWeightsT()
     for f in _W_FIELDS:
@@ -304,10 +313,34 @@ def encoder_layer(weights: dict, quant: LayerQuantT, x: np.ndarray, batch: int, 
         for f in _D_FIELDS:
             inter[f] = np.zeros(shapes[f][0], dtype=shapes[f][1])
             setattr(d, f, inter[f].ctypes.data)
-    rc = lib().orc_encoder_layer(C.byref(w), C.byref(quant), _ptr(x), _ptr(y), batch, seq, hidden, heads, ffn,
-                                 C.byref(d) if dump else None)
+    kl = None if key_lens is None else _arr(key_lens, np.int32)
+    assert kl is None or kl.size == batch
+    rc = lib().orc_encoder_layer_masked(C.byref(w), C.byref(quant), _ptr(x), _ptr(y), batch, seq, hidden, heads, ffn,
+                                        None if kl is None else _ptr(kl), C.byref(d) if dump else None)
     _chk(rc, "encoder_layer")
     return (y, inter) if dump else y
+
+
+def mask_scores(scores: np.ndarray, batch: int, heads: int, seq: int, key_lens) -> np.ndarray:
+    """Copy of scores [batch*heads, seq, seq] with the padded keys set to the masked logit."""
+    out = _arr(scores, np.int32).copy()
+    kl = _arr(key_lens, np.int32)
+    _chk(lib().orc_mask_scores(_ptr(out), batch, heads, seq, _ptr(kl)), "mask_scores")
+    return out
+
+
+def embedding(ids, seq: int, tok, pos, tok_dy, pos_dy, gamma_q, beta_q, ln_shift: int, return_sum: bool = False):
+    """INT8 embedding + integer LayerNorm.  ids int32 [T]; tok int8 [V,H]; pos int8 [P,H]; *_dy = (m, s)."""
+    ids = _arr(ids, np.int32)
+    tok, pos = _arr(tok, np.int8), _arr(pos, np.int8)
+    gq, bq = _arr(gamma_q, np.int32), _arr(beta_q, np.int32)
+    T, H = ids.size, tok.shape[1]
+    y = np.zeros((T, H), dtype=np.int8)
+    r = np.zeros((T, H), dtype=np.int32)
+    rc = lib().orc_embedding(_ptr(ids), T, seq, H, tok.shape[0], pos.shape[0], _ptr(tok), _ptr(pos), tok_dy[0], tok_dy[1],
+                             pos_dy[0], pos_dy[1], _ptr(gq), _ptr(bq), ln_shift, _ptr(r), _ptr(y))
+    _chk(rc, "embedding")
+    return (y, r) if return_sum else y
 
 
 def num_threads() -> int:

@@ -31,6 +31,14 @@
  *   orc_layernorm        Sec. 3.6, Eq. 15 + Alg. 4.
  *   orc_encoder_layer    Fig. 1 (right) attention block + the rest of a
  *                        post-LN encoder layer (Sec. 4.1: RoBERTa).
+ *   orc_mask_scores      padded keys of a batch of sequences (the paper does
+ *                        not mention padding; reading: a masked key has the
+ *                        logit "minus infinity", i.e. INT32_MIN, so its
+ *                        integer exponential is exactly zero).
+ *   orc_embedding        INT8 embedding (Sec. 1 contribution 3, App. C.1: "the
+ *                        Embedding layer is kept at INT8 precision"; the sum
+ *                        of the tables and the LayerNorm after it are not
+ *                        spelled out; reading below).
  *
  * Parity pins live in tests/test_oracle_*.py.
  */
@@ -459,9 +467,27 @@ typedef struct {
     int32_t* f1; int8_t* g; int32_t* r2;
 } orc_layer_dump_t;
 
-int orc_encoder_layer(const orc_layer_weights_t* w, const orc_layer_quant_t* q,
-                      const int8_t* x, int8_t* y, int batch, int seq, int hidden, int heads, int ffn,
-                      const orc_layer_dump_t* dump)
+/* Keys at positions >= key_lens[b] of sequence b are padding: their logits become INT32_MIN before the
+ * Softmax (for every head and every query), so that d = max - q is at least 2^31 - 2^20 or so, z >= 31
+ * and the integer exponential is exactly 0 (Alg. 3; the maximum is taken over the row after masking, and
+ * 1 <= key_lens[b] <= L keeps a real key in it).  scores: [B*heads, L, L]. */
+int orc_mask_scores(int32_t* scores, int batch, int heads, int seq, const int32_t* key_lens)
+{
+    if (!scores || !key_lens || batch < 0 || heads < 1 || seq < 1) return ORC_E_ARG;
+    for (int b = 0; b < batch; ++b) {
+        if (key_lens[b] < 1 || key_lens[b] > seq) return ORC_E_ARG;
+        for (int h = 0; h < heads; ++h)
+            for (int i = 0; i < seq; ++i) {
+                int32_t* row = scores + (((int64_t)b * heads + h) * seq + i) * seq;
+                for (int j = key_lens[b]; j < seq; ++j) row[j] = (int32_t)I32_MIN;
+            }
+    }
+    return ORC_OK;
+}
+
+int orc_encoder_layer_masked(const orc_layer_weights_t* w, const orc_layer_quant_t* q,
+                             const int8_t* x, int8_t* y, int batch, int seq, int hidden, int heads, int ffn,
+                             const int32_t* key_lens, const orc_layer_dump_t* dump)
 {
     if (!w || !q || !x || !y) return ORC_E_ARG;
     if (batch < 1 || seq < 1 || hidden < 1 || heads < 1 || ffn < 1 || hidden % heads) return ORC_E_ARG;
@@ -495,6 +521,9 @@ int orc_encoder_layer(const orc_layer_weights_t* w, const orc_layer_quant_t* q,
     d.sA_o = L * 3 * H; d.sA_i = dh; d.sW_o = L * 3 * H; d.sW_i = dh; d.sC_o = nh * L * L; d.sC_i = L * L;
     d.per_channel = 0; d.dy_m = q->scores_m; d.dy_s = q->scores_s; d.out_dtype = ORC_I32; d.out_clamp = 2147483647;
     RUN(orc_gemm_requant(&d, qkv, qkv + H, NULL, NULL, NULL, NULL, sc));
+
+    /* (padded keys, if any) */
+    if (key_lens) RUN(orc_mask_scores(sc, batch, heads, seq, key_lens));
 
     /* 3: softmax over the last axis */
     RUN(orc_softmax(sc, pr, B * nh * L, (int)L, L, L, &q->softmax));
@@ -550,6 +579,46 @@ int orc_encoder_layer(const orc_layer_weights_t* w, const orc_layer_quant_t* q,
     }
 done:
     free(qkv); free(sc); free(pr); free(ctx); free(r1); free(h1); free(f1); free(g); free(r2);
+    return rc;
+}
+
+int orc_encoder_layer(const orc_layer_weights_t* w, const orc_layer_quant_t* q,
+                      const int8_t* x, int8_t* y, int batch, int seq, int hidden, int heads, int ffn,
+                      const orc_layer_dump_t* dump)
+{
+    return orc_encoder_layer_masked(w, q, x, y, batch, seq, hidden, heads, ffn, NULL, dump);
+}
+
+/* ------------------------------------------------------------------------- */
+/* INT8 embedding.  Reading (the paper only says the layer is kept at INT8):   */
+/*   r[t][c] = clamp( DY(tok[id_t][c]; tok_dy) + DY(pos[t mod seq][c]; pos_dy), +-(2^15 - 1) )       */
+/*   y[t]    = integer LayerNorm of r[t] (Sec. 3.6), INT8                                           */
+/* i.e. both INT8 tables are brought to one INT32 scale, the input scale of the LayerNorm, exactly as   */
+/* a residual is added in the layer; token ids outside [0, vocab) are clamped into it (data never     */
+/* faults).  The position of token t is t mod seq (every sequence starts at position 0).              */
+/* r_out (optional) receives r.                                                                       */
+/* ------------------------------------------------------------------------- */
+int orc_embedding(const int32_t* ids, int64_t tokens, int seq, int hidden, int vocab, int max_pos,
+                  const int8_t* tok, const int8_t* pos, int32_t tok_m, int32_t tok_s, int32_t pos_m, int32_t pos_s,
+                  const int32_t* gamma_q, const int32_t* beta_q, int ln_shift, int32_t* r_out, int8_t* y)
+{
+    if (!ids || !tok || !pos || !gamma_q || !beta_q || !y) return ORC_E_ARG;
+    if (tokens < 0 || seq < 1 || hidden < 1 || vocab < 1 || max_pos < seq) return ORC_E_ARG;
+    if (!dyadic_ok(tok_s) || !dyadic_ok(pos_s)) return ORC_E_PARAM;
+    int32_t* r = (int32_t*)malloc(sizeof(int32_t) * (size_t)(tokens * hidden + 1));
+    if (!r) return ORC_E_NOMEM;
+    for (int64_t t = 0; t < tokens; ++t) {
+        int64_t id = ids[t];
+        id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+        const int64_t p = t % seq;
+        for (int c = 0; c < hidden; ++c) {
+            const int64_t v = orc_dyadic(tok[id * hidden + c], tok_m, tok_s) + orc_dyadic(pos[p * hidden + c], pos_m, pos_s);
+            r[t * hidden + c] = (int32_t)clamp64(v, -32767, 32767);
+        }
+    }
+    if (r_out) memcpy(r_out, r, sizeof(int32_t) * (size_t)(tokens * hidden));
+    const int rc = orc_layernorm(r, y, tokens, hidden, hidden, hidden, gamma_q, beta_q, ln_shift);
+    free(r);
     return rc;
 }
 

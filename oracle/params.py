@@ -99,6 +99,14 @@ def layernorm_params(gamma, beta, S_out: float):
     raise ValueError("no LayerNorm shift satisfies the range preconditions")
 
 
+def embedding_params(emb: dict, S_out: float):
+    """Integer constants of the INT8 embedding: the two table scales are brought to the LayerNorm input scale S_r,
+    tok_dy = dyadic(S_tok / S_r), pos_dy = dyadic(S_pos / S_r); LayerNorm constants as in layernorm_params.
+    Returns (tok_dy, pos_dy, gamma_q, beta_q, shift)."""
+    gq, bq, s = layernorm_params(emb["gamma"], emb["beta"], S_out)
+    return dyadic_from_double(emb["S_tok"] / emb["S_r"]), dyadic_from_double(emb["S_pos"] / emb["S_r"]), gq, bq, s
+
+
 def layer_params(raw: dict, sc: dict, hidden: int, heads: int):
     """Integer parameters of one encoder layer from raw synthetic weights and static scales.
 

@@ -175,3 +175,34 @@ def gemm_operands(M: int, N: int, K: int, seed: int = SEED, layer: int = 0):
     A = r.integers(-127, 128, size=(M, K), dtype=np.int8)
     W, sw, b = _linear(r, N, K)
     return A, W, sw, b
+
+
+def embedding_raw(hidden: int, vocab: int, max_pos: int, seed: int = SEED):
+    """Synthetic embedding tables (stand-ins for trained ones): token table N(0, 0.05), position table N(0, 0.02),
+    each symmetric INT8 with its own scale max|.|/127; LayerNorm gamma ~ N(1, 0.1), beta ~ N(0, 0.1); the INT32 sum is
+    held at the power-of-two scale S_r = 2^-12 (|sum| stays far below 2^15 - 1 for these tables).
+    Returns dict(tok, S_tok, pos, S_pos, gamma, beta, S_r)."""
+    rng = np.random.default_rng(seed + 7919)
+    tok_f = rng.normal(0.0, 0.05, size=(vocab, hidden))
+    pos_f = rng.normal(0.0, 0.02, size=(max_pos, hidden))
+    S_tok, S_pos = float(np.max(np.abs(tok_f)) / 127), float(np.max(np.abs(pos_f)) / 127)
+    tok = np.clip(np.rint(tok_f / S_tok), -127, 127).astype(np.int8)
+    pos = np.clip(np.rint(pos_f / S_pos), -127, 127).astype(np.int8)
+    gamma = rng.normal(1.0, 0.1, size=hidden)
+    beta = rng.normal(0.0, 0.1, size=hidden)
+    return dict(tok=tok, S_tok=S_tok, pos=pos, S_pos=S_pos, gamma=gamma, beta=beta, S_r=2.0 ** -12)
+
+
+def token_ids(tokens: int, vocab: int, seed: int = SEED) -> np.ndarray:
+    """Token ids with a Zipf-like skew (frequent ids repeat, as in text), int32 [tokens]."""
+    rng = np.random.default_rng(seed + 104729)
+    z = rng.zipf(1.3, size=tokens)
+    return ((z - 1) % vocab).astype(np.int32)
+
+
+def key_lengths(batch: int, seq: int, seed: int = SEED) -> np.ndarray:
+    """Valid lengths of a padded batch: uniform in [seq/4, seq], the longest sequence full; int32 [batch]."""
+    rng = np.random.default_rng(seed + 15485863)
+    lens = rng.integers(max(1, seq // 4), seq + 1, size=batch).astype(np.int32)
+    lens[0] = seq
+    return lens

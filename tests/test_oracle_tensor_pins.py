@@ -293,3 +293,77 @@ def test_encoder_layer_each_step_tracks_its_float_counterpart(cfg):
     assert np.array_equal(oracle.softmax(d["scores"], q.softmax), d["probs"])
     assert np.array_equal(oracle.gelu(d["f1"], q.gelu), d["g"])
     assert np.array_equal(oracle.layernorm(d["r2"], w["ln2_gamma_q"], w["ln2_beta_q"], q.ln2_shift), y)
+
+
+# ------------------------------------------------------------------ padded keys
+def _masked_case():
+    cfg = synth.EncoderConfig("masked", 128, 2, 256, 48, 3, 1)
+    x_q, S_x, _ = synth.input_activations(cfg)
+    sc = synth.model_scales(cfg, S_x)
+    w, q = P.layer_params(synth.layer_raw(cfg, 0), sc[0], cfg.hidden, cfg.heads)
+    return cfg, x_q, w, q
+
+
+def test_masked_keys_equal_a_shorter_sequence():
+    # A sequence padded to L with its keys masked must give, on its valid tokens, exactly what the same tokens
+    # give as a sequence of their own length: nothing but the attention looks across tokens.
+    cfg, x_q, w, q = _masked_case()
+    B, L, H = cfg.batch, cfg.seq, cfg.hidden
+    lens = np.array([L, 29, 1], np.int32)
+    y = oracle.encoder_layer(w, q, x_q, B, L, H, cfg.heads, cfg.ffn, key_lens=lens).reshape(B, L, H)
+    for b, n in enumerate(lens):
+        alone = oracle.encoder_layer(w, q, x_q.reshape(B, L, H)[b, :n], 1, int(n), H, cfg.heads, cfg.ffn)
+        assert np.array_equal(y[b, :n], alone), "sequence %d" % b
+    # and masking nothing is the unmasked layer
+    full = np.full(B, L, np.int32)
+    assert np.array_equal(oracle.encoder_layer(w, q, x_q, B, L, H, cfg.heads, cfg.ffn, key_lens=full),
+                          oracle.encoder_layer(w, q, x_q, B, L, H, cfg.heads, cfg.ffn))
+
+
+def test_masked_keys_get_probability_zero_and_rows_still_sum_to_one():
+    cfg, x_q, w, q = _masked_case()
+    B, L, H, nh = cfg.batch, cfg.seq, cfg.hidden, cfg.heads
+    lens = np.array([L, 17, 40], np.int32)
+    _, d = oracle.encoder_layer(w, q, x_q, B, L, H, nh, cfg.ffn, dump=True, key_lens=lens)
+    probs = d["probs"].reshape(B, nh, L, L)
+    for b, n in enumerate(lens):
+        assert np.all(probs[b, :, :, n:] == 0)
+        assert np.all(np.abs(probs[b, :, :, :n].astype(np.int64).sum(-1) - 128) <= n // 2 + 1)   # sum of n roundings of a unit mass
+    assert np.all(d["scores"].reshape(B, nh, L, L)[1, :, :, 17:] == -2 ** 31)
+    # the mask itself: only the padded columns change
+    sc0 = RNG.integers(-50000, 50000, size=(B * nh, L, L)).astype(np.int32)
+    m = oracle.mask_scores(sc0, B, nh, L, lens).reshape(B, nh, L, L)
+    for b, n in enumerate(lens):
+        assert np.array_equal(m[b, :, :, :n], sc0.reshape(B, nh, L, L)[b, :, :, :n]) and np.all(m[b, :, :, n:] == -2 ** 31)
+    for bad in ([L, 0, 5], [L + 1, 3, 3]):
+        with pytest.raises(oracle.OracleError):
+            oracle.mask_scores(sc0, B, nh, L, np.array(bad, np.int32))
+
+
+# ------------------------------------------------------------------ INT8 embedding
+def test_embedding_vs_big_int_and_float():
+    H, V, Pmax, seq, T = 96, 50, 40, 20, 60
+    emb = synth.embedding_raw(H, V, Pmax)
+    S_out = 5.0 / 127
+    tok_dy, pos_dy, gq, bq, s = P.embedding_params(emb, S_out)
+    ids = synth.token_ids(T, V)
+    ids[:4] = [0, V - 1, -7, V + 100]                                  # the last two are clamped into the table
+    y, r = oracle.embedding(ids, seq, emb["tok"], emb["pos"], tok_dy, pos_dy, gq, bq, s, return_sum=True)
+    # the INT32 sum, element by element in Python integers
+    cid = np.clip(ids, 0, V - 1)
+    for t in (0, 1, 2, 3, 19, 20, 21, 59):
+        for c in (0, 1, H - 1):
+            a = (int(emb["tok"][cid[t], c]) * tok_dy[0] + (1 << (tok_dy[1] - 1))) >> tok_dy[1]
+            b = (int(emb["pos"][t % seq, c]) * pos_dy[0] + (1 << (pos_dy[1] - 1))) >> pos_dy[1]
+            assert r[t, c] == max(-32767, min(32767, a + b))
+    # position = t mod seq: tokens t and t + seq with the same id get the same row
+    ids2 = np.r_[np.arange(seq), np.arange(seq)].astype(np.int32) % V
+    y2 = oracle.embedding(ids2, seq, emb["tok"], emb["pos"], tok_dy, pos_dy, gq, bq, s)
+    assert np.array_equal(y2[:seq], y2[seq:])
+    # it is the LayerNorm of that sum
+    assert np.array_equal(y, oracle.layernorm(r, gq, bq, s))
+    # and tracks the float embedding: LN(tok S_tok + pos S_pos) gamma + beta
+    real = emb["tok"][cid].astype(np.float64) * emb["S_tok"] + emb["pos"][np.arange(T) % seq].astype(np.float64) * emb["S_pos"]
+    assert np.max(np.abs(r * emb["S_r"] - real)) <= emb["S_r"] * 1.0 + 1e-9           # two roundings of half a step each
+    want = np.clip(fpref.layernorm(real, emb["gamma"], emb["beta"]) / S_out, -127, 127)
+    assert np.max(np.abs(y - want)) <= 1.5
