@@ -125,6 +125,15 @@ typedef struct {
 int ibert_softmax_i(const int32_t* x, void* y, int64_t rows, int32_t cols, int64_t ldx, int64_t ldy,
                     const ibert_softmax_params* params, void* stream);
 
+/* The same over padded rows: row r has n = key_lens[r / rows_per_len] real columns (key_lens: device int32,
+ * ceil(rows / rows_per_len) entries, read by the kernel; values outside [1, cols] are clamped into it, since the
+ * host cannot see them).  The paper does not treat padding; reading: a masked logit is "minus infinity", here
+ * INT32_MIN, set before the row maximum is taken, so e_j of a masked column is 0 (unless the real logits themselves
+ * sit within 31*q_ln2 of INT32_MIN) and y_j = 0 is written for it.  rows_per_len >= 1 (IBERT_ERR_SHAPE). */
+int ibert_softmax_masked_i(const int32_t* x, void* y, int64_t rows, int32_t cols, int64_t ldx, int64_t ldy,
+                           const ibert_softmax_params* params, const int32_t* key_lens, int64_t rows_per_len,
+                           void* stream);
+
 /* ------------------------------------------------------------------------------------------------
  * ibert_gelu_i -- integer-only GELU (Alg. 2; Eq. 8-9), element-wise, followed by requantization.
  *
@@ -176,6 +185,24 @@ int ibert_gemm_i8_gelu(const ibert_gemm_desc* desc, const int8_t* A, const int8_
  * ---------------------------------------------------------------------------------------------- */
 int ibert_layernorm_i(const int32_t* x, int8_t* y, int64_t rows, int32_t C, int64_t ldx, int64_t ldy,
                       const int32_t* gamma_q, const int32_t* beta_q, int32_t shift, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * ibert_embedding_i -- the INT8 embedding that feeds the first layer (Sec. 1, third contribution; App. C.1: the
+ * embedding tables are INT8 like every other parameter).  The paper does not spell out how the looked-up rows are
+ * added and normalized; reading, for token t (its position is t mod seq):
+ *   r_c = clamp(DY(tok[id_t][c]; tok_dy) + DY(pos[t mod seq][c]; pos_dy), -(2^15-1), 2^15-1)
+ *         both tables rescaled to one INT32 scale S_r (tok_dy ~ S_tok/S_r, pos_dy ~ S_pos/S_r), summed exactly
+ *   y   = ibert_layernorm_i(r; gamma_q, beta_q, ln_shift)              one kernel, r never stored
+ * ids: device int32 [tokens], clamped into [0, vocab) by the kernel; tok: device int8 [vocab, hidden]; pos: device
+ * int8 [max_pos, hidden] with max_pos >= seq; y: device int8 [tokens, ldy]; the dyadics are host pointers.
+ * Segment (token-type) embeddings are not part of RoBERTa and not provided.
+ * Errors: IBERT_ERR_SHAPE (negative sizes, max_pos < seq, ldy < hidden), IBERT_ERR_PARAM_RANGE (shift of a dyadic
+ * outside [0, 62], hidden > 1024, ln_shift outside [1, 30]), IBERT_ERR_NULL.
+ * ---------------------------------------------------------------------------------------------- */
+int ibert_embedding_i(const int32_t* ids, const int8_t* tok, const int8_t* pos, int64_t tokens, int32_t seq,
+                      int32_t hidden, int32_t vocab, int32_t max_pos, const ibert_dyadic* tok_dy,
+                      const ibert_dyadic* pos_dy, const int32_t* gamma_q, const int32_t* beta_q, int32_t ln_shift,
+                      int8_t* y, int64_t ldy, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
  * ibert_encoder_layer_i -- one post-LN encoder layer, integer-only end to end (Fig. 1 right for the
@@ -232,6 +259,15 @@ int ibert_encoder_layer_i(const ibert_layer_weights* weights, const ibert_layer_
                           int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* The layer over padded sequences: sequence b attends to its first key_lens[b] keys only (key_lens: device int32
+ * [batch], read by the kernels, clamped into [1, seq]; see ibert_softmax_masked_i for the reading).  Every token
+ * row, padded ones included, is still computed; on the first key_lens[b] tokens of a sequence the result equals the
+ * layer run on that sequence alone at its own length.  key_lens == NULL is ibert_encoder_layer_i. */
+int ibert_encoder_layer_masked_i(const ibert_layer_weights* weights, const ibert_layer_quant* quant,
+                                 const int8_t* x, int8_t* y,
+                                 int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn,
+                                 const int32_t* key_lens, void* workspace, size_t workspace_bytes, void* stream);
+
 /* n_layers layers back to back (layer l+1 reads layer l's output); weights/quant: host arrays of
  * n_layers entries.  x is not modified; y receives the last layer's output.  The workspace needs
  * ibert_encoder_workspace_bytes() (one layer's workspace plus two ping-pong activation buffers). */
@@ -240,6 +276,10 @@ int ibert_encoder_i(const ibert_layer_weights* weights, const ibert_layer_quant*
                     const int8_t* x, int8_t* y,
                     int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn,
                     void* workspace, size_t workspace_bytes, void* stream);
+int ibert_encoder_masked_i(const ibert_layer_weights* weights, const ibert_layer_quant* quant, int32_t n_layers,
+                           const int8_t* x, int8_t* y,
+                           int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn,
+                           const int32_t* key_lens, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
  * Host-only helpers: the one place where a real number appears.  All arithmetic is IEEE binary64 in
@@ -297,6 +337,11 @@ size_t ibert_attention_scratch_bytes(int32_t batch, int32_t seq, int32_t heads);
 int ibert_attention_i(const int8_t* qkv, int8_t* ctx, int32_t batch, int32_t seq, int32_t hidden, int32_t heads,
                       const ibert_dyadic* scores_dy, const ibert_softmax_params* softmax, const ibert_dyadic* ctx_dy,
                       void* scratch, size_t scratch_bytes, void* stream);
+/* With padded sequences: key_lens as for ibert_encoder_layer_masked_i (NULL: no padding). */
+int ibert_attention_masked_i(const int8_t* qkv, int8_t* ctx, int32_t batch, int32_t seq, int32_t hidden, int32_t heads,
+                             const ibert_dyadic* scores_dy, const ibert_softmax_params* softmax,
+                             const ibert_dyadic* ctx_dy, const int32_t* key_lens, void* scratch, size_t scratch_bytes,
+                             void* stream);
 
 /* Kernel fusions inside ibert_encoder_layer_i / ibert_encoder_i (and ibert_attention_i).
  *   bit 0: steps 7 and 8 (FFN up-projection and GELU) run as one kernel where ibert_gemm_i8_gelu can do so; the

@@ -35,9 +35,9 @@
  *                        not mention padding; reading: a masked key has the
  *                        logit "minus infinity", i.e. INT32_MIN, so its
  *                        integer exponential is exactly zero).
- *   orc_embedding        INT8 embedding (Sec. 1 contribution 3, App. C.1: "the
- *                        Embedding layer is kept at INT8 precision"; the sum
- *                        of the tables and the LayerNorm after it are not
+ *   orc_embedding        INT8 embedding (Sec. 1 contribution 3, App. C.1 say
+ *                        only that the embedding tables are INT8; how the
+ *                        looked-up rows are added and normalized is not
  *                        spelled out; reading below).
  *
  * Parity pins live in tests/test_oracle_*.py.

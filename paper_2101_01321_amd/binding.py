@@ -93,6 +93,16 @@ SIGNATURES = {
     "ibert_attention_scratch_bytes": (C.c_size_t, [C.c_int32] * 3),
     "ibert_attention_i": (C.c_int, [_P, _P] + [C.c_int32] * 4 + [C.POINTER(Dyadic), C.POINTER(SoftmaxParams),
                                                                  C.POINTER(Dyadic), _P, C.c_size_t, _P]),
+    "ibert_attention_masked_i": (C.c_int, [_P, _P] + [C.c_int32] * 4 + [C.POINTER(Dyadic), C.POINTER(SoftmaxParams),
+                                                                        C.POINTER(Dyadic), _P, _P, C.c_size_t, _P]),
+    "ibert_softmax_masked_i": (C.c_int, [_P, _P, C.c_int64, C.c_int32, C.c_int64, C.c_int64, C.POINTER(SoftmaxParams), _P,
+                                         C.c_int64, _P]),
+    "ibert_embedding_i": (C.c_int, [_P, _P, _P, C.c_int64] + [C.c_int32] * 4 + [C.POINTER(Dyadic), C.POINTER(Dyadic), _P, _P,
+                                                                                 C.c_int32, _P, C.c_int64, _P]),
+    "ibert_encoder_layer_masked_i": (C.c_int, [C.POINTER(LayerWeights), C.POINTER(LayerQuant), _P, _P] + [C.c_int32] * 5 +
+                                     [_P, _P, C.c_size_t, _P]),
+    "ibert_encoder_masked_i": (C.c_int, [C.POINTER(LayerWeights), C.POINTER(LayerQuant), C.c_int32, _P, _P] +
+                               [C.c_int32] * 5 + [_P, _P, C.c_size_t, _P]),
     "ibert_softmax_i": (C.c_int, [_P, _P, C.c_int64, C.c_int32, C.c_int64, C.c_int64, C.POINTER(SoftmaxParams), _P]),
     "ibert_gelu_i": (C.c_int, [_P, _P, C.c_int64, C.POINTER(GeluParams), _P]),
     "ibert_layernorm_i": (C.c_int, [_P, _P, C.c_int64, C.c_int32, C.c_int64, C.c_int64, _P, _P, C.c_int32, _P]),
@@ -224,6 +234,27 @@ def ibert_attention_i(qkv, ctx, batch, seq, hidden, heads, scores_dy: Dyadic, so
                                  C.byref(ctx_dy), _dp(scratch), nbytes, _stream(stream)), "ibert_attention_i")
 
 
+def ibert_attention_masked_i(qkv, ctx, batch, seq, hidden, heads, scores_dy: Dyadic, softmax: SoftmaxParams, ctx_dy: Dyadic,
+                             key_lens, scratch=None, stream=None):
+    nbytes = 0 if scratch is None else scratch.numel() * scratch.element_size()
+    _chk(lib().ibert_attention_masked_i(_dp(qkv), _dp(ctx), batch, seq, hidden, heads, C.byref(scores_dy), C.byref(softmax),
+                                        C.byref(ctx_dy), _dp(key_lens), _dp(scratch), nbytes, _stream(stream)),
+         "ibert_attention_masked_i")
+
+
+def ibert_softmax_masked_i(x, y, rows: int, cols: int, ldx: int, ldy: int, params: SoftmaxParams, key_lens,
+                           rows_per_len: int, stream=None):
+    _chk(lib().ibert_softmax_masked_i(_dp(x), _dp(y), rows, cols, ldx, ldy, C.byref(params), _dp(key_lens), rows_per_len,
+                                      _stream(stream)), "ibert_softmax_masked_i")
+
+
+def ibert_embedding_i(ids, tok, pos, tokens: int, seq: int, hidden: int, vocab: int, max_pos: int, tok_dy: Dyadic,
+                      pos_dy: Dyadic, gamma_q, beta_q, ln_shift: int, y, ldy: int, stream=None):
+    _chk(lib().ibert_embedding_i(_dp(ids), _dp(tok), _dp(pos), tokens, seq, hidden, vocab, max_pos, C.byref(tok_dy),
+                                 C.byref(pos_dy), _dp(gamma_q), _dp(beta_q), ln_shift, _dp(y), ldy, _stream(stream)),
+         "ibert_embedding_i")
+
+
 def ibert_set_fusion(flags: int) -> int:
     return int(lib().ibert_set_fusion(flags))
 
@@ -262,6 +293,21 @@ def ibert_encoder_layer_i(weights: LayerWeights, quant: LayerQuant, x, y, batch,
     _chk(lib().ibert_encoder_layer_i(C.byref(weights), C.byref(quant), _dp(x), _dp(y), batch, seq, hidden, heads, ffn,
                                      _dp(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
          "ibert_encoder_layer_i")
+
+
+def ibert_encoder_layer_masked_i(weights: LayerWeights, quant: LayerQuant, x, y, batch, seq, hidden, heads, ffn, key_lens,
+                                 workspace, stream=None):
+    _chk(lib().ibert_encoder_layer_masked_i(C.byref(weights), C.byref(quant), _dp(x), _dp(y), batch, seq, hidden, heads,
+                                            ffn, _dp(key_lens), _dp(workspace),
+                                            workspace.numel() * workspace.element_size(), _stream(stream)),
+         "ibert_encoder_layer_masked_i")
+
+
+def ibert_encoder_masked_i(weights, quant, n_layers: int, x, y, batch, seq, hidden, heads, ffn, key_lens, workspace,
+                           stream=None):
+    _chk(lib().ibert_encoder_masked_i(weights, quant, n_layers, _dp(x), _dp(y), batch, seq, hidden, heads, ffn,
+                                      _dp(key_lens), _dp(workspace), workspace.numel() * workspace.element_size(),
+                                      _stream(stream)), "ibert_encoder_masked_i")
 
 
 def ibert_encoder_i(weights, quant, n_layers: int, x, y, batch, seq, hidden, heads, ffn, workspace, stream=None):

@@ -15,6 +15,8 @@
 //   * The probabilities are packed four to a dword as they are produced; the four dwords i = 4kb..4kb+3 are
 //     exactly the lane's MFMA operand for key block kb under the key order above, so P never moves.
 //   * Context: L/16 MFMAs per wavefront, requantized and stored as 4 bytes per lane.
+//   * Padded sequences: the keys from key_lens[b] on take the logit INT32_MIN before the row maximum is taken (the
+//     paper does not treat padding; this is the integer form of adding minus infinity to a masked logit).
 #include "common.h"
 #include "softmax_math.h"
 
@@ -31,6 +33,7 @@ struct AttentionArgs {
     int32_t s_m, s_s;      // scores requantization
     int32_t c_m, c_s;      // context requantization
     SoftmaxConst sm;
+    const int32_t* key_lens;   // optional [batch]: sequence b attends to its first key_lens[b] keys only
 };
 
 constexpr int ATT_DH = 64, ATT_QB = 64, ATT_THREADS = 256;
@@ -143,6 +146,16 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttentionArgs a)
         for (int r = 0; r < 4; ++r)
             sc[i][r] = RQ ? dyadic_hi(acc[r], a.s_m, s_rnd, a.s_s) : clamp_i64_to_i32(dyadic64(acc[r], a.s_m, a.s_s), 2147483647);
     }
+    if (a.key_lens) {                                      // uniform over the workgroup
+        int32_t nk = a.key_lens[b];
+        nk = nk < 1 ? 1 : nk;
+        if (nk < ATT_L) {
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) sc[i][r] = 16 * i + 4 * fch + r < nk ? sc[i][r] : INT32_MIN;
+        }
+    }
 
     // ---- softmax over the L keys of the lane's query (four lanes share a query) ---------------
     int32_t mx = sc[0][0];
@@ -236,7 +249,8 @@ static int launch_attention_l(const AttentionArgs& a, int64_t blocks, bool fast,
 }
 
 int launch_attention(const int8_t* qkv, int8_t* ctx, int32_t batch, int32_t seq, int32_t hidden, int32_t heads,
-                     ibert_dyadic scores_dy, const ibert_softmax_params& sp, ibert_dyadic ctx_dy, hipStream_t stream)
+                     ibert_dyadic scores_dy, const ibert_softmax_params& sp, ibert_dyadic ctx_dy, hipStream_t stream,
+                     const int32_t* key_lens)
 {
     if (!attention_fused_ok(qkv, ctx, seq, hidden, heads)) return IBERT_ERR_NOT_IMPLEMENTED;
     const int64_t blocks = (int64_t)batch * heads * (seq / ATT_QB);
@@ -248,6 +262,7 @@ int launch_attention(const int8_t* qkv, int8_t* ctx, int32_t batch, int32_t seq,
     a.ld_qkv = 3 * (int64_t)hidden; a.ld_ctx = hidden;
     a.s_m = scores_dy.m; a.s_s = scores_dy.s; a.c_m = ctx_dy.m; a.c_s = ctx_dy.s;
     a.sm = softmax_const(sp);
+    a.key_lens = key_lens;
     // register-only requantization: accumulators are below 64*127^2 (scores) and L*127*127 (context) < 2^23
     const bool rq = a.s_s >= 21 && a.s_s <= 62 && a.c_s >= 23 && a.c_s <= 62;
     const bool fast = softmax_fast_ok(sp);

@@ -125,12 +125,18 @@ int launch_gemm_gelu(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W,
                      int32_t* scratch, hipStream_t stream);
 bool attention_fused_ok(const int8_t* qkv, const int8_t* ctx, int32_t seq, int32_t hidden, int32_t heads);
 int launch_attention(const int8_t* qkv, int8_t* ctx, int32_t batch, int32_t seq, int32_t hidden, int32_t heads,
-                     ibert_dyadic scores_dy, const ibert_softmax_params& sp, ibert_dyadic ctx_dy, hipStream_t stream);
+                     ibert_dyadic scores_dy, const ibert_softmax_params& sp, ibert_dyadic ctx_dy, hipStream_t stream,
+                     const int32_t* key_lens = nullptr);
+// key_lens (device, optional): row r keeps its first key_lens[r / rows_per_len] columns
 int launch_softmax(const int32_t* x, void* y, int64_t rows, int32_t cols, int64_t ldx, int64_t ldy,
-                   const ibert_softmax_params& p, hipStream_t stream);
+                   const ibert_softmax_params& p, hipStream_t stream, const int32_t* key_lens = nullptr,
+                   int64_t rows_per_len = 0);
 int launch_gelu(const int32_t* x, int8_t* y, int64_t n, const ibert_gelu_params& p, hipStream_t stream);
 int launch_layernorm(const int32_t* x, int8_t* y, int64_t rows, int32_t C, int64_t ldx, int64_t ldy,
                      const int32_t* gamma_q, const int32_t* beta_q, int32_t shift, hipStream_t stream);
+int launch_embedding(const int32_t* ids, const int8_t* tok, const int8_t* pos, int64_t tokens, int32_t seq, int32_t C,
+                     int32_t vocab, ibert_dyadic tok_dy, ibert_dyadic pos_dy, const int32_t* gamma_q,
+                     const int32_t* beta_q, int32_t shift, int8_t* y, int64_t ldy, hipStream_t stream);
 
 // Parameter validation shared by the public entry points and the layer.
 int check_gemm(const ibert_gemm_desc& d, const void* A, const void* W, const void* mult,

@@ -69,7 +69,7 @@ static int layout(int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int
 // Steps 2-4 (scores, Softmax, context) as three kernels through the INT32 scores and INT8 probabilities buffers.
 static int run_attention_unfused(const int8_t* qkv, int32_t* scores, int8_t* probs, int8_t* ctx, int64_t B, int64_t L,
                                  int64_t H, int64_t nh, const ibert_dyadic& scores_dy, const ibert_softmax_params& softmax,
-                                 const ibert_dyadic& ctx_dy, hipStream_t stream)
+                                 const ibert_dyadic& ctx_dy, const int32_t* key_lens, hipStream_t stream)
 {
     const int64_t dh = H / nh;
     ibert_gemm_desc d;
@@ -93,9 +93,9 @@ static int run_attention_unfused(const int8_t* qkv, int32_t* scores, int8_t* pro
     RUN_GEMM(qkv, qkv + H, nullptr, nullptr, nullptr, nullptr, scores);
     prof_after(stream, 2, 2.0 * B * nh * L * L * dh, gemm_bytes(L, L, dh, B * nh, 4, false, false));
 
-    // 3: softmax over the key axis
+    // 3: softmax over the key axis (the nh*L rows of sequence b keep key_lens[b] keys)
     prof_before(stream);
-    rc = launch_softmax(scores, probs, B * nh * L, (int32_t)L, L, L, softmax, stream);
+    rc = launch_softmax(scores, probs, B * nh * L, (int32_t)L, L, L, softmax, stream, key_lens, nh * L);
     if (rc) return rc;
     prof_after(stream, 3, 0.0, 5.0 * B * nh * L * L);
 
@@ -118,24 +118,24 @@ static int run_attention_unfused(const int8_t* qkv, int32_t* scores, int8_t* pro
 // Steps 2-4: one kernel where the shape allows it (and `fused` asks for it), else the three-kernel route.
 static int run_attention(const int8_t* qkv, int32_t* scores, int8_t* probs, int8_t* ctx, int64_t B, int64_t L, int64_t H,
                          int64_t nh, const ibert_dyadic& scores_dy, const ibert_softmax_params& softmax,
-                         const ibert_dyadic& ctx_dy, bool fused, hipStream_t stream)
+                         const ibert_dyadic& ctx_dy, const int32_t* key_lens, bool fused, hipStream_t stream)
 {
     if (fused && attention_fused_ok(qkv, ctx, (int32_t)L, (int32_t)H, (int32_t)nh)) {
         prof_before(stream);
         const int rc = launch_attention(qkv, ctx, (int32_t)B, (int32_t)L, (int32_t)H, (int32_t)nh, scores_dy, softmax,
-                                        ctx_dy, stream);
+                                        ctx_dy, stream, key_lens);
         if (rc) return rc;
         // both MatMuls; bytes: Q, K, V read once, the context written once
         prof_after(stream, 2, 4.0 * B * nh * L * L * (H / nh), 4.0 * B * L * H);
         return IBERT_OK;
     }
     if (!scores || !probs) return IBERT_ERR_WORKSPACE;
-    return run_attention_unfused(qkv, scores, probs, ctx, B, L, H, nh, scores_dy, softmax, ctx_dy, stream);
+    return run_attention_unfused(qkv, scores, probs, ctx, B, L, H, nh, scores_dy, softmax, ctx_dy, key_lens, stream);
 }
 
 static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, const int8_t* x, int8_t* y,
-                     int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn, char* ws,
-                     const ibert_layer_workspace_layout& lo, hipStream_t stream)
+                     int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn, const int32_t* key_lens,
+                     char* ws, const ibert_layer_workspace_layout& lo, hipStream_t stream)
 {
     const int64_t B = batch, L = seq, H = hidden, nh = heads, F = ffn, T = B * L, dh = H / nh;
     int8_t* qkv = reinterpret_cast<int8_t*>(ws + lo.qkv);
@@ -167,7 +167,8 @@ static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, c
     prof_after(stream, 1, 2.0 * T * 3 * H * H, gemm_bytes(T, 3 * H, H, 1, 1, false, true));
 
     // 2-4: attention scores, Softmax, context
-    rc = run_attention(qkv, scores, probs, ctx, B, L, H, nh, q.scores_dy, q.softmax, q.ctx_dy, (g_fusion & 2) != 0, stream);
+    rc = run_attention(qkv, scores, probs, ctx, B, L, H, nh, q.scores_dy, q.softmax, q.ctx_dy, key_lens,
+                       (g_fusion & 2) != 0, stream);
     if (rc) return rc;
 
     // 5: output projection + residual x, INT32 at the LayerNorm input scale
@@ -276,6 +277,15 @@ int ibert_attention_i(const int8_t* qkv, int8_t* ctx, int32_t batch, int32_t seq
                       const ibert_dyadic* scores_dy, const ibert_softmax_params* softmax, const ibert_dyadic* ctx_dy,
                       void* scratch, size_t scratch_bytes, void* stream)
 {
+    return ibert_attention_masked_i(qkv, ctx, batch, seq, hidden, heads, scores_dy, softmax, ctx_dy, nullptr, scratch,
+                                    scratch_bytes, stream);
+}
+
+int ibert_attention_masked_i(const int8_t* qkv, int8_t* ctx, int32_t batch, int32_t seq, int32_t hidden, int32_t heads,
+                             const ibert_dyadic* scores_dy, const ibert_softmax_params* softmax,
+                             const ibert_dyadic* ctx_dy, const int32_t* key_lens, void* scratch, size_t scratch_bytes,
+                             void* stream)
+{
     using namespace ibert;
     if (!scores_dy || !softmax || !ctx_dy) return IBERT_ERR_NULL;
     if (batch < 0 || seq < 1 || hidden < 1 || heads < 1 || hidden % heads) return IBERT_ERR_SHAPE;
@@ -292,7 +302,7 @@ int ibert_attention_i(const int8_t* qkv, int8_t* ctx, int32_t batch, int32_t seq
         scores = static_cast<int32_t*>(scratch);
         probs = static_cast<int8_t*>(scratch) + align_up(n * 4);
     }
-    return run_attention(qkv, scores, probs, ctx, batch, seq, hidden, heads, *scores_dy, *softmax, *ctx_dy,
+    return run_attention(qkv, scores, probs, ctx, batch, seq, hidden, heads, *scores_dy, *softmax, *ctx_dy, key_lens,
                          (g_fusion & 2) != 0, (hipStream_t)stream);
 }
 
@@ -378,6 +388,14 @@ int ibert_encoder_layer_i(const ibert_layer_weights* weights, const ibert_layer_
                           int8_t* y, int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn,
                           void* workspace, size_t workspace_bytes, void* stream)
 {
+    return ibert_encoder_layer_masked_i(weights, quant, x, y, batch, seq, hidden, heads, ffn, nullptr, workspace,
+                                        workspace_bytes, stream);
+}
+
+int ibert_encoder_layer_masked_i(const ibert_layer_weights* weights, const ibert_layer_quant* quant, const int8_t* x,
+                                 int8_t* y, int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn,
+                                 const int32_t* key_lens, void* workspace, size_t workspace_bytes, void* stream)
+{
     if (!weights || !quant || !x || !y || !workspace) return IBERT_ERR_NULL;
     ibert_layer_workspace_layout lo;
     int rc = ibert::layout(batch, seq, hidden, heads, ffn, &lo);
@@ -386,13 +404,21 @@ int ibert_encoder_layer_i(const ibert_layer_weights* weights, const ibert_layer_
     if (workspace_bytes < lo.total || !ibert::aligned(workspace, 256)) return IBERT_ERR_WORKSPACE;
     rc = ibert::check_layer(*weights, *quant, seq, hidden);
     if (rc) return rc;
-    return ibert::run_layer(*weights, *quant, x, y, batch, seq, hidden, heads, ffn, (char*)workspace, lo,
+    return ibert::run_layer(*weights, *quant, x, y, batch, seq, hidden, heads, ffn, key_lens, (char*)workspace, lo,
                             (hipStream_t)stream);
 }
 
 int ibert_encoder_i(const ibert_layer_weights* weights, const ibert_layer_quant* quant, int32_t n_layers,
                     const int8_t* x, int8_t* y, int32_t batch, int32_t seq, int32_t hidden, int32_t heads,
                     int32_t ffn, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return ibert_encoder_masked_i(weights, quant, n_layers, x, y, batch, seq, hidden, heads, ffn, nullptr, workspace,
+                                  workspace_bytes, stream);
+}
+
+int ibert_encoder_masked_i(const ibert_layer_weights* weights, const ibert_layer_quant* quant, int32_t n_layers,
+                           const int8_t* x, int8_t* y, int32_t batch, int32_t seq, int32_t hidden, int32_t heads,
+                           int32_t ffn, const int32_t* key_lens, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!weights || !quant || !x || !y || !workspace) return IBERT_ERR_NULL;
     if (n_layers < 1) return IBERT_ERR_SHAPE;
@@ -411,7 +437,7 @@ int ibert_encoder_i(const ibert_layer_weights* weights, const ibert_layer_quant*
     const int8_t* in = x;
     for (int32_t l = 0; l < n_layers; ++l) {
         int8_t* out = (l == n_layers - 1) ? y : pp[l & 1];
-        rc = ibert::run_layer(weights[l], quant[l], in, out, batch, seq, hidden, heads, ffn, ws, lo,
+        rc = ibert::run_layer(weights[l], quant[l], in, out, batch, seq, hidden, heads, ffn, key_lens, ws, lo,
                               (hipStream_t)stream);
         if (rc) return rc;
         in = out;

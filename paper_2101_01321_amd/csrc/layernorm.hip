@@ -5,9 +5,21 @@
 // per-row scalar work (mean, variance, Newton integer square root, reciprocal factor) is done
 // redundantly by the lanes of the group, which is why short groups (16 lanes, 4 rows per wave) are
 // preferred when there are enough rows to fill the chip.
+//
+// The same kernel also serves the INT8 embedding (Sec. 1, contribution 3; App. C.1): there the row is not read from
+// an INT32 buffer but made on the fly from one row of the INT8 token table and one of the INT8 position table, each
+// rescaled by a dyadic number to the common INT32 scale of the sum, and then normalized as above.
 #include "common.h"
 
 namespace ibert {
+
+struct EmbedArgs {
+    const int32_t* ids;  // [rows] token ids, clamped into [0, vocab)
+    const int8_t* tok;   // [vocab, C]
+    const int8_t* pos;   // [>= seq, C]; row r takes position r mod seq
+    int32_t seq, vocab;
+    int32_t tok_m, tok_s, pos_m, pos_s;
+};
 
 struct LayerNormArgs {
     const int32_t* x;
@@ -19,6 +31,7 @@ struct LayerNormArgs {
     const int32_t* beta_q;
     int32_t shift;
     uint32_t magic_c;    // floor(2^32 / C) + 1 (0 for C == 1): reciprocal multiply for the divisions by C
+    EmbedArgs emb;       // only read by the embedding instantiations
 };
 
 // floor(u / C) for u < 2^31: est = mulhi(u, magic) is the quotient or one more (the excess is below
@@ -66,15 +79,24 @@ constexpr int LN_THREADS = 256;
 
 // ALIGNED: rows 16-byte (x) / 4-byte (y) aligned, C % 4 == 0, gamma/beta 16-byte aligned: every 4-element
 // chunk is either entirely inside the row or entirely outside, and moves as one vector.
-template <int LPR, int NCH, bool ALIGNED>
+// EMB: the row is DY(tok[id]) + DY(pos[row mod seq]) instead of x[row] (ALIGNED then means 4-byte aligned table rows).
+template <int LPR, int NCH, bool ALIGNED, bool EMB = false>
 __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArgs a)
 {
     constexpr int ROWS_PER_BLOCK = LN_THREADS / LPR;
     const int lane = threadIdx.x % LPR;
     const int64_t row = (int64_t)blockIdx.x * ROWS_PER_BLOCK + threadIdx.x / LPR;
     const bool live = row < a.rows;
-    const int32_t* xr = a.x + (live ? row : 0) * a.ldx;
     const int32_t C = a.C;
+    const int32_t* xr = EMB ? nullptr : a.x + (live ? row : 0) * a.ldx;
+    const int8_t *tr = nullptr, *pr = nullptr;
+    if (EMB) {
+        const int64_t r0 = live ? row : 0;
+        int32_t id = a.emb.ids[r0];
+        id = id < 0 ? 0 : (id >= a.emb.vocab ? a.emb.vocab - 1 : id);
+        tr = a.emb.tok + (int64_t)id * C;
+        pr = a.emb.pos + (r0 % a.emb.seq) * C;
+    }
     const int32_t rnd = 1 << (a.shift - 1);
 
     // gamma and beta are shared by every row of the workgroup: one coalesced copy into LDS
@@ -91,7 +113,29 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         const int col = (c * LPR + lane) * 4;
-        if (ALIGNED) {
+        if (EMB) {
+            int32_t tv[4], pv[4];
+            if (ALIGNED) {
+                const int cc = col < C ? col : 0;
+                const uint32_t t4 = *reinterpret_cast<const uint32_t*>(tr + cc), p4 = *reinterpret_cast<const uint32_t*>(pr + cc);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    tv[e] = (int8_t)(t4 >> (8 * e));
+                    pv[e] = (int8_t)(p4 >> (8 * e));
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int ce = col + e < C ? col + e : 0;
+                    tv[e] = tr[ce];
+                    pv[e] = pr[ce];
+                }
+            }
+            // the sum is taken in 64 bits and clamped once, as the definition has it
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                v[c][e] = clamp_i64_to_i32(dyadic64(tv[e], a.emb.tok_m, a.emb.tok_s) + dyadic64(pv[e], a.emb.pos_m, a.emb.pos_s), 32767);
+        } else if (ALIGNED) {
             const int cc = col < C ? col : 0;          // out-of-row chunks re-read chunk 0 and are masked below
             const int4 t = *reinterpret_cast<const int4*>(xr + cc);
             v[c][0] = t.x; v[c][1] = t.y; v[c][2] = t.z; v[c][3] = t.w;
@@ -200,19 +244,17 @@ static void launch_rows(const LayerNormArgs& a, bool al, hipStream_t stream)
 {
     constexpr int rpb = LN_THREADS / LPR;
     const unsigned blocks = (unsigned)((a.rows + rpb - 1) / rpb);
-    if (al) hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, true>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
+    if (a.emb.ids) {
+        if (al) hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, true, true>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
+        else hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, false, true>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
+    } else if (al) hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, true>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
     else hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, false>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
 }
 
-int launch_layernorm(const int32_t* x, int8_t* y, int64_t rows, int32_t C, int64_t ldx, int64_t ldy,
-                     const int32_t* gamma_q, const int32_t* beta_q, int32_t shift, hipStream_t stream)
+static int dispatch_rows(const LayerNormArgs& a, bool al, hipStream_t stream)
 {
-    if (rows == 0) return IBERT_OK;
-    if (rows > 0x7fffffffLL) return IBERT_ERR_SHAPE;
-    const uint32_t magic = C == 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) / (uint32_t)C) + 1);
-    LayerNormArgs a{x, y, rows, C, ldx, ldy, gamma_q, beta_q, shift, magic};
-    const bool al = aligned(x, 16) && ldx % 4 == 0 && aligned(y, 4) && ldy % 4 == 0 && C % 4 == 0 &&
-                    aligned(gamma_q, 16) && aligned(beta_q, 16);
+    const int64_t rows = a.rows;
+    const int32_t C = a.C;
     // Lanes per row: the per-row scalar work (mean, variance, square root, reciprocal) is repeated by every
     // lane of a row, so short groups are cheaper, but the chip needs about two wavefronts per SIMD (2048 in
     // all) to overlap the load, reduce and store phases of different rows.
@@ -232,8 +274,34 @@ int launch_layernorm(const int32_t* x, int8_t* y, int64_t rows, int32_t C, int64
         else launch_rows<16, 16>(a, al, stream);
     }
     IBERT_LAUNCH_CHECK("layernorm kernel");
-    g_last_kernel = "layernorm_rows_kernel";
+    g_last_kernel = a.emb.ids ? "layernorm_rows_kernel<embedding>" : "layernorm_rows_kernel";
     return IBERT_OK;
+}
+
+static uint32_t magic_for(int32_t C) { return C == 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) / (uint32_t)C) + 1); }
+
+int launch_layernorm(const int32_t* x, int8_t* y, int64_t rows, int32_t C, int64_t ldx, int64_t ldy,
+                     const int32_t* gamma_q, const int32_t* beta_q, int32_t shift, hipStream_t stream)
+{
+    if (rows == 0) return IBERT_OK;
+    if (rows > 0x7fffffffLL) return IBERT_ERR_SHAPE;
+    LayerNormArgs a{x, y, rows, C, ldx, ldy, gamma_q, beta_q, shift, magic_for(C), EmbedArgs{}};
+    const bool al = aligned(x, 16) && ldx % 4 == 0 && aligned(y, 4) && ldy % 4 == 0 && C % 4 == 0 &&
+                    aligned(gamma_q, 16) && aligned(beta_q, 16);
+    return dispatch_rows(a, al, stream);
+}
+
+int launch_embedding(const int32_t* ids, const int8_t* tok, const int8_t* pos, int64_t tokens, int32_t seq, int32_t C,
+                     int32_t vocab, ibert_dyadic tok_dy, ibert_dyadic pos_dy, const int32_t* gamma_q,
+                     const int32_t* beta_q, int32_t shift, int8_t* y, int64_t ldy, hipStream_t stream)
+{
+    if (tokens == 0) return IBERT_OK;
+    if (tokens > 0x7fffffffLL) return IBERT_ERR_SHAPE;
+    LayerNormArgs a{nullptr, y, tokens, C, 0, ldy, gamma_q, beta_q, shift, magic_for(C),
+                    EmbedArgs{ids, tok, pos, seq, vocab, tok_dy.m, tok_dy.s, pos_dy.m, pos_dy.s}};
+    const bool al = aligned(tok, 4) && aligned(pos, 4) && aligned(y, 4) && ldy % 4 == 0 && C % 4 == 0 &&
+                    aligned(gamma_q, 16) && aligned(beta_q, 16);
+    return dispatch_rows(a, al, stream);
 }
 
 }  // namespace ibert
@@ -247,4 +315,20 @@ extern "C" int ibert_layernorm_i(const int32_t* x, int8_t* y, int64_t rows, int3
     if (rows == 0) return IBERT_OK;
     if (!x || !y || !gamma_q || !beta_q) return IBERT_ERR_NULL;
     return ibert::launch_layernorm(x, y, rows, C, ldx, ldy, gamma_q, beta_q, shift, (hipStream_t)stream);
+}
+
+extern "C" int ibert_embedding_i(const int32_t* ids, const int8_t* tok, const int8_t* pos, int64_t tokens, int32_t seq,
+                                 int32_t hidden, int32_t vocab, int32_t max_pos, const ibert_dyadic* tok_dy,
+                                 const ibert_dyadic* pos_dy, const int32_t* gamma_q, const int32_t* beta_q,
+                                 int32_t ln_shift, int8_t* y, int64_t ldy, void* stream)
+{
+    if (!tok_dy || !pos_dy) return IBERT_ERR_NULL;
+    if (tokens < 0 || seq < 1 || hidden < 1 || vocab < 1 || max_pos < seq || ldy < hidden) return IBERT_ERR_SHAPE;
+    if (!ibert::dyadic_ok(*tok_dy) || !ibert::dyadic_ok(*pos_dy)) return IBERT_ERR_PARAM_RANGE;
+    const int rc = ibert::check_layernorm(hidden, ln_shift);
+    if (rc) return rc;
+    if (tokens == 0) return IBERT_OK;
+    if (!ids || !tok || !pos || !gamma_q || !beta_q || !y) return IBERT_ERR_NULL;
+    return ibert::launch_embedding(ids, tok, pos, tokens, seq, hidden, vocab, *tok_dy, *pos_dy, gamma_q, beta_q, ln_shift, y,
+                                   ldy, (hipStream_t)stream);
 }

@@ -17,7 +17,18 @@ struct SoftmaxArgs {
     int32_t cols;
     int64_t ldx, ldy;
     SoftmaxConst c;
+    const int32_t* key_lens;   // optional: row r keeps its first key_lens[r / rows_per_len] columns, the rest are masked
+    int64_t rows_per_len;
 };
+
+// Number of columns of `row` that are real keys.  A masked column takes the logit INT32_MIN ("minus infinity"): its
+// exponential is then zero unless the whole row sits at the bottom of the INT32 range.
+__device__ __forceinline__ int32_t live_cols(const SoftmaxArgs& a, int64_t row)
+{
+    if (!a.key_lens) return a.cols;
+    const int32_t n = a.key_lens[row / a.rows_per_len];
+    return n < 1 ? 1 : (n > a.cols ? a.cols : n);
+}
 
 template <int LPR>
 __device__ __forceinline__ int32_t group_max(int32_t v)
@@ -43,6 +54,7 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_rows_kernel(SoftmaxArgs a)
     const int64_t row = (int64_t)blockIdx.x * ROWS_PER_BLOCK + threadIdx.x / LPR;
     const bool live = row < a.rows;
     const int32_t* xr = a.x + (live ? row : 0) * a.ldx;
+    const int32_t nk = live_cols(a, live ? row : 0);
 
     int32_t q[NCH][4];
     int32_t mx = INT32_MIN;
@@ -51,10 +63,11 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_rows_kernel(SoftmaxArgs a)
         const int col = (c * LPR + lane) * 4;
         if (ALIGNED && live && col + 3 < a.cols) {
             const int4 v = *reinterpret_cast<const int4*>(xr + col);
-            q[c][0] = v.x; q[c][1] = v.y; q[c][2] = v.z; q[c][3] = v.w;
+            q[c][0] = col < nk ? v.x : INT32_MIN; q[c][1] = col + 1 < nk ? v.y : INT32_MIN;
+            q[c][2] = col + 2 < nk ? v.z : INT32_MIN; q[c][3] = col + 3 < nk ? v.w : INT32_MIN;
         } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) q[c][e] = (live && col + e < a.cols) ? xr[col + e] : INT32_MIN;
+            for (int e = 0; e < 4; ++e) q[c][e] = (live && col + e < nk) ? xr[col + e] : INT32_MIN;
         }
 #pragma unroll
         for (int e = 0; e < 4; ++e) mx = q[c][e] > mx ? q[c][e] : mx;
@@ -121,9 +134,11 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_long_kernel(SoftmaxArgs a)
     const int64_t row = blockIdx.x;
     const int32_t* xr = a.x + row * a.ldx;
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const int32_t nk = live_cols(a, row);
+    auto at = [&](int j) { return j < nk ? xr[j] : INT32_MIN; };
 
     int32_t mx = INT32_MIN;
-    for (int j = threadIdx.x; j < a.cols; j += SM_THREADS) mx = xr[j] > mx ? xr[j] : mx;
+    for (int j = threadIdx.x; j < nk; j += SM_THREADS) mx = xr[j] > mx ? xr[j] : mx;
     mx = group_max<64>(mx);
     if (lane == 0) s_max[wave] = mx;
     __syncthreads();
@@ -132,7 +147,7 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_long_kernel(SoftmaxArgs a)
     for (int w = 1; w < SM_THREADS / 64; ++w) mx = s_max[w] > mx ? s_max[w] : mx;
 
     uint32_t sum = 0;
-    for (int j = threadIdx.x; j < a.cols; j += SM_THREADS) sum += iexp_from_diff((uint32_t)mx - (uint32_t)xr[j], a.c);
+    for (int j = threadIdx.x; j < a.cols; j += SM_THREADS) sum += iexp_from_diff((uint32_t)mx - (uint32_t)at(j), a.c);
     sum = group_sum<64>(sum);
     if (lane == 0) s_sum[wave] = sum;
     __syncthreads();
@@ -142,7 +157,7 @@ __global__ __launch_bounds__(SM_THREADS) void softmax_long_kernel(SoftmaxArgs a)
     const uint32_t Fz = 0x80000000u / sum;
 
     for (int j = threadIdx.x; j < a.cols; j += SM_THREADS) {
-        uint32_t o = normalise(iexp_from_diff((uint32_t)mx - (uint32_t)xr[j], a.c), Fz, a.c.k);
+        uint32_t o = normalise(iexp_from_diff((uint32_t)mx - (uint32_t)at(j), a.c), Fz, a.c.k);
         if (OUT_I8) {
             o = o > 127u ? 127u : o;
             (reinterpret_cast<int8_t*>(a.y) + row * a.ldy)[j] = (int8_t)o;
@@ -188,11 +203,12 @@ static void launch_rows(const SoftmaxArgs& a, bool al, bool i8, bool fast, hipSt
 }
 
 int launch_softmax(const int32_t* x, void* y, int64_t rows, int32_t cols, int64_t ldx, int64_t ldy,
-                   const ibert_softmax_params& p, hipStream_t stream)
+                   const ibert_softmax_params& p, hipStream_t stream, const int32_t* key_lens, int64_t rows_per_len)
 {
     if (rows == 0) return IBERT_OK;
     SoftmaxArgs a;
     a.x = x; a.y = y; a.rows = rows; a.cols = cols; a.ldx = ldx; a.ldy = ldy;
+    a.key_lens = key_lens; a.rows_per_len = rows_per_len > 0 ? rows_per_len : 1;
     a.c = softmax_const(p);
     const bool i8 = p.out_dtype == IBERT_I8;
     const bool fast = softmax_fast_ok(p);
@@ -226,4 +242,17 @@ extern "C" int ibert_softmax_i(const int32_t* x, void* y, int64_t rows, int32_t 
     if (rows == 0) return IBERT_OK;
     if (!x || !y) return IBERT_ERR_NULL;
     return ibert::launch_softmax(x, y, rows, cols, ldx, ldy, *params, (hipStream_t)stream);
+}
+
+extern "C" int ibert_softmax_masked_i(const int32_t* x, void* y, int64_t rows, int32_t cols, int64_t ldx, int64_t ldy,
+                                      const ibert_softmax_params* params, const int32_t* key_lens, int64_t rows_per_len,
+                                      void* stream)
+{
+    if (!params) return IBERT_ERR_NULL;
+    if (rows < 0 || cols < 1 || ldx < cols || ldy < cols || rows_per_len < 1) return IBERT_ERR_SHAPE;
+    const int rc = ibert::check_softmax(*params, cols);
+    if (rc) return rc;
+    if (rows == 0) return IBERT_OK;
+    if (!x || !y || !key_lens) return IBERT_ERR_NULL;
+    return ibert::launch_softmax(x, y, rows, cols, ldx, ldy, *params, (hipStream_t)stream, key_lens, rows_per_len);
 }

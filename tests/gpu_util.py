@@ -63,21 +63,26 @@ def gemm_gelu(desc_kwargs, A, W, bias, mult, shift, gelu_params, out_elems, with
     return out[:out_elems], (None if tS is None else tS.cpu().numpy())
 
 
-def attention(qkv, batch, seq, hidden, heads, scores_dy, softmax_params, ctx_dy, with_scratch=True):
-    """Steps 2-4 through ibert_attention_i.  qkv: int8 [batch*seq, 3*hidden]; returns ctx int8 [batch*seq, hidden]."""
+def attention(qkv, batch, seq, hidden, heads, scores_dy, softmax_params, ctx_dy, with_scratch=True, key_lens=None):
+    """Steps 2-4 through ibert_attention_i (ibert_attention_masked_i with key_lens).  qkv: int8 [batch*seq, 3*hidden];
+    returns ctx int8 [batch*seq, hidden]."""
     tq = to_dev(qkv, np.int8)
     tc = torch.full((batch * seq * hidden + 16,), 77, dtype=torch.int8, device=DEV)
     ts = None
     if with_scratch:
         ts = torch.zeros(B.ibert_attention_scratch_bytes(batch, seq, heads), dtype=torch.uint8, device=DEV)
-    B.ibert_attention_i(tq, tc, batch, seq, hidden, heads, B.Dyadic(*scores_dy), softmax_params, B.Dyadic(*ctx_dy), ts)
+    if key_lens is None:
+        B.ibert_attention_i(tq, tc, batch, seq, hidden, heads, B.Dyadic(*scores_dy), softmax_params, B.Dyadic(*ctx_dy), ts)
+    else:
+        B.ibert_attention_masked_i(tq, tc, batch, seq, hidden, heads, B.Dyadic(*scores_dy), softmax_params,
+                                   B.Dyadic(*ctx_dy), to_dev(key_lens, np.int32), ts)
     torch.cuda.synchronize()
     out = tc.cpu().numpy()
     assert np.all(out[batch * seq * hidden:] == 77), "wrote past the end"
     return out[:batch * seq * hidden].reshape(batch * seq, hidden)
 
 
-def softmax(x, params, cols=None, ldx=None, ldy=None, x_off=0, y_off=0):
+def softmax(x, params, cols=None, ldx=None, ldy=None, x_off=0, y_off=0, key_lens=None, rows_per_len=1):
     x = np.ascontiguousarray(x, np.int32)
     rows = x.shape[0]
     ldx = x.shape[1] if ldx is None else ldx
@@ -87,7 +92,10 @@ def softmax(x, params, cols=None, ldx=None, ldy=None, x_off=0, y_off=0):
     tx[x_off:].view(rows, ldx)[:, :x.shape[1]] = to_dev(x)
     i8 = params.out_dtype == B.I8
     ty = torch.full((rows * ldy + y_off,), 77, dtype=torch.int8 if i8 else torch.int32, device=DEV)
-    B.ibert_softmax_i(tx[x_off:], ty[y_off:], rows, cols, ldx, ldy, params)
+    if key_lens is None:
+        B.ibert_softmax_i(tx[x_off:], ty[y_off:], rows, cols, ldx, ldy, params)
+    else:
+        B.ibert_softmax_masked_i(tx[x_off:], ty[y_off:], rows, cols, ldx, ldy, params, to_dev(key_lens, np.int32), rows_per_len)
     torch.cuda.synchronize()
     return ty[y_off:].view(rows, ldy).cpu().numpy()
 
@@ -117,6 +125,23 @@ def layernorm(x, gamma_q, beta_q, shift, ldx=None, ldy=None, x_off=0, y_off=0):
     return ty[y_off:].view(rows, ldy).cpu().numpy()
 
 
+def embedding(ids, seq, tok, pos, tok_dy, pos_dy, gamma_q, beta_q, shift, ldy=None, y_off=0):
+    """ibert_embedding_i; returns int8 [tokens, hidden]."""
+    ids = np.ascontiguousarray(ids, np.int32)
+    T, H = ids.size, tok.shape[1]
+    ldy = H if ldy is None else ldy
+    ty = torch.full((T * ldy + y_off + 16,), 77, dtype=torch.int8, device=DEV)
+    B.ibert_embedding_i(to_dev(ids), to_dev(tok, np.int8), to_dev(pos, np.int8), T, seq, H, tok.shape[0], pos.shape[0],
+                        B.Dyadic(*tok_dy), B.Dyadic(*pos_dy), to_dev(gamma_q, np.int32), to_dev(beta_q, np.int32), shift,
+                        ty[y_off:], ldy)
+    torch.cuda.synchronize()
+    out = ty.cpu().numpy()
+    assert np.all(out[:y_off] == 77) and np.all(out[y_off + T * ldy:] == 77), "wrote outside the output"
+    body = out[y_off:y_off + T * ldy].reshape(T, ldy)
+    assert np.all(body[:, H:] == 77), "wrote into the row padding"
+    return body[:, :H]
+
+
 class DeviceModel:
     """All layers of a synthetic encoder resident on the GPU, plus workspace."""
 
@@ -133,17 +158,25 @@ class DeviceModel:
         self.ws = torch.zeros(self.ws_bytes, dtype=torch.uint8, device=DEV)
         self.layout = B.ibert_encoder_layer_workspace_layout(c.batch, c.seq, c.hidden, c.heads, c.ffn)
 
-    def forward(self, x_q: torch.Tensor) -> torch.Tensor:
+    def forward(self, x_q: torch.Tensor, key_lens=None) -> torch.Tensor:
         c = self.cfg
         y = torch.empty_like(x_q)
-        B.ibert_encoder_i(self.weights, self.quant, self.n_layers, x_q, y, c.batch, c.seq, c.hidden, c.heads, c.ffn, self.ws)
+        if key_lens is None:
+            B.ibert_encoder_i(self.weights, self.quant, self.n_layers, x_q, y, c.batch, c.seq, c.hidden, c.heads, c.ffn, self.ws)
+        else:
+            B.ibert_encoder_masked_i(self.weights, self.quant, self.n_layers, x_q, y, c.batch, c.seq, c.hidden, c.heads,
+                                     c.ffn, key_lens, self.ws)
         return y
 
-    def layer_forward(self, l: int, x_q: torch.Tensor) -> torch.Tensor:
+    def layer_forward(self, l: int, x_q: torch.Tensor, key_lens=None) -> torch.Tensor:
         c = self.cfg
         y = torch.empty_like(x_q)
-        B.ibert_encoder_layer_i(self.layers[l].weights, self.layers[l].quant, x_q, y, c.batch, c.seq, c.hidden, c.heads,
-                                c.ffn, self.ws)
+        if key_lens is None:
+            B.ibert_encoder_layer_i(self.layers[l].weights, self.layers[l].quant, x_q, y, c.batch, c.seq, c.hidden, c.heads,
+                                    c.ffn, self.ws)
+        else:
+            B.ibert_encoder_layer_masked_i(self.layers[l].weights, self.layers[l].quant, x_q, y, c.batch, c.seq, c.hidden,
+                                           c.heads, c.ffn, key_lens, self.ws)
         return y
 
     def intermediates(self) -> dict:

@@ -514,6 +514,168 @@ def test_encoder_full_size_sampled_sequences(G, name, seqs):
     assert y.min() >= -127 and y.std() > 5
 
 
+# ------------------------------------------------------------------------------------------- padded sequences
+@pytest.mark.parametrize("cols,rpl", [(5, 1), (64, 7), (128, 24), (200, 3), (384, 5), (513, 2), (2500, 4)])
+def test_softmax_masked_matches_oracle(G, cols, rpl):
+    from paper_2101_01321_amd import binding as B
+    nseq = 9
+    rows = nseq * rpl - (rpl // 2)                           # the last group of rows is short
+    x, S = synth.softmax_logits(rows, cols)
+    if oracle.lib().orc_softmax_check(P.softmax_params(S), cols) != 0:
+        S = 2.0 ** -4
+    x[rpl, :] = -2 ** 31 + 3                                 # real logits at the bottom of the range (a row with one real
+                                                             # key): the masked e_j are not 0 there
+    lens = np.array([cols, 1, 2, cols - 1, max(1, cols // 2), 3, 4, max(1, cols - 3), max(1, cols // 3)], np.int32).clip(1, cols)
+    sp, op = B.ibert_softmax_params_from_scale(S, cols), P.softmax_params(S)
+    xm = x.copy()
+    for r in range(rows):
+        xm[r, lens[r // rpl]:] = -2 ** 31
+    want = oracle.softmax(xm, op)
+    G.say("softmax masked cols=%d rows_per_len=%d" % (cols, rpl))
+    _eq(G.softmax(x, sp, key_lens=lens, rows_per_len=rpl), want, "masked softmax cols=%d" % cols)
+    if cols in (5, 513):
+        got = G.softmax(x, sp, ldx=cols + 3, ldy=cols + 1, x_off=1, y_off=3, key_lens=lens, rows_per_len=rpl)
+        _eq(got[:, :cols], want, "masked softmax unaligned cols=%d" % cols)
+    # lengths outside [1, cols] are clamped into it
+    wild = lens.copy()
+    wild[0], wild[1] = cols + 1000, -5
+    _eq(G.softmax(x, sp, key_lens=wild, rows_per_len=rpl), want, "clamped lengths cols=%d" % cols)
+
+
+@pytest.mark.parametrize("B_,nh,L,S,sdy,cdy,lens", [
+    (4, 3, 128, 2.0 ** -6, (1518500250, 36), (1073741824, 37), (128, 1, 77, 64)),
+    (3, 2, 128, 2.0 ** -2, (1518500250, 41), (60000, 22), (5, 127, 16)),           # general Softmax / requantization forms
+    (2, 2, 256, 2.0 ** -6, (1187698534, 28), (1073741824, 37), (200, 65)),
+    (2, 1, 512, 2.0 ** -6, (1187698534, 28), (1518500250, 38), (512, 300)),
+    (3, 2, 72, 2.0 ** -6, (1518500250, 36), (1073741824, 37), (72, 10, 71)),       # three kernels through scratch
+])
+def test_attention_masked(G, B_, nh, L, S, sdy, cdy, lens):
+    from paper_2101_01321_amd import binding as B
+    H = nh * 64
+    rng = np.random.default_rng(B_ * 100 + nh * 10 + L + 1)
+    qkv = np.clip(np.rint(rng.normal(0, 40, size=(B_ * L, 3 * H))), -127, 127).astype(np.int8)
+    lens = np.array(lens, np.int32)
+    sp, op = B.ibert_softmax_params_from_scale(S, L), P.softmax_params(S)
+    # oracle: scores, mask, Softmax, context, step by step
+    dh, flat = 64, qkv.reshape(-1)
+    spec = GemmSpec(L, L, dh, lda=3 * H, ldw=3 * H, ldc=L, batch_outer=B_, batch_inner=nh, sA=(L * 3 * H, dh),
+                    sW=(L * 3 * H, dh), sC=(nh * L * L, L * L), per_channel=0, dy=sdy, out_dtype=I32, out_clamp=2 ** 31 - 1)
+    scores = oracle.mask_scores(oracle.gemm_requant(spec, flat, flat[H:], out_elems=B_ * nh * L * L), B_, nh, L, lens)
+    probs = oracle.softmax(scores.reshape(-1, L), op)
+    spec = GemmSpec(L, dh, L, lda=L, ldw=3 * H, ldc=H, batch_outer=B_, batch_inner=nh, trans_w=1, sA=(nh * L * L, L * L),
+                    sW=(L * 3 * H, dh), sC=(L * H, dh), per_channel=0, dy=cdy, out_dtype=I8, out_clamp=127)
+    want = oracle.gemm_requant(spec, probs.reshape(-1), flat[2 * H:], out_elems=B_ * L * H).reshape(B_ * L, H)
+    assert not np.array_equal(want, _attention_oracle(qkv, B_, L, H, nh, sdy, op, cdy))   # the mask matters
+    G.say("masked attention B=%d heads=%d L=%d" % (B_, nh, L))
+    _eq(G.attention(qkv, B_, L, H, nh, sdy, sp, cdy, key_lens=lens), want, "masked attention")
+    old = B.ibert_set_fusion(0)
+    try:
+        G.say("masked attention, fusion off")
+        _eq(G.attention(qkv, B_, L, H, nh, sdy, sp, cdy, key_lens=lens), want, "masked attention (three kernels)")
+    finally:
+        B.ibert_set_fusion(old)
+
+
+@pytest.mark.parametrize("cfg,lens", [
+    (synth.EncoderConfig("masked", 128, 2, 256, 128, 3, 2), (128, 29, 1)),         # one-kernel attention
+    (synth.EncoderConfig("masked_ragged", 192, 3, 320, 40, 3, 1), (40, 7, 39)),    # three-kernel attention
+])
+def test_layer_masked_every_row(G, cfg, lens):
+    import torch
+    from paper_2101_01321_amd import binding as B
+    x_q, S_x, _ = synth.input_activations(cfg)
+    lens = np.array(lens, np.int32)
+    tl = G.to_dev(lens)
+    for fusion in (3, 0):
+        B.ibert_set_fusion(fusion)
+        try:
+            model = G.DeviceModel(cfg, S_x)
+            cur, tx = x_q, G.to_dev(x_q)
+            for l in range(cfg.layers):
+                w, q = P.layer_params(synth.layer_raw(cfg, l), model.scales[l], cfg.hidden, cfg.heads)
+                want = oracle.encoder_layer(w, q, cur, cfg.batch, cfg.seq, cfg.hidden, cfg.heads, cfg.ffn, key_lens=lens)
+                G.say("masked layer %s l=%d fusion=%d" % (cfg.name, l, fusion))
+                ty = model.layer_forward(l, tx, key_lens=tl)
+                torch.cuda.synchronize()
+                _eq(ty.cpu().numpy(), want, "%s layer %d" % (cfg.name, l))
+                cur, tx = want, ty
+            G.say("masked encoder %s in one call" % cfg.name)
+            y = model.forward(G.to_dev(x_q), key_lens=tl)
+            torch.cuda.synchronize()
+            _eq(y.cpu().numpy(), cur, "%s encoder" % cfg.name)
+        finally:
+            B.ibert_set_fusion(3)
+
+
+def test_encoder_masked_full_size_sampled_sequences(G):
+    # Base, sequence length 128, batch 32 with a mix of lengths: a padded sequence equals, on its real tokens, the
+    # same tokens run alone at their own length (the oracle never sees the padding)
+    import torch
+    cfg = synth.CONFIGS["base_b32"]
+    x_q, S_x, _ = synth.input_activations(cfg)
+    lens = synth.key_lengths(cfg.batch, cfg.seq)
+    G.say("masked encoder base_b32: building")
+    model = G.DeviceModel(cfg, S_x)
+    y = model.forward(G.to_dev(x_q), key_lens=G.to_dev(lens))
+    torch.cuda.synchronize()
+    y = y.cpu().numpy().reshape(cfg.batch, cfg.seq, cfg.hidden)
+    L, H = cfg.seq, cfg.hidden
+    for s in (3, int(np.argmin(lens))):
+        n = int(lens[s])
+        G.say("masked encoder base_b32: oracle on sequence %d of length %d" % (s, n))
+        cur = x_q.reshape(cfg.batch, L, H)[s, :n]
+        for l in range(cfg.layers):
+            w, q = P.layer_params(synth.layer_raw(cfg, l), model.scales[l], H, cfg.heads)
+            cur = oracle.encoder_layer(w, q, cur, 1, n, H, cfg.heads, cfg.ffn)
+        _eq(y[s, :n], cur, "sequence %d" % s)
+
+
+# ------------------------------------------------------------------------------------------- embedding
+@pytest.mark.parametrize("H,V,seq,T", [(768, 1000, 128, 4096 + 37), (1024, 300, 512, 1500), (64, 50, 20, 60), (100, 17, 9, 31),
+                                       (3, 5, 4, 11), (257, 40, 33, 70)])
+def test_embedding_matches_oracle(G, H, V, seq, T):
+    emb = synth.embedding_raw(H, V, seq + 2)
+    tok_dy, pos_dy, gq, bq, s = P.embedding_params(emb, 5.0 / 127)
+    ids = synth.token_ids(T, V)
+    ids[:4] = [0, V - 1, -7, V + 100]
+    want = oracle.embedding(ids, seq, emb["tok"], emb["pos"], tok_dy, pos_dy, gq, bq, s)
+    G.say("embedding H=%d V=%d seq=%d T=%d" % (H, V, seq, T))
+    _eq(G.embedding(ids, seq, emb["tok"], emb["pos"], tok_dy, pos_dy, gq, bq, s), want, "embedding")
+    if H in (100, 257, 768):
+        G.say("embedding H=%d padded/unaligned output rows" % H)
+        _eq(G.embedding(ids, seq, emb["tok"], emb["pos"], tok_dy, pos_dy, gq, bq, s, ldy=H + 3, y_off=1), want, "embedding ldy")
+    # dyadics that drive the sum into the clamp
+    big = ((2 ** 31 - 1, 20), (2 ** 30, 22))
+    want = oracle.embedding(ids, seq, emb["tok"], emb["pos"], big[0], big[1], gq, bq, s)
+    _eq(G.embedding(ids, seq, emb["tok"], emb["pos"], big[0], big[1], gq, bq, s), want, "embedding, clamped sum")
+
+
+def test_embedding_feeds_the_encoder(G):
+    # ids -> embedding -> masked encoder, all on the device, against the oracle chain
+    import torch
+    from paper_2101_01321_amd import binding as B
+    cfg = synth.EncoderConfig("emb", 128, 2, 256, 128, 2, 2)
+    emb = synth.embedding_raw(cfg.hidden, 500, cfg.seq)
+    S_x = 5.0 / 127
+    tok_dy, pos_dy, gq, bq, s = P.embedding_params(emb, S_x)
+    ids = synth.token_ids(cfg.tokens, 500)
+    lens = np.array([128, 50], np.int32)
+    x_want = oracle.embedding(ids, cfg.seq, emb["tok"], emb["pos"], tok_dy, pos_dy, gq, bq, s)
+    model = G.DeviceModel(cfg, S_x)
+    cur = x_want
+    for l in range(cfg.layers):
+        w, q = P.layer_params(synth.layer_raw(cfg, l), model.scales[l], cfg.hidden, cfg.heads)
+        cur = oracle.encoder_layer(w, q, cur, cfg.batch, cfg.seq, cfg.hidden, cfg.heads, cfg.ffn, key_lens=lens)
+    tx = torch.empty(cfg.tokens, cfg.hidden, dtype=torch.int8, device=G.DEV)
+    G.say("embedding + masked encoder")
+    B.ibert_embedding_i(G.to_dev(ids), G.to_dev(emb["tok"]), G.to_dev(emb["pos"]), cfg.tokens, cfg.seq, cfg.hidden, 500,
+                        cfg.seq, B.Dyadic(*tok_dy), B.Dyadic(*pos_dy), G.to_dev(gq), G.to_dev(bq), s, tx, cfg.hidden)
+    y = model.forward(tx, key_lens=G.to_dev(lens))
+    torch.cuda.synchronize()
+    _eq(tx.cpu().numpy(), x_want, "embedding output")
+    _eq(y.cpu().numpy(), cur, "encoder on the embedded tokens")
+
+
 def test_dequantised_output_tracks_float_layer(G):
     """Tolerance check on GPU outputs: one tiny layer, each op against its float counterpart (teacher-forced)."""
     import torch

@@ -212,6 +212,37 @@ def test_fused_entry_points_reject_bad_arguments_before_touching_the_gpu():
     L.ibert_set_fusion(old)
 
 
+def test_embedding_and_masked_entry_points_reject_bad_arguments_before_touching_the_gpu():
+    L = B.lib()
+    dy = B.Dyadic(1518500250, 36)
+    dummy = 256
+    emb = lambda ids, tok, pos, T, seq, H, V, mp, tdy, pdy, g, b, sh, y, ldy: L.ibert_embedding_i(
+        ids, tok, pos, T, seq, H, V, mp, tdy, pdy, g, b, sh, y, ldy, None)
+    ok = (dummy, dummy, dummy, 10, 4, 64, 100, 8, C.byref(dy), C.byref(dy), dummy, dummy, 12, dummy, 64)
+    def but(**kw):
+        names = ("ids", "tok", "pos", "T", "seq", "H", "V", "mp", "tdy", "pdy", "g", "b", "sh", "y", "ldy")
+        a = dict(zip(names, ok))
+        a.update(kw)
+        return emb(*[a[n] for n in names])
+    assert but(tdy=None) == -1 and but(pdy=None) == -1
+    assert but(T=-1) == -2 and but(seq=0) == -2 and but(V=0) == -2 and but(mp=3) == -2 and but(ldy=63) == -2
+    assert but(tdy=C.byref(B.Dyadic(1, 63))) == -3 and but(H=1025, ldy=1025) == -3 and but(sh=0) == -3 and but(sh=31) == -3
+    assert but(T=0, ids=None, y=None) == 0                                     # no tokens: nothing to do
+    assert but(ids=None) == -1 and but(tok=None) == -1 and but(y=None) == -1 and but(g=None) == -1
+    # masked Softmax
+    sp = B.ibert_softmax_params_from_scale(2.0 ** -6, 128)
+    sm = lambda x, y, rows, cols, ldx, ldy, p, kl, rpl: L.ibert_softmax_masked_i(x, y, rows, cols, ldx, ldy, p, kl, rpl, None)
+    assert sm(dummy, dummy, 4, 128, 128, 128, None, dummy, 2) == -1
+    assert sm(dummy, dummy, 4, 128, 128, 128, C.byref(sp), dummy, 0) == -2
+    assert sm(dummy, dummy, 4, 128, 100, 128, C.byref(sp), dummy, 2) == -2
+    assert sm(dummy, dummy, 4, 128, 128, 128, C.byref(sp), None, 2) == -1
+    assert sm(None, None, 0, 128, 128, 128, C.byref(sp), None, 2) == 0
+    # the masked layer validates like the plain one (the lengths live on the device and are not looked at)
+    assert L.ibert_encoder_layer_masked_i(None, None, dummy, dummy, 1, 128, 768, 12, 3072, dummy, dummy, 1 << 30, None) == -1
+    assert L.ibert_encoder_masked_i(None, None, 1, dummy, dummy, 1, 128, 768, 12, 3072, dummy, dummy, 1 << 30, None) == -1
+    assert L.ibert_attention_masked_i(dummy, dummy, 1, 128, 768, 5, C.byref(dy), C.byref(sp), C.byref(dy), dummy, None, 0, None) == -2
+
+
 def test_single_precision_root_estimate_is_off_by_at_most_one():
     # the LayerNorm kernel takes floor(sqrt(n)) from a correctly rounded single-precision root of n (itself
     # rounded to single precision) plus one integer correction step; the recipe is replayed here in numpy
