@@ -56,6 +56,11 @@ class GeluT(C.Structure):
                 ("out_m", C.c_int32), ("out_s", C.c_int32)]
 
 
+class HGeluT(C.Structure):
+    _fields_ = [("slope_m", C.c_int32), ("slope_s", C.c_int32), ("q_3", C.c_int32), ("q_6", C.c_int32),
+                ("q_max", C.c_int32), ("out_m", C.c_int32), ("out_s", C.c_int32)]
+
+
 _P = C.c_void_p
 
 
@@ -108,6 +113,12 @@ def lib():
         L.orc_gelu_check.argtypes = [C.POINTER(GeluT)]
         L.orc_gelu.restype = C.c_int
         L.orc_gelu.argtypes = [_P, _P, C.c_int64, C.POINTER(GeluT)]
+        L.orc_hgelu_t.restype = C.c_int64
+        L.orc_hgelu_t.argtypes = [C.c_int64, C.POINTER(HGeluT)]
+        L.orc_hgelu_check.restype = C.c_int
+        L.orc_hgelu_check.argtypes = [C.POINTER(HGeluT)]
+        L.orc_hgelu.restype = C.c_int
+        L.orc_hgelu.argtypes = [_P, _P, C.c_int64, C.POINTER(HGeluT)]
         L.orc_layernorm_check.restype = C.c_int
         L.orc_layernorm_check.argtypes = [C.c_int, _P, _P, C.c_int]
         L.orc_layernorm.restype = C.c_int
@@ -269,6 +280,18 @@ def gelu(x: np.ndarray, gp: GeluT) -> np.ndarray:
     x = _arr(x, np.int32)
     y = np.zeros(x.shape, dtype=np.int8)
     _chk(lib().orc_gelu(_ptr(x), _ptr(y), x.size, C.byref(gp)), "gelu")
+    return y
+
+
+def hgelu_t(q: int, hp: HGeluT) -> int:
+    return int(lib().orc_hgelu_t(int(q), C.byref(hp)))
+
+
+def hgelu(x: np.ndarray, hp: HGeluT) -> np.ndarray:
+    """h-GELU (Eq. 6) in integers, requantized to INT8."""
+    x = _arr(x, np.int32)
+    y = np.zeros(x.shape, dtype=np.int8)
+    _chk(lib().orc_hgelu(_ptr(x), _ptr(y), x.size, C.byref(hp)), "hgelu")
     return y
 
 

@@ -27,6 +27,9 @@
  *   orc_iexp             Alg. 3, I-Exp, Eq. 12-14.
  *   orc_softmax          Alg. 3, I-Softmax, Eq. 10-11.
  *   orc_ierf / orc_igelu_t / orc_gelu   Alg. 2, Eq. 8-9.
+ *   orc_hgelu_t / orc_hgelu  h-GELU, Eq. 6 (the alternative the paper measures
+ *                        i-GELU against; given there as a real-valued formula,
+ *                        the integer form below is a reading).
  *   orc_isqrt            Alg. 4.
  *   orc_layernorm        Sec. 3.6, Eq. 15 + Alg. 4.
  *   orc_encoder_layer    Fig. 1 (right) attention block + the rest of a
@@ -320,6 +323,53 @@ int orc_gelu(const int32_t* x, int8_t* y, int64_t n, const orc_gelu_t* p)
     for (int64_t i = 0; i < n; ++i) {
         int64_t t = orc_igelu_t(x[i], p);
         int64_t o = orc_dyadic(t, p->out_m, p->out_s);
+        y[i] = (int8_t)clamp64(o, -127, 127);
+    }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Eq. 6, h-GELU(x) = x ReLU6(1.702 x + 3) / 6, on the integer q of scale S:   */
+/*   q <- clamp(q, -q_max, q_max)                                             */
+/*   u  = clamp(DY(q; slope) + q_3, 0, q_6)   slope ~ 1.702, q_3 = floor(3/S), */
+/*                                            q_6 = floor(6/S); scale S        */
+/*   t  = q u                                 scale S^2 (the 1/6 goes into the */
+/*                                            output multiplier)               */
+/*   y  = clamp(DY(t; out), -127, 127)        out ~ S^2 / (6 S_out)            */
+/* ------------------------------------------------------------------------- */
+typedef struct {
+    int32_t slope_m, slope_s;
+    int32_t q_3, q_6, q_max;
+    int32_t out_m, out_s;
+} orc_hgelu_par_t;
+
+int orc_hgelu_check(const orc_hgelu_par_t* p)
+{
+    if (!p) return ORC_E_ARG;
+    if (!dyadic_ok(p->slope_s) || !dyadic_ok(p->out_s)) return ORC_E_PARAM;
+    if (p->q_3 < 0 || p->q_6 < p->q_3 || p->q_max < 0) return ORC_E_PARAM;
+    if ((i128)p->q_max * p->q_6 > I32_MAX) return ORC_E_PARAM;       /* |t| < 2^31 */
+    return ORC_OK;
+}
+
+int64_t orc_hgelu_t(int64_t q, const orc_hgelu_par_t* p)
+{
+    q = clamp64(q, -(int64_t)p->q_max, p->q_max);
+    int64_t u = orc_dyadic(q, p->slope_m, p->slope_s) + p->q_3;
+    u = u < 0 ? 0 : (u > p->q_6 ? p->q_6 : u);
+    return q * u;
+}
+
+int orc_hgelu(const int32_t* x, int8_t* y, int64_t n, const orc_hgelu_par_t* p)
+{
+    int rc = orc_hgelu_check(p);
+    if (rc) return rc;
+    if (n < 0) return ORC_E_ARG;
+    if (n == 0) return ORC_OK;
+    if (!x || !y) return ORC_E_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t o = orc_dyadic(orc_hgelu_t(x[i], p), p->out_m, p->out_s);
         y[i] = (int8_t)clamp64(o, -127, 127);
     }
     return ORC_OK;

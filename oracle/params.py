@@ -11,7 +11,7 @@ import math
 
 import numpy as np
 
-from . import GeluT, LayerQuantT, SoftmaxT, I8, I32
+from . import GeluT, HGeluT, LayerQuantT, SoftmaxT, I8, I32
 
 LN2 = 0.6931471805599453  # ln 2 rounded to binary64
 
@@ -78,6 +78,18 @@ def gelu_params(S_in: float, S_out: float) -> GeluT:
     p.q_max = (2 ** 31 - 1) // bound
     S_t = S_in * S_erf / 2.0
     p.out_m, p.out_s = dyadic_from_double(S_t / S_out)
+    return p
+
+
+def hgelu_params(S_in: float, S_out: float) -> HGeluT:
+    """Eq. 6 on integers of scale S: slope = dyadic(1.702), q_3 = floor(3/S), q_6 = floor(6/S), q_max the largest
+    input for which q*q_6 fits 31 bits, out = dyadic(S^2 / (6 S_out))."""
+    p = HGeluT()
+    p.slope_m, p.slope_s = dyadic_from_double(1.702)
+    p.q_3 = math.floor(3.0 / S_in)
+    p.q_6 = math.floor(6.0 / S_in)
+    p.q_max = (2 ** 31 - 1) // max(1, p.q_6)
+    p.out_m, p.out_s = dyadic_from_double(S_in * S_in / (6.0 * S_out))
     return p
 
 

@@ -12,6 +12,18 @@ def gelu(x):
     return x * 0.5 * (1.0 + erf(x / np.sqrt(2.0)))
 
 
+def hgelu(x):
+    """Eq. 6: x ReLU6(1.702 x + 3) / 6."""
+    x = np.asarray(x, dtype=np.float64)
+    return x * np.clip(1.702 * x + 3.0, 0.0, 6.0) / 6.0
+
+
+def sigmoid_gelu(x):
+    """Eq. 5: x sigma(1.702 x)."""
+    x = np.asarray(x, dtype=np.float64)
+    return x / (1.0 + np.exp(-1.702 * x))
+
+
 def softmax(x):
     x = np.asarray(x, dtype=np.float64)
     e = np.exp(x - x.max(axis=-1, keepdims=True))
