@@ -207,18 +207,31 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
 
-    if graph is not None:                 # 20 launches per replay: a single one is shorter than a host launch
-        with torch.cuda.stream(stream):
-            embed()
-        torch.cuda.synchronize()
-        ge = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(ge, stream=stream):
-            for _ in range(20):
-                embed()
-        emb_us = timed(ge.replay, 20) * 1e3 / 20
-    else:
-        emb_us = timed(embed, 200) * 1e3
+    emb_us = None                         # set below, once per_launch_us exists
     emb_bytes = c.tokens * (4 + 2 * c.hidden) + c.seq * c.hidden          # ids, a token row in, a row out; positions once
+
+    # h-GELU (the alternative of Eq. 6) next to i-GELU as standalone kernels on the FFN activation [tokens, ffn]
+    gx, gS = synth.gelu_inputs(c.tokens, c.ffn)
+    t_gx = torch.from_numpy(gx.reshape(-1)).to(dev)
+    t_gy = torch.empty(t_gx.numel(), dtype=torch.int8, device=dev)
+    hp, gp = B.ibert_hgelu_params_from_scale(gS, 8.0 / 127), B.ibert_gelu_params_from_scale(gS, 8.0 / 127)
+
+    def per_launch_us(fn):
+        if graph is None:
+            return timed(fn, 200) * 1e3
+        with torch.cuda.stream(stream):
+            fn()
+        torch.cuda.synchronize()
+        g_ = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_, stream=stream):
+            for _ in range(20):
+                fn()
+        return timed(g_.replay, 20) * 1e3 / 20
+
+    emb_us = per_launch_us(embed)         # 20 launches per graph replay: a single one is shorter than a host launch
+    hg_us = per_launch_us(lambda: B.ibert_hgelu_i(t_gx, t_gy, t_gx.numel(), hp, stream=stream))
+    ig_us = per_launch_us(lambda: B.ibert_gelu_i(t_gx, t_gy, t_gx.numel(), gp, stream=stream))
+    gelu_bytes = 5 * t_gx.numel()
     fm = forward_masked
     if graph is not None:
         with torch.cuda.stream(stream):
@@ -233,6 +246,9 @@ def main():
         "embedding": {"kernel": "layernorm_rows_kernel<embedding>", "us": round(emb_us, 2),
                       "GB/s": round(emb_bytes / emb_us / 1e3, 1), "hbm_frac": round(emb_bytes / (emb_us * 1e-6) / PEAK_HBM, 4),
                       "algorithmic_bytes": emb_bytes, "vocab": vocab},
+        "h_gelu": {"kernel": "gelu_kernel<h-GELU>", "us": round(hg_us, 2), "GB/s": round(gelu_bytes / hg_us / 1e3, 1),
+                   "hbm_frac": round(gelu_bytes / (hg_us * 1e-6) / PEAK_HBM, 4), "algorithmic_bytes": gelu_bytes,
+                   "i_gelu_same_shape_us": round(ig_us, 2)},
         "masked_forward": {"ms_per_step": round(masked_ms, 4), "sequences/s": round(c.batch / (masked_ms * 1e-3), 1),
                            "real_tokens/s": round(float(lens.sum()) / (masked_ms * 1e-3), 1),
                            "lengths": "uniform in [seq/4, seq], mean %.1f" % float(lens.mean())},

@@ -154,6 +154,24 @@ typedef struct {
 int ibert_gelu_i(const int32_t* x, int8_t* y, int64_t n, const ibert_gelu_params* params, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * ibert_hgelu_i -- h-GELU, the integer-friendly alternative the paper compares i-GELU with (Eq. 6; Table 1):
+ * x ReLU6(1.702 x + 3) / 6.  The paper gives only the real-valued formula; reading, on integers of scale S:
+ *   q   <- clamp(q, -q_max, q_max)
+ *   u    = clamp(DY(q; slope) + q_3, 0, q_6)            slope ~ 1.702, q_3 = floor(3/S), q_6 = floor(6/S)
+ *   t    = q * u                                        (scale S^2; the division by 6 is part of `out`)
+ *   y    = clamp(DY(t; out), -127, 127)                 out ~ S^2 / (6 S_out)
+ * Preconditions (else IBERT_ERR_PARAM_RANGE): 0 <= q_3 <= q_6, q_max >= 0, q_max * q_6 <= 2^31-1, both shifts in
+ * [0, 62].  x: device int32 [n]; y: device int8 [n]; params: host.  Not used by ibert_encoder_layer_i.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+    ibert_dyadic slope;
+    int32_t q_3, q_6, q_max;
+    ibert_dyadic out;
+} ibert_hgelu_params;
+
+int ibert_hgelu_i(const int32_t* x, int8_t* y, int64_t n, const ibert_hgelu_params* params, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
  * ibert_gemm_i8_gelu -- the FFN up-projection and its GELU in one call (Sec. 4.1: the MatMul result is
  * requantized to the GELU input scale; Alg. 2 follows), bit-identical to
  *     ibert_gemm_i8_requant(desc with out_dtype = IBERT_I32, out_clamp = gelu->q_max, no residual) -> f
@@ -302,6 +320,9 @@ int ibert_softmax_params_from_scale(double S, int32_t cols, int32_t out_frac_bit
  * q_c = q_1 = floor(1/S_erf); q_max = floor((2^31-1) / (max(|q_c|,|q_b^2+q_c|) + |q_1|));
  * out = dyadic((S_in*S_erf/2) / S_out). */
 int ibert_gelu_params_from_scale(double S_in, double S_out, ibert_gelu_params* out);
+/* h-GELU: slope = dyadic(1.702), q_3 = floor(3/S_in), q_6 = floor(6/S_in), q_max = floor((2^31-1) / max(1, q_6)),
+ * out = dyadic(S_in^2 / (6 S_out)).  S_in, S_out > 0 and finite, q_6 must fit 31 bits. */
+int ibert_hgelu_params_from_scale(double S_in, double S_out, ibert_hgelu_params* out);
 
 /* gamma_q[i] = rint(gamma[i]/S_out * 2^(shift-10)), beta_q[i] = rint(beta[i]/S_out * 2^shift) with the
  * largest shift in [1,30] such that max|gamma_q| < 2^14 and max|beta_q| < 2^29 (host arrays). */

@@ -59,6 +59,10 @@ class GeluParams(C.Structure):
                 ("out", Dyadic)]
 
 
+class HGeluParams(C.Structure):
+    _fields_ = [("slope", Dyadic), ("q_3", C.c_int32), ("q_6", C.c_int32), ("q_max", C.c_int32), ("out", Dyadic)]
+
+
 class LayerWeights(C.Structure):
     _fields_ = [(n, _P) for n in (
         "w_qkv", "b_qkv", "m_qkv", "s_qkv", "w_o", "b_o", "m_o", "s_o", "ln1_gamma_q", "ln1_beta_q",
@@ -105,6 +109,8 @@ SIGNATURES = {
                                [C.c_int32] * 5 + [_P, _P, C.c_size_t, _P]),
     "ibert_softmax_i": (C.c_int, [_P, _P, C.c_int64, C.c_int32, C.c_int64, C.c_int64, C.POINTER(SoftmaxParams), _P]),
     "ibert_gelu_i": (C.c_int, [_P, _P, C.c_int64, C.POINTER(GeluParams), _P]),
+    "ibert_hgelu_i": (C.c_int, [_P, _P, C.c_int64, C.POINTER(HGeluParams), _P]),
+    "ibert_hgelu_params_from_scale": (C.c_int, [C.c_double, C.c_double, C.POINTER(HGeluParams)]),
     "ibert_layernorm_i": (C.c_int, [_P, _P, C.c_int64, C.c_int32, C.c_int64, C.c_int64, _P, _P, C.c_int32, _P]),
     "ibert_encoder_layer_workspace_bytes": (C.c_size_t, [C.c_int32] * 5),
     "ibert_encoder_layer_workspace_layout": (C.c_int, [C.c_int32] * 5 + [C.POINTER(WorkspaceLayout)]),
@@ -266,6 +272,16 @@ def ibert_softmax_i(x, y, rows: int, cols: int, ldx: int, ldy: int, params: Soft
 
 def ibert_gelu_i(x, y, n: int, params: GeluParams, stream=None):
     _chk(lib().ibert_gelu_i(_dp(x), _dp(y), n, C.byref(params), _stream(stream)), "ibert_gelu_i")
+
+
+def ibert_hgelu_params_from_scale(S_in: float, S_out: float) -> HGeluParams:
+    p = HGeluParams()
+    _chk(lib().ibert_hgelu_params_from_scale(float(S_in), float(S_out), C.byref(p)), "ibert_hgelu_params_from_scale")
+    return p
+
+
+def ibert_hgelu_i(x, y, n: int, params: HGeluParams, stream=None):
+    _chk(lib().ibert_hgelu_i(_dp(x), _dp(y), n, C.byref(params), _stream(stream)), "ibert_hgelu_i")
 
 
 def ibert_layernorm_i(x, y, rows: int, Cc: int, ldx: int, ldy: int, gamma_q, beta_q, shift: int, stream=None):

@@ -132,6 +132,7 @@ int launch_softmax(const int32_t* x, void* y, int64_t rows, int32_t cols, int64_
                    const ibert_softmax_params& p, hipStream_t stream, const int32_t* key_lens = nullptr,
                    int64_t rows_per_len = 0);
 int launch_gelu(const int32_t* x, int8_t* y, int64_t n, const ibert_gelu_params& p, hipStream_t stream);
+int launch_hgelu(const int32_t* x, int8_t* y, int64_t n, const ibert_hgelu_params& p, hipStream_t stream);
 int launch_layernorm(const int32_t* x, int8_t* y, int64_t rows, int32_t C, int64_t ldx, int64_t ldy,
                      const int32_t* gamma_q, const int32_t* beta_q, int32_t shift, hipStream_t stream);
 int launch_embedding(const int32_t* ids, const int8_t* tok, const int8_t* pos, int64_t tokens, int32_t seq, int32_t C,
@@ -143,6 +144,7 @@ int check_gemm(const ibert_gemm_desc& d, const void* A, const void* W, const voi
                const void* shift, const void* residual, const void* C);
 int check_softmax(const ibert_softmax_params& p, int32_t cols);
 int check_gelu(const ibert_gelu_params& p);
+int check_hgelu(const ibert_hgelu_params& p);
 int check_layernorm(int32_t C, int32_t shift);
 
 }  // namespace ibert

@@ -11,17 +11,23 @@ struct GeluArgs {
     int8_t* y;
     int64_t n;
     GeluConst c;
+    HGeluConst h;       // read by the h-GELU instantiations only
 };
 
 constexpr int GELU_THREADS = 256;
 constexpr int GELU_UNROLL = 4;                        // 16-byte chunks per lane
 
-template <bool VEC, bool FAST>
+// HG: h-GELU (Eq. 6) instead of i-GELU (Alg. 2); the streaming skeleton is the same.
+template <bool VEC, bool FAST, bool HG = false>
 __global__ __launch_bounds__(GELU_THREADS) void gelu_kernel(GeluArgs a)
 {
     const int64_t block_base = (int64_t)blockIdx.x * (GELU_THREADS * GELU_UNROLL * 4);
-    const int32_t rnd = 1 << ((a.c.s - 33) & 31), sh = (a.c.s - 32) & 31;
-    auto one = [&](int32_t q) { return FAST ? gelu_one_fast(q, a.c, rnd, sh) : gelu_one(q, a.c); };
+    const int32_t out_s = HG ? a.h.s : a.c.s;
+    const int32_t rnd = 1 << ((out_s - 33) & 31), sh = (out_s - 32) & 31;
+    auto one = [&](int32_t q) {
+        if (HG) return FAST ? hgelu_one_fast(q, a.h, rnd, sh) : hgelu_one(q, a.h);
+        return FAST ? gelu_one_fast(q, a.c, rnd, sh) : gelu_one(q, a.c);
+    };
     if (VEC) {
         int4 v[GELU_UNROLL];
         int64_t base[GELU_UNROLL];
@@ -60,10 +66,37 @@ int check_gelu(const ibert_gelu_params& p)
     return IBERT_OK;
 }
 
+int check_hgelu(const ibert_hgelu_params& p)
+{
+    if (!dyadic_ok(p.slope) || !dyadic_ok(p.out)) return IBERT_ERR_PARAM_RANGE;
+    if (p.q_3 < 0 || p.q_6 < p.q_3 || p.q_max < 0) return IBERT_ERR_PARAM_RANGE;
+    if ((__int128)p.q_max * p.q_6 > 2147483647LL) return IBERT_ERR_PARAM_RANGE;
+    return IBERT_OK;
+}
+
+int launch_hgelu(const int32_t* x, int8_t* y, int64_t n, const ibert_hgelu_params& p, hipStream_t stream)
+{
+    if (n == 0) return IBERT_OK;
+    GeluArgs a{x, y, n, GeluConst{}, HGeluConst{p.slope.m, p.slope.s, p.q_3, p.q_6, p.q_max, p.out.m, p.out.s}};
+    const int64_t per_block = (int64_t)GELU_THREADS * GELU_UNROLL * 4;
+    const int64_t blocks = (n + per_block - 1) / per_block;
+    if (blocks > 0x7fffffffLL) return IBERT_ERR_SHAPE;
+    const bool vec = aligned(x, 16) && aligned(y, 4);
+    const bool fast = hgelu_fast_ok(p);
+    const dim3 grid((unsigned)blocks), block(GELU_THREADS);
+    if (vec && fast) hipLaunchKernelGGL((gelu_kernel<true, true, true>), grid, block, 0, stream, a);
+    else if (vec) hipLaunchKernelGGL((gelu_kernel<true, false, true>), grid, block, 0, stream, a);
+    else if (fast) hipLaunchKernelGGL((gelu_kernel<false, true, true>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((gelu_kernel<false, false, true>), grid, block, 0, stream, a);
+    IBERT_LAUNCH_CHECK("gelu_kernel<h-GELU>");
+    g_last_kernel = "gelu_kernel<h-GELU>";
+    return IBERT_OK;
+}
+
 int launch_gelu(const int32_t* x, int8_t* y, int64_t n, const ibert_gelu_params& p, hipStream_t stream)
 {
     if (n == 0) return IBERT_OK;
-    GeluArgs a{x, y, n, GeluConst{p.q_b, p.q_c, p.q_1, p.q_max, p.out.m, p.out.s}};
+    GeluArgs a{x, y, n, GeluConst{p.q_b, p.q_c, p.q_1, p.q_max, p.out.m, p.out.s}, HGeluConst{}};
     const int64_t per_block = (int64_t)GELU_THREADS * GELU_UNROLL * 4;
     const int64_t blocks = (n + per_block - 1) / per_block;
     if (blocks > 0x7fffffffLL) return IBERT_ERR_SHAPE;
@@ -90,4 +123,15 @@ extern "C" int ibert_gelu_i(const int32_t* x, int8_t* y, int64_t n, const ibert_
     if (n == 0) return IBERT_OK;
     if (!x || !y) return IBERT_ERR_NULL;
     return ibert::launch_gelu(x, y, n, *params, (hipStream_t)stream);
+}
+
+extern "C" int ibert_hgelu_i(const int32_t* x, int8_t* y, int64_t n, const ibert_hgelu_params* params, void* stream)
+{
+    if (!params) return IBERT_ERR_NULL;
+    if (n < 0) return IBERT_ERR_SHAPE;
+    const int rc = ibert::check_hgelu(*params);
+    if (rc) return rc;
+    if (n == 0) return IBERT_OK;
+    if (!x || !y) return IBERT_ERR_NULL;
+    return ibert::launch_hgelu(x, y, n, *params, (hipStream_t)stream);
 }

@@ -124,6 +124,22 @@ int ibert_gelu_params_from_scale(double S_in, double S_out, ibert_gelu_params* o
     return ibert::check_gelu(*out);
 }
 
+int ibert_hgelu_params_from_scale(double S_in, double S_out, ibert_hgelu_params* out)
+{
+    if (!out) return IBERT_ERR_NULL;
+    if (!(S_in > 0.0) || !(S_out > 0.0) || !std::isfinite(S_in) || !std::isfinite(S_out)) return IBERT_ERR_PARAM_RANGE;
+    int rc = ibert_dyadic_from_double(1.702, &out->slope);                    // Eq. 6
+    if (rc) return rc;
+    const double q_3 = std::floor(3.0 / S_in), q_6 = std::floor(6.0 / S_in);
+    if (q_6 > 2147483647.0) return IBERT_ERR_PARAM_RANGE;
+    out->q_3 = (int32_t)q_3;
+    out->q_6 = (int32_t)q_6;
+    out->q_max = (int32_t)(2147483647LL / (out->q_6 > 1 ? out->q_6 : 1));
+    rc = ibert_dyadic_from_double(S_in * S_in / (6.0 * S_out), &out->out);
+    if (rc) return rc;
+    return ibert::check_hgelu(*out);
+}
+
 int ibert_layernorm_params_from_float(const double* gamma, const double* beta, int32_t C, double S_out,
                                       int32_t* gamma_q, int32_t* beta_q, int32_t* shift)
 {

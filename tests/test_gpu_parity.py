@@ -50,6 +50,43 @@ def test_gelu_matches_oracle(G, S_in, S_out):
             _eq(G.gelu(x[:n], gp, x_off=xo, y_off=yo), oracle.gelu(x[:n], op), "gelu n=%d" % n)
 
 
+@pytest.mark.parametrize("S_in,S_out", [(2.0 ** -7, 8.0 / 127), (2.0 ** -6, 0.406), (2.0 ** -4, 0.1), (0.011, 0.02),
+                                        (2.0 ** -13, 0.05), (0.9, 0.3)])
+def test_hgelu_matches_oracle(G, S_in, S_out):
+    # Eq. 6 in integers; scales of 2^-4 and above leave the 24-bit forms (q_max reaches 2^23), 2^-13 has a large q_6
+    from paper_2101_01321_amd import binding as B
+    hp, op = B.ibert_hgelu_params_from_scale(S_in, S_out), P.hgelu_params(S_in, S_out)
+    x, _ = synth.gelu_inputs(517, 3072, scale=S_in)
+    x = x.reshape(-1)
+    x[:8] = [0, 1, -1, 2 ** 31 - 1, -2 ** 31, hp.q_max, -hp.q_max, hp.q_max + 1]
+    x[8:4008] = np.arange(-2000, 2000)
+    want = oracle.hgelu(x, op)
+    assert len(np.unique(want)) > 3
+    G.say("h-GELU S_in=%g n=%d" % (S_in, x.size))
+    _eq(G.hgelu(x, hp), want, "h-GELU")
+    for n, xo, yo in [(1, 0, 0), (3, 0, 0), (4097, 0, 0), (5000, 1, 0), (5000, 0, 3), (16385, 3, 1)]:
+        G.say("h-GELU ragged n=%d x_off=%d y_off=%d" % (n, xo, yo))
+        _eq(G.hgelu(x[:n], hp, x_off=xo, y_off=yo), want[:n], "h-GELU n=%d" % n)
+    # hand-made constants outside what the helper produces: negative slope, shifts at the ends of the range
+    for slope, out in (((-1827387392, 30), (1518500250, 40)), ((1827387392, 0), (1518500250, 62)), ((3, 1), (5, 2)),
+                       ((1827387392, 31), (1518500250, 33)), ((1827387392, 32), (-1518500250, 36))):
+        hp2, op2 = B.ibert_hgelu_params_from_scale(S_in, S_out), P.hgelu_params(S_in, S_out)
+        hp2.slope.m, hp2.slope.s, hp2.out.m, hp2.out.s = slope[0], slope[1], out[0], out[1]
+        op2.slope_m, op2.slope_s, op2.out_m, op2.out_s = slope[0], slope[1], out[0], out[1]
+        if slope[1] == 0:
+            hp2.q_max = op2.q_max = min(hp2.q_max, 1)        # slope 2^30.8: keep DY(q; slope) inside 64 bits either way
+        G.say("h-GELU constants slope=%s out=%s" % (slope, out))
+        _eq(G.hgelu(x[:20000], hp2), oracle.hgelu(x[:20000], op2), "h-GELU slope=%s out=%s" % (slope, out))
+
+
+def test_hgelu_full_shape(G):
+    from paper_2101_01321_amd import binding as B
+    x, S = synth.gelu_inputs(4096, 3072)                     # the FFN activation of Base, batch 32
+    hp, op = B.ibert_hgelu_params_from_scale(S, 8.0 / 127), P.hgelu_params(S, 8.0 / 127)
+    G.say("h-GELU full [4096,3072]")
+    _eq(G.hgelu(x, hp), oracle.hgelu(x, op).reshape(-1), "h-GELU full")
+
+
 def test_gelu_full_shape(G):
     from paper_2101_01321_amd import binding as B
     x, S = synth.gelu_inputs(4096, 3072)                     # configs[1]: N(0,2) at scale 2^-7

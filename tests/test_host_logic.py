@@ -75,6 +75,10 @@ def test_softmax_gelu_layernorm_helpers_agree_with_the_oracle_derivation():
         w = P.gelu_params(float(S), S_out)
         g = B.ibert_gelu_params_from_scale(float(S), S_out)
         assert (g.q_b, g.q_c, g.q_1, g.q_max, g.out.m, g.out.s) == (w.q_b, w.q_c, w.q_1, w.q_max, w.out_m, w.out_s)
+        hw = P.hgelu_params(float(S), S_out)
+        hg = B.ibert_hgelu_params_from_scale(float(S), S_out)
+        assert (hg.slope.m, hg.slope.s, hg.q_3, hg.q_6, hg.q_max, hg.out.m, hg.out.s) == \
+               (hw.slope_m, hw.slope_s, hw.q_3, hw.q_6, hw.q_max, hw.out_m, hw.out_s)
     for C_ in (1, 7, 256, 768, 1024):
         gamma = RNG.normal(1.0, 0.1, size=C_)
         beta = RNG.normal(0.0, 0.1, size=C_)
@@ -229,6 +233,14 @@ def test_embedding_and_masked_entry_points_reject_bad_arguments_before_touching_
     assert but(tdy=C.byref(B.Dyadic(1, 63))) == -3 and but(H=1025, ldy=1025) == -3 and but(sh=0) == -3 and but(sh=31) == -3
     assert but(T=0, ids=None, y=None) == 0                                     # no tokens: nothing to do
     assert but(ids=None) == -1 and but(tok=None) == -1 and but(y=None) == -1 and but(g=None) == -1
+    # h-GELU
+    hp = B.ibert_hgelu_params_from_scale(2.0 ** -6, 0.05)
+    assert L.ibert_hgelu_i(dummy, dummy, 8, None, None) == -1 and L.ibert_hgelu_i(dummy, dummy, -1, C.byref(hp), None) == -2
+    assert L.ibert_hgelu_i(None, None, 0, C.byref(hp), None) == 0 and L.ibert_hgelu_i(None, dummy, 8, C.byref(hp), None) == -1
+    for field, val in (("q_max", 2 ** 31 - 1), ("q_3", -1), ("q_6", 5)):
+        bad = B.ibert_hgelu_params_from_scale(2.0 ** -6, 0.05)
+        setattr(bad, field, val)
+        assert L.ibert_hgelu_i(dummy, dummy, 8, C.byref(bad), None) == -3
     # masked Softmax
     sp = B.ibert_softmax_params_from_scale(2.0 ** -6, 128)
     sm = lambda x, y, rows, cols, ldx, ldy, p, kl, rpl: L.ibert_softmax_masked_i(x, y, rows, cols, ldx, ldy, p, kl, rpl, None)

@@ -292,3 +292,14 @@ def test_isqrt_squares_neighbours_and_random_uint32():
     # (the result is still exact), so nothing may hard-code four.
     assert oracle.isqrt(17413928) == (math.isqrt(17413928), 6)
     assert iters.max() <= 7
+
+
+def test_error_curve_report_regenerates_table1(capsys):
+    from oracle import error_curves
+    dist, gap = error_curves.main(["--scale", str(2.0 ** -8), "--samples", "3"])
+    tab = _table1()
+    for name, key in (("h-GELU", "h_gelu"), ("i-GELU", "i_gelu")):
+        assert abs(dist[name][0] - tab[key][0]) < _unit_of_last_printed_digit(tab[key][0])
+        assert abs(dist[name][1] - tab[key][1]) < _unit_of_last_printed_digit(tab[key][1])
+    assert gap < 2.13e-3 + 4 * 2.0 ** -8                     # the real-valued gap plus the scale's own resolution
+    assert "Table 1" in capsys.readouterr().out
