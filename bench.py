@@ -42,6 +42,97 @@ def measured_traffic(kernel, config):
     return None if e is None else e["read"] + e["written"]
 
 
+def latency_grid(args):
+    """The paper's latency grid (Table 3: BERT-Base / BERT-Large, sequence length 128 / 256, batch 1 / 2 / 4 / 8) on
+    this GPU: the integer encoder of this library against a plain PyTorch float encoder of the same shape (FP32 and
+    BF16; library GEMMs, unfused softmax / GELU / LayerNorm -- the counterpart of the paper's FP32 baseline), each
+    replayed from a HIP graph.  Prints one JSON line."""
+    import numpy as np
+    import torch
+    import torch.nn.functional as F
+    from paper_2101_01321_amd import binding as B, synth
+
+    B.lib()
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.Stream()
+
+    def timed_graph(fn, reps):
+        with torch.cuda.stream(stream):
+            fn()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(stream):
+            for _ in range(5):
+                g.replay()
+            e0.record(stream)
+            for _ in range(reps):
+                g.replay()
+            e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def float_encoder(c, dtype):
+        gen = torch.Generator(device="cpu").manual_seed(1)
+        def w(*shape):
+            return (torch.randn(*shape, generator=gen) * 0.02).to(dev, dtype)
+        layers = [dict(w_qkv=w(3 * c.hidden, c.hidden), b_qkv=w(3 * c.hidden), w_o=w(c.hidden, c.hidden), b_o=w(c.hidden),
+                       w_1=w(c.ffn, c.hidden), b_1=w(c.ffn), w_2=w(c.hidden, c.ffn), b_2=w(c.hidden),
+                       g1=torch.ones(c.hidden, device=dev, dtype=dtype), be1=torch.zeros(c.hidden, device=dev, dtype=dtype),
+                       g2=torch.ones(c.hidden, device=dev, dtype=dtype), be2=torch.zeros(c.hidden, device=dev, dtype=dtype))
+                  for _ in range(c.layers)]
+        dh = c.hidden // c.heads
+
+        def run(x, Bn, L):
+            for p in layers:
+                qkv = F.linear(x, p["w_qkv"], p["b_qkv"]).view(Bn, L, 3, c.heads, dh).permute(2, 0, 3, 1, 4)
+                a = torch.softmax(torch.matmul(qkv[0], qkv[1].transpose(-1, -2)) * (dh ** -0.5), dim=-1)
+                ctx = torch.matmul(a, qkv[2]).permute(0, 2, 1, 3).reshape(Bn * L, c.hidden)
+                h = F.layer_norm(F.linear(ctx, p["w_o"], p["b_o"]) + x, (c.hidden,), p["g1"], p["be1"])
+                f = F.linear(F.gelu(F.linear(h, p["w_1"], p["b_1"])), p["w_2"], p["b_2"])
+                x = F.layer_norm(f + h, (c.hidden,), p["g2"], p["be2"])
+            return x
+        return run
+
+    cells = []
+    for model, base in (("base", synth.CONFIGS["base_b32"]), ("large", synth.CONFIGS["large_b32"])):
+        big = synth.EncoderConfig(model, base.hidden, base.heads, base.ffn, 256, 8, base.layers)
+        x_q, S_x, _ = synth.input_activations(big)
+        scales = synth.model_scales(big, S_x)
+        layers = [B.DeviceLayer(synth.layer_raw(big, l), scales[l], big.hidden, big.heads, big.seq, dev) for l in range(big.layers)]
+        weights = (B.LayerWeights * big.layers)(*[l.weights for l in layers])
+        quant = (B.LayerQuant * big.layers)(*[l.quant for l in layers])
+        ws = torch.zeros(B.ibert_encoder_workspace_bytes(big.batch, big.seq, big.hidden, big.heads, big.ffn), dtype=torch.uint8, device=dev)
+        xq = torch.from_numpy(x_q).to(dev)
+        f32, bf16 = float_encoder(big, torch.float32), float_encoder(big, torch.bfloat16)
+        for L in (128, 256):
+            for Bn in (1, 2, 4, 8):
+                T = Bn * L
+                xi = xq[:T].contiguous()
+                yi = torch.empty_like(xi)
+                t_int = timed_graph(lambda: B.ibert_encoder_i(weights, quant, big.layers, xi, yi, Bn, L, big.hidden, big.heads,
+                                                              big.ffn, ws, stream=stream), args.steps)
+                res = {"model": model, "seq": L, "batch": Bn, "int8_ms": round(t_int, 4)}
+                for name, enc, dt in (("fp32", f32, torch.float32), ("bf16", bf16, torch.bfloat16)):
+                    xf = torch.randn(T, big.hidden, device=dev, dtype=dt)
+                    out = {}
+                    def run_float():
+                        out["y"] = enc(xf, Bn, L)
+                    res[name + "_ms"] = round(timed_graph(run_float, args.steps), 4)
+                res["speedup_vs_fp32"] = round(res["fp32_ms"] / res["int8_ms"], 2)
+                res["speedup_vs_bf16"] = round(res["bf16_ms"] / res["int8_ms"], 2)
+                cells.append(res)
+                print("grid %s L=%d B=%d: int8 %.3f ms, fp32 %.3f ms, bf16 %.3f ms" % (
+                    model, L, Bn, res["int8_ms"], res["fp32_ms"], res["bf16_ms"]), file=sys.stderr, flush=True)
+        del layers, ws, f32, bf16
+        torch.cuda.empty_cache()
+    print(json.dumps({"metric": "latency grid, full encoder forward (ms per forward, HIP-graph replay)", "n_gpus": 1,
+                      "steps": args.steps, "data": "synthetic", "float_reference": "PyTorch %s eager ops in a graph" % torch.__version__,
+                      "cells": cells}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -53,10 +144,15 @@ def main():
     ap.add_argument("--cpu-seqs", type=int, default=8, help="sequences of the workload the CPU oracle runs")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 256 MiB device copies (reference for the FETCH_SIZE/WRITE_SIZE counters)")
+    ap.add_argument("--latency-grid", action="store_true",
+                    help="instead of the headline workload: Base/Large x seq 128/256 x batch 1/2/4/8, integer path vs a PyTorch float encoder")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.latency_grid:
+        return latency_grid(args)
 
     import numpy as np
     import torch
