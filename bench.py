@@ -144,6 +144,8 @@ def main():
     ap.add_argument("--cpu-seqs", type=int, default=8, help="sequences of the workload the CPU oracle runs")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 256 MiB device copies (reference for the FETCH_SIZE/WRITE_SIZE counters)")
+    ap.add_argument("--fusion", type=int, default=-1,
+                    help="fusion mask of the layer (bit 0 GELU, bit 1 attention, bit 2 LayerNorm); default: the library's (7)")
     ap.add_argument("--latency-grid", action="store_true",
                     help="instead of the headline workload: Base/Large x seq 128/256 x batch 1/2/4/8, integer path vs a PyTorch float encoder")
     args = ap.parse_args()
@@ -159,6 +161,8 @@ def main():
     from paper_2101_01321_amd import binding as B, synth
 
     B.lib()
+    if args.fusion >= 0:
+        B.ibert_set_fusion(args.fusion)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     cfg = synth.CONFIGS[args.config]
@@ -385,7 +389,8 @@ def main():
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "%s: %d layers, hidden %d, heads %d, ffn %d, seq %d, batch %d" % (
             c.name, c.layers, c.hidden, c.heads, c.ffn, c.seq, c.batch),
-            "launch": "hip-graph replay" if graph is not None else "host launches"},
+            "launch": "hip-graph replay" if graph is not None else "host launches",
+            "fusion_mask": B.ibert_set_fusion(-1)},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "per_step": step_table,

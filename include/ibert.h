@@ -265,7 +265,11 @@ typedef struct {
 
 /* Byte offsets of the intermediates inside the workspace (each 256-byte aligned). */
 typedef struct {
-    size_t qkv, scores, probs, ctx, r1, h1, f1, g, r2, total;
+    size_t qkv, scores, probs, ctx, r1, h1, f1, g, r2;
+    size_t ln_stats;   /* row statistics shared by the column tiles of a fused MatMul + LayerNorm; its last 4 bytes are a
+                          status word: bit 0 is set (never cleared by the library) if a tile ever gave up waiting for
+                          its neighbours, in which case that call's output is wrong; stays 0 in a healthy run */
+    size_t total;
 } ibert_layer_workspace_layout;
 
 size_t ibert_encoder_layer_workspace_bytes(int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn);
@@ -364,12 +368,37 @@ int ibert_attention_masked_i(const int8_t* qkv, int8_t* ctx, int32_t batch, int3
                              const ibert_dyadic* ctx_dy, const int32_t* key_lens, void* scratch, size_t scratch_bytes,
                              void* stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * ibert_gemm_i8_layernorm -- a projection with residual and the LayerNorm that follows it in one call (steps 5+6 and
+ * 9+10 of the layer; App. C.1, Sec. 3.6), bit-identical to
+ *     ibert_gemm_i8_requant(desc with out_dtype = IBERT_I32, out_clamp = 2^15-1) -> r   [M, N] int32
+ *     ibert_layernorm_i(r; gamma_q, beta_q, ln_shift) -> y
+ * desc: one problem (batch_outer = batch_inner = 1), out_dtype IBERT_I32, out_clamp 32767 (else IBERT_ERR_SHAPE);
+ * ldc is ignored.  1 <= N <= 1024.  y: device int8 [M, ldy].
+ * One kernel when M is a multiple of 128, N a multiple of 96 or 128, K a multiple of 128, all rows 16-byte aligned,
+ * and the problem is of the size for which the library uses 128-row tiles anyway (about one tile per compute unit:
+ * e.g. 4096 tokens at hidden 768 or 1024; ibert_gemm_config_override 7, 9, 11 or 12 forces it), with bit 2 of the
+ * fusion mask set: the column tiles of a row
+ * exchange the row's sum and sum of squares through integer atomics in `scratch` and normalize their own part, so r is
+ * never stored.  Otherwise two kernels through r in `scratch`.
+ * scratch: device, 256-byte aligned, ibert_gemm_layernorm_scratch_bytes(M, N) bytes (IBERT_ERR_WORKSPACE); its last word
+ * is the status word described at ibert_layer_workspace_layout.
+ * ---------------------------------------------------------------------------------------------- */
+size_t ibert_gemm_layernorm_scratch_bytes(int32_t M, int32_t N);
+int ibert_gemm_i8_layernorm(const ibert_gemm_desc* desc, const int8_t* A, const int8_t* W, const int32_t* bias,
+                            const int32_t* mult, const int32_t* shift, const int8_t* residual, const int32_t* gamma_q,
+                            const int32_t* beta_q, int32_t ln_shift, int8_t* y, int64_t ldy, void* scratch,
+                            size_t scratch_bytes, void* stream);
+
 /* Kernel fusions inside ibert_encoder_layer_i / ibert_encoder_i (and ibert_attention_i).
  *   bit 0: steps 7 and 8 (FFN up-projection and GELU) run as one kernel where ibert_gemm_i8_gelu can do so; the
  *          workspace region f1 is then left untouched;
  *   bit 1: steps 2, 3 and 4 run as one kernel where ibert_attention_i can do so; the workspace regions scores
- *          and probs are then left untouched (profile records: one, numbered 2).
- * Default: 3.  flags >= 0 sets the mask (unknown bits are dropped), a negative value only queries.  Returns the
+ *          and probs are then left untouched (profile records: one, numbered 2);
+ *   bit 2: steps 5+6 and steps 9+10 (projection with residual, then LayerNorm) each run as one kernel where
+ *          ibert_gemm_i8_layernorm can do so; the workspace regions r1 / r2 are then left untouched (profile records:
+ *          one per pair, numbered 5 / 9).
+ * Default: 7.  flags >= 0 sets the mask (unknown bits are dropped), a negative value only queries.  Returns the
  * previous mask.  Outputs do not depend on the mask.  Not thread-safe. */
 int ibert_set_fusion(int32_t flags);
 

@@ -75,7 +75,7 @@ class LayerQuant(C.Structure):
 
 
 class WorkspaceLayout(C.Structure):
-    _fields_ = [(n, C.c_size_t) for n in ("qkv", "scores", "probs", "ctx", "r1", "h1", "f1", "g", "r2", "total")]
+    _fields_ = [(n, C.c_size_t) for n in ("qkv", "scores", "probs", "ctx", "r1", "h1", "f1", "g", "r2", "ln_stats", "total")]
 
 
 class LayerScales(C.Structure):
@@ -94,6 +94,8 @@ SIGNATURES = {
     "ibert_gemm_config_override": (C.c_int, [C.c_int32]),
     "ibert_gemm_i8_gelu": (C.c_int, [C.POINTER(GemmDesc)] + [_P] * 5 + [C.POINTER(GeluParams)] + [_P] * 3),
     "ibert_set_fusion": (C.c_int, [C.c_int32]),
+    "ibert_gemm_layernorm_scratch_bytes": (C.c_size_t, [C.c_int32, C.c_int32]),
+    "ibert_gemm_i8_layernorm": (C.c_int, [C.POINTER(GemmDesc)] + [_P] * 8 + [C.c_int32, _P, C.c_int64, _P, C.c_size_t, _P]),
     "ibert_attention_scratch_bytes": (C.c_size_t, [C.c_int32] * 3),
     "ibert_attention_i": (C.c_int, [_P, _P] + [C.c_int32] * 4 + [C.POINTER(Dyadic), C.POINTER(SoftmaxParams),
                                                                  C.POINTER(Dyadic), _P, C.c_size_t, _P]),
@@ -259,6 +261,17 @@ def ibert_embedding_i(ids, tok, pos, tokens: int, seq: int, hidden: int, vocab: 
     _chk(lib().ibert_embedding_i(_dp(ids), _dp(tok), _dp(pos), tokens, seq, hidden, vocab, max_pos, C.byref(tok_dy),
                                  C.byref(pos_dy), _dp(gamma_q), _dp(beta_q), ln_shift, _dp(y), ldy, _stream(stream)),
          "ibert_embedding_i")
+
+
+def ibert_gemm_layernorm_scratch_bytes(M: int, N: int) -> int:
+    return int(lib().ibert_gemm_layernorm_scratch_bytes(M, N))
+
+
+def ibert_gemm_i8_layernorm(desc: GemmDesc, A, W, bias, mult, shift, residual, gamma_q, beta_q, ln_shift: int, y, ldy: int,
+                            scratch, stream=None):
+    _chk(lib().ibert_gemm_i8_layernorm(C.byref(desc), _dp(A), _dp(W), _dp(bias), _dp(mult), _dp(shift), _dp(residual),
+                                       _dp(gamma_q), _dp(beta_q), ln_shift, _dp(y), ldy, _dp(scratch),
+                                       scratch.numel() * scratch.element_size(), _stream(stream)), "ibert_gemm_i8_layernorm")
 
 
 def ibert_set_fusion(flags: int) -> int:

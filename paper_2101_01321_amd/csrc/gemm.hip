@@ -18,6 +18,7 @@
 
 #include "common.h"
 #include "gelu_math.h"
+#include "layernorm_math.h"
 
 namespace ibert {
 
@@ -49,6 +50,19 @@ struct GemmArgs {
     int32_t gelu_fast; // GELU epilogue: the 24-bit form applies
     int32_t gelu_lut_lo, gelu_lut_n;   // GELU epilogue: table of the values at lo .. lo + n - 1 behind the tile's LDS (n = 0: none)
     GeluConst gelu;    // GELU epilogue: constants (the clamp before it is out_clamp = q_max)
+    // LayerNorm epilogue (LN kernels only): the requantized row is normalized before it leaves the registers
+    const int32_t* ln_gamma;
+    const int32_t* ln_beta;
+    int8_t* ln_y;
+    int64_t ln_ldy;
+    unsigned long long* ln_sum;    // [M] row sums with their contribution counts, zero on entry
+    unsigned long long* ln_sq;     // [M] row sums of squares with their contribution counts, zero on entry
+    uint32_t* ln_status;           // bit 0 is set if a wait for the other tiles of a row ever ran out
+    int32_t ln_shift;
+    uint32_t ln_magic;             // reciprocal multiplier for the divisions by N
+    // Words every launch clears on its way in (the row statistics of the LayerNorm epilogue that runs next)
+    uint32_t* zero_p;
+    int64_t zero_words;
 #ifdef IBERT_KERNEL_TIMING
     long long* dbg;    // development only: per-wave phase timestamps
 #endif
@@ -141,10 +155,20 @@ struct EpiLayout {
 // fragment reads of the next phase and (second phase) the loads of the step after next, one barrier per step.
 // GELU = true (INT8 output): the requantized, clamped value is the GELU input; integer GELU (Alg. 2) and its
 // requantization to INT8 are applied before the store, so the INT32 tensor between the two never exists.
-template <int BM, int BN, int BK, int RING, bool OUT_I8, int KMODE, bool TW = false, bool DMA = false, bool GELU = false>
+// LN = true (INT32 result, not stored): integer LayerNorm (Sec. 3.6) over the whole output row follows in the same
+// kernel.  A row spans the tiles_n column tiles of one tile row, which are different workgroups: each adds its part of
+// the row's sum and sum of squares to two words in global memory that also count the contributions (integer atomics:
+// exact in any order), polls them until all have arrived, and then normalizes the values it still holds in registers
+// (sum of squared deviations = sum x^2 - 2 mu sum x + N mu^2, exactly, in 64 bits) and stores INT8.  The wait cannot
+// deadlock: workgroups start in index order and the tiles of a tile row are consecutive, so all earlier tile rows are
+// complete or running and only the newest may be partly started; it is bounded all the same, and a wait that runs
+// out sets a status bit instead of hanging.
+template <int BM, int BN, int BK, int RING, bool OUT_I8, int KMODE, bool TW = false, bool DMA = false, bool GELU = false,
+          bool LN = false>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
 {
     static_assert(!GELU || OUT_I8, "the GELU epilogue writes INT8");
+    static_assert(!LN || (DMA && !OUT_I8 && !GELU), "the LayerNorm epilogue belongs to the whole-tile INT32 kernels");
     constexpr int CPR = BK / 16;                       // 16-byte chunks per tile row
     constexpr int RPP = GEMM_THREADS / CPR;            // tile rows loaded per pass of the workgroup
     constexpr int LA = BM / RPP, LW = BN / RPP;        // chunks per lane per K step
@@ -160,6 +184,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
+    if (g.zero_words > 0) {
+        for (int64_t i = (int64_t)blockIdx.x * GEMM_THREADS + tid; i < g.zero_words; i += (int64_t)gridDim.x * GEMM_THREADS)
+            g.zero_p[i] = 0u;
+    }
 #ifdef IBERT_KERNEL_TIMING
     long long tstamp[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     tstamp[0] = __builtin_readcyclecounter();
@@ -278,14 +306,21 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
 
     // Per-channel constants of this tile's BN columns, one or two columns per lane; used after the main loop.
     constexpr int PPT = (BN + GEMM_THREADS - 1) / GEMM_THREADS;
-    int32_t pb[PPT], pm[PPT], ps[PPT];
+    int32_t pb[PPT], pm[PPT], ps[PPT], pg[PPT], pe[PPT];
 #pragma unroll
     for (int q = 0; q < PPT; ++q) {
         int nn = n0 + q * GEMM_THREADS + tid;
         nn = nn < g.N ? nn : g.N - 1;
-        pb[q] = g.bias ? g.bias[nn] : 0;
-        pm[q] = g.per_channel ? g.mult[nn] : g.dy_m;
-        ps[q] = g.per_channel ? g.shift[nn] : g.dy_s;
+        pb[q] = 0; pm[q] = g.dy_m; ps[q] = g.dy_s; pg[q] = 0; pe[q] = 0;
+        if (g.bias) pb[q] = g.bias[nn];
+        if (g.per_channel) {
+            pm[q] = g.mult[nn];
+            ps[q] = g.shift[nn];
+        }
+        if (LN) {
+            pg[q] = g.ln_gamma[nn];
+            pe[q] = g.ln_beta[nn];
+        }
     }
 
     if constexpr (DMA) {
@@ -473,6 +508,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
     int32_t* stage = reinterpret_cast<int32_t*>(lds);              // [32 * JC][SP]
     int32_t* par = stage + 32 * JC * SP;                           // [3][BN]: bias, mult, shift
     uint32_t* resl = reinterpret_cast<uint32_t*>(par + 3 * BN);    // [BM][BN / 4]: residual tile, 4 channels per dword
+    // LN only, [2][BN]: gamma, beta -- inside the staging area (which that epilogue does not use), behind the
+    // BM x (BN + 16) bytes through which its packed output goes
+    int32_t* lnp = stage + BM * (BN + 16) / 4;
+    static_assert(!LN || BM * (BN + 16) / 4 + 2 * BN <= 32 * JC * SP, "room for the LayerNorm constants");
 
     const int64_t c_off = zo * g.sC_o + zi * g.sC_i;
     const int8_t* R = g.R ? g.R + zo * g.sR_o + zi * g.sR_i : nullptr;
@@ -486,6 +525,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
             par[c] = pb[q];
             par[BN + c] = pm[q];
             par[2 * BN + c] = ps[q];
+            if (LN) {
+                lnp[c] = pg[q];
+                lnp[BN + c] = pe[q];
+            }
             const int32_t ab = pb[q] < 0 ? -pb[q] : pb[q];
             bad |= (ps[q] < 33 || ps[q] > 62 || ab < 0 || ab >= (1 << 30)) ? 1 : 0;
         }
@@ -700,7 +743,151 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
             }
         }
     };
-    if (interior && fast) {
+    if constexpr (LN) {
+        // The launcher admits whole tiles with vector-aligned residual and output rows only.
+        const bool has_res = R != nullptr;
+        int32_t s1[FM];
+        uint64_t s2[FM];
+#pragma unroll
+        for (int j = 0; j < FM; ++j) { s1[j] = 0; s2[j] = 0; }
+        const uint32_t* const r_base = resl + (wm0 + frow) * G4 + (wn0 >> 2) + fch;
+        // 1: requantize in place (the accumulator registers now hold the LayerNorm input, clamped to 16 bits), and
+        //    add up the lane's share of each row
+        auto requant_rows = [&](auto fast_tag) __attribute__((always_inline)) {
+            constexpr bool FAST = decltype(fast_tag)::value;
+#pragma clang loop unroll(full)
+            for (int i = 0; i < FN; ++i) {
+                const int cl = wn0 + 16 * i + 4 * fch;
+                const v4i bb = *reinterpret_cast<const v4i*>(par + cl);
+                const v4i mm = *reinterpret_cast<const v4i*>(par + BN + cl);
+                const v4i ss = *reinterpret_cast<const v4i*>(par + 2 * BN + cl);
+                int64_t cc[4];
+                int32_t sh[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    cc[e] = (int64_t)bb[e] * mm[e] + ((int64_t)1 << ((ss[e] - 1) & 63));
+                    sh[e] = (ss[e] - 32) & 31;
+                }
+#pragma clang loop unroll(full)
+                for (int j = 0; j < FM; ++j) {
+                    const uint32_t pk = has_res ? r_base[j * 16 * G4 + i * 4] : 0u;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int32_t r8 = (int32_t)(int8_t)(pk >> (8 * e));
+                        int32_t v;
+                        if (FAST) {
+                            const int64_t p = (int64_t)acc[i][j][e] * mm[e] + cc[e];
+                            v = (int32_t)(p >> 32) >> sh[e];
+                            if (has_res) v += (int32_t)(((int64_t)r8 * g.res_m + g.res_rnd) >> g.res_s);
+                            v = med3_i32(v, clamp_lo, clamp_hi);
+                        } else {
+                            const int32_t a = acc[i][j][e] + bb[e];
+                            const int shq = ss[e] & 63;
+                            int64_t w = ((int64_t)a * mm[e] + (shq > 0 ? (int64_t)1 << (shq - 1) : 0)) >> shq;
+                            if (has_res) w += ((int64_t)r8 * g.res_m + g.res_rnd) >> g.res_s;
+                            v = clamp_i64_to_i32(w, g.out_clamp);
+                        }
+                        acc[i][j][e] = v;
+                        s1[j] += v;                                // out_clamp = 2^15 - 1: a 24-bit square
+                        s2[j] += (uint32_t)smul24(v, v);
+                    }
+                }
+            }
+        };
+        if (fast) requant_rows(std::true_type{}); else requant_rows(std::false_type{});
+        // 2: the four lanes that share a token row combine, and one of them adds the wavefront's share to the row's two
+        //    totals.  Each total is one 64-bit word that also counts its contributions: sum of (x + 2^21) in bits
+        //    [0, 40) with the count from bit 40 up (a wavefront's share of a sum is below 2^21 in magnitude), sum of x^2
+        //    in bits [0, 48) (below 2^40) with the count from bit 48 up.  Integer additions: exact in any order.
+#pragma unroll
+        for (int j = 0; j < FM; ++j) {
+            s1[j] += __shfl_xor(s1[j], 16, 64);
+            s1[j] += __shfl_xor(s1[j], 32, 64);
+            uint32_t lo = (uint32_t)s2[j], hi = (uint32_t)(s2[j] >> 32);   // 64-bit values travel as two dwords
+            uint64_t t = s2[j];
+            t += ((uint64_t)(uint32_t)__shfl_xor((int32_t)hi, 16, 64) << 32) | (uint32_t)__shfl_xor((int32_t)lo, 16, 64);
+            lo = (uint32_t)t; hi = (uint32_t)(t >> 32);
+            t += ((uint64_t)(uint32_t)__shfl_xor((int32_t)hi, 32, 64) << 32) | (uint32_t)__shfl_xor((int32_t)lo, 32, 64);
+            s2[j] = t;
+            if (fch == 0) {
+                const int64_t row = (int64_t)m0 + wm0 + 16 * j + frow;
+                __hip_atomic_fetch_add(g.ln_sum + row, ((unsigned long long)1 << 40) + (unsigned long long)(s1[j] + (1 << 21)),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_add(g.ln_sq + row, ((unsigned long long)1 << 48) + (unsigned long long)s2[j],
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        // 3: wait until every column tile of this tile row has added its two shares per row: the totals themselves say
+        //    so, and the read that finds them complete is the read that is used.  Everything shared goes through
+        //    agent-scope atomics (performed where all workgroups see them), so no cache is written back or invalidated.
+        const uint32_t need = 2u * (uint32_t)g.tiles_n;
+        unsigned long long tsum[FM], tsq[FM];
+        for (int spins = 0;; ++spins) {
+            bool done = true;
+#pragma unroll
+            for (int j = 0; j < FM; ++j) {
+                const int64_t row = (int64_t)m0 + wm0 + 16 * j + frow;
+                tsum[j] = __hip_atomic_load(g.ln_sum + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                tsq[j] = __hip_atomic_load(g.ln_sq + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+#pragma unroll
+            for (int j = 0; j < FM; ++j) done = done && (uint32_t)(tsum[j] >> 40) == need && (uint32_t)(tsq[j] >> 48) == need;
+            if (__builtin_amdgcn_ballot_w64(!done) == 0) break;
+            if (spins > (1 << 20)) {                               // seconds: never in a healthy run
+                if (lane == 0) __hip_atomic_fetch_or(g.ln_status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(2);
+        }
+        // 4: per-row mean and factor (every lane of a row repeats them)
+        const uint32_t Nu = (uint32_t)g.N;
+        int32_t mu[FM], fr[FM];
+        bool big = false;
+#pragma unroll
+        for (int j = 0; j < FM; ++j) {
+            const int32_t S = (int32_t)(uint32_t)(tsum[j] & (((unsigned long long)1 << 40) - 1)) - (int32_t)(need << 21);
+            const unsigned long long Q = tsq[j] & (((unsigned long long)1 << 48) - 1);
+            mu[j] = ln_row_mean(S, Nu, g.ln_magic);
+            // sum (x - mu)^2 = Q - 2 mu S + N mu^2: exact in 64 bits, never negative
+            const int64_t ssd = (int64_t)Q - 2 * (int64_t)mu[j] * S + (int64_t)Nu * mu[j] * mu[j];
+            fr[j] = ln_row_factor((uint64_t)ssd, Nu, g.ln_magic);
+            big |= fr[j] >= (1 << 23);
+        }
+        const bool f24 = __builtin_amdgcn_ballot_w64(big) == 0;   // else sigma <= 2 somewhere: full 32-bit multiplies
+        // 5: normalize, pack, and go through LDS once so that the stores are whole 16-byte pieces of rows
+        constexpr int SPB = BN + 16;
+        int8_t* const ostage = lds;
+        const int32_t lrnd = 1 << (g.ln_shift - 1);
+#pragma clang loop unroll(full)
+        for (int i = 0; i < FN; ++i) {
+            const int cl = wn0 + 16 * i + 4 * fch;
+            const v4i gm = *reinterpret_cast<const v4i*>(lnp + cl);
+            v4i bt = *reinterpret_cast<const v4i*>(lnp + BN + cl);
+            bt += lrnd;
+#pragma clang loop unroll(full)
+            for (int j = 0; j < FM; ++j) {
+                int32_t o[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int32_t d = acc[i][j][e] - mu[j];
+                    const int32_t nn = (f24 ? smul24(d, fr[j]) : d * fr[j]) >> 14;
+                    o[e] = med3_i32(smad24(nn, gm[e], bt[e]) >> g.ln_shift, -127, 127);
+                }
+                *reinterpret_cast<uint32_t*>(ostage + (wm0 + 16 * j + frow) * SPB + wn0 + 16 * i + 4 * fch) = pack4_perm(o[0], o[1], o[2], o[3]);
+            }
+        }
+        __syncthreads();
+        constexpr int C16 = BN / 16, CH = BM * C16;
+        int8_t* const yt = g.ln_y + (int64_t)m0 * g.ln_ldy + n0;
+#pragma unroll
+        for (int q0 = 0; q0 < CH; q0 += GEMM_THREADS) {
+            const int q = q0 + tid;
+            if (CH % GEMM_THREADS == 0 || q < CH) {
+                const int row = q / C16, c16 = q - row * C16;
+                *reinterpret_cast<v4i*>(yt + (int64_t)row * g.ln_ldy + c16 * 16) = *reinterpret_cast<const v4i*>(ostage + row * SPB + c16 * 16);
+            }
+        }
+    } else if (interior && fast) {
         // (GELU excludes a residual; without a table -- it did not fit, or the parameters are unusual -- the
         // arithmetic form runs, with the choice between its two variants made per value)
         if (GELU && g.gelu_lut_n > 0) finish_direct(std::false_type{}, std::false_type{}, std::true_type{});
@@ -815,7 +1002,7 @@ static long long* g_dbg_buf = nullptr;
 #endif
 static int g_config_override = -1;
 
-template <int BM, int BN, int BK, int RING, bool TW = false, bool DMA = false, bool GELU = false>
+template <int BM, int BN, int BK, int RING, bool TW = false, bool DMA = false, bool GELU = false, bool LN = false>
 static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
 {
     g.tiles_m = (g.M + BM - 1) / BM;
@@ -835,7 +1022,7 @@ static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
     }
 #define IBERT_GEMM_LAUNCH(I8_, KT_)                                                                       \
     do {                                                                                                  \
-        auto kern = gemm_nt_mfma_kernel<BM, BN, BK, RING, I8_, KT_, TW, DMA, GELU && I8_>;                    \
+        auto kern = gemm_nt_mfma_kernel<BM, BN, BK, RING, I8_, KT_, TW, DMA, GELU && I8_, LN && !I8_>;       \
         static size_t attr_bytes = 0;                                                                     \
         if (lds_bytes > attr_bytes) {                                                                     \
             IBERT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                      \
@@ -847,6 +1034,11 @@ static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
     if constexpr (GELU) {
         if (!i8 || g.K % BK != 0) return IBERT_ERR_NOT_IMPLEMENTED;
         IBERT_GEMM_LAUNCH(true, 0);
+    } else if constexpr (LN) {
+        if (i8 || g.K % BK != 0) return IBERT_ERR_NOT_IMPLEMENTED;
+        // tile rows must not straddle the XCD runs: the column tiles of a row start back to back
+        if (g.xcd_chunk % g.tiles_n != 0) g.xcd_chunk = 0;
+        IBERT_GEMM_LAUNCH(false, 0);
     } else if (g.K % BK == 0) {
         if (i8) IBERT_GEMM_LAUNCH(true, 0); else IBERT_GEMM_LAUNCH(false, 0);
     } else if constexpr (!DMA) {
@@ -860,9 +1052,9 @@ static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
     static char label[2][2][96];
     char* l = label[i8 ? 1 : 0][g.K % BK == 0 ? 0 : 1];
     if (!l[0])
-        std::snprintf(l, sizeof label[0][0], "gemm_nt_mfma_kernel<%d, %d, %d, %d, %s, %d, %s, %s, %s>", BM, BN, BK, RING,
+        std::snprintf(l, sizeof label[0][0], "gemm_nt_mfma_kernel<%d, %d, %d, %d, %s, %d, %s, %s, %s, %s>", BM, BN, BK, RING,
                       i8 ? "true" : "false", g.K % BK == 0 ? 0 : 1, TW ? "true" : "false", DMA ? "true" : "false",
-                      GELU ? "true" : "false");
+                      GELU ? "true" : "false", LN ? "true" : "false");
     g_last_kernel = l;
     return IBERT_OK;
 }
@@ -958,9 +1150,13 @@ static int choose_config(const ibert_gemm_desc& d, int64_t nb, bool gelu)
 
 // gelu != nullptr asks for the GELU epilogue (INT8 output, no residual; out_clamp must be gelu->q_max): only the
 // direct-to-LDS tiles carry it, any other problem returns IBERT_ERR_NOT_IMPLEMENTED without launching.
+// ln != nullptr asks for the LayerNorm epilogue (INT32 result at out_clamp = 2^15 - 1, one problem, N <= 1024; C is
+// not written): only the direct-to-LDS 128-row tiles carry it, and only where such a tile is the choice for the
+// problem anyway; otherwise IBERT_ERR_NOT_IMPLEMENTED, nothing launched.
+// zero != nullptr: words the kernel clears while it starts (any MFMA-path launch; else IBERT_ERR_NOT_IMPLEMENTED).
 int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, const int32_t* bias,
                 const int32_t* mult, const int32_t* shift, const int8_t* residual, void* C, hipStream_t stream,
-                const ibert_gelu_params* gelu)
+                const ibert_gelu_params* gelu, const LnFuse* ln, const ZeroReq* zero)
 {
     const int64_t nb = (int64_t)d.batch_outer * d.batch_inner;
     if (nb == 0 || d.M == 0 || d.N == 0) return IBERT_OK;
@@ -994,17 +1190,48 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
         g.gelu_fast = gelu_fast_ok(*gelu) ? 1 : 0;
         gelu_table_range(*gelu, &g.gelu_lut_lo, &g.gelu_lut_n);
     }
-    g.c_vec = aligned(C, i8 ? 4 : 16) && d.ldc % 4 == 0 && d.strideC_outer % 4 == 0 && d.strideC_inner % 4 == 0;
+    g.ln_gamma = g.ln_beta = nullptr; g.ln_y = nullptr; g.ln_ldy = 0; g.ln_sum = nullptr; g.ln_sq = nullptr;
+    g.ln_status = nullptr; g.ln_shift = 1; g.ln_magic = 0;
+    g.zero_p = zero ? zero->p : nullptr;
+    g.zero_words = zero ? zero->words : 0;
+    if (ln) {
+        // (N / 96 <= 10 column tiles: the contribution counts stay far inside their bit fields)
+        if (gelu || i8 || nb != 1 || d.out_clamp != 32767 || d.N > 1024 || d.trans_w) return IBERT_ERR_NOT_IMPLEMENTED;
+        if (!aligned(ln->y, 16) || ln->ldy % 16 != 0 || !aligned(ln->gamma_q, 4) || (residual && !(aligned(residual, 16) && d.ldr % 16 == 0)))
+            return IBERT_ERR_NOT_IMPLEMENTED;
+        g.ln_gamma = ln->gamma_q; g.ln_beta = ln->beta_q; g.ln_y = ln->y; g.ln_ldy = ln->ldy;
+        g.ln_sum = ln->sum; g.ln_sq = ln->sq; g.ln_status = ln->status;
+        g.ln_shift = ln->shift; g.ln_magic = ln_magic_for(d.N);
+    }
+    g.c_vec = ln ? 1 : aligned(C, i8 ? 4 : 16) && d.ldc % 4 == 0 && d.strideC_outer % 4 == 0 && d.strideC_inner % 4 == 0;
     g.c_vec16 = i8 && aligned(C, 16) && d.ldc % 16 == 0 && d.strideC_outer % 16 == 0 && d.strideC_inner % 16 == 0;
     g.r_vec = residual && aligned(residual, 16) && d.ldr % 16 == 0 && d.strideR_outer % 16 == 0 && d.strideR_inner % 16 == 0;
 
     const bool fast = d.trans_w == 0 && d.K > 0 && aligned(A, 16) && aligned(W, 16) && d.lda % 16 == 0 && d.ldw % 16 == 0 &&
                       d.strideA_outer % 16 == 0 && d.strideA_inner % 16 == 0 && d.strideW_outer % 16 == 0 &&
                       d.strideW_inner % 16 == 0;
-    if (gelu && !(fast && d.K % 16 == 0)) return IBERT_ERR_NOT_IMPLEMENTED;
+    if ((gelu || ln) && !(fast && d.K % 16 == 0)) return IBERT_ERR_NOT_IMPLEMENTED;
+    if (zero && !(fast && d.K % 16 == 0)) return IBERT_ERR_NOT_IMPLEMENTED;
     if (fast) {
         if (d.K % 16 != 0) return launch_tail(g, i8, stream);       // bytewise K tail
         const int cfg = choose_config(d, nb, gelu != nullptr);
+        if (ln) {
+            g.ldc = d.N;                                            // (unused: keeps the epilogue's row offsets small)
+            // Only where a 128-row tile is the choice for this problem anyway: measured, the exchange between the column
+            // tiles costs 4-5 us, which beats a LayerNorm kernel of its own when every CU has one tile (Base and Large
+            // at 4096 tokens), and loses both when the tiles are few (a smaller MatMul tile and a 4 us LayerNorm do
+            // better) and when they are many (bigger tiles do better, and waiting tiles hold their CU).
+            const bool w96 = dma_ok(d, 128, 96), w128 = dma_ok(d, 128, 128);
+            const int lcfg = (cfg == 7 || cfg == 9 || cfg == 11 || cfg == 12) ? cfg : -1;
+            switch (lcfg) {
+                case 7: if (w128) return launch_mfma<128, 128, 128, 2, false, true, false, true>(g, i8, stream); break;
+                case 9: if (w96) return launch_mfma<128, 96, 128, 2, false, true, false, true>(g, i8, stream); break;
+                case 11: if (w96) return launch_mfma<128, 96, 128, 3, false, true, false, true>(g, i8, stream); break;
+                case 12: if (w128) return launch_mfma<128, 128, 128, 3, false, true, false, true>(g, i8, stream); break;
+                default: break;
+            }
+            return IBERT_ERR_NOT_IMPLEMENTED;
+        }
         if (gelu) {
             switch (cfg) {
                 case 6: if (dma_ok(d, 256, 192)) return launch_mfma<256, 192, 128, 2, false, true, true>(g, i8, stream); break;
@@ -1037,6 +1264,7 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
                          aligned(W, 4) && d.lda % 16 == 0 && d.ldw % 4 == 0 && d.strideA_outer % 16 == 0 &&
                          d.strideA_inner % 16 == 0 && d.strideW_outer % 4 == 0 && d.strideW_inner % 4 == 0;
     if (fast_tw) {
+        if (zero) return IBERT_ERR_NOT_IMPLEMENTED;
         if (d.N <= 64) return launch_mfma<128, 64, 64, 2, true>(g, i8, stream);
         return launch_mfma<128, 128, 64, 2, true>(g, i8, stream);
     }

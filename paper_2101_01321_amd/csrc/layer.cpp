@@ -44,8 +44,24 @@ static double gemm_bytes(double M, double N, double K, double batch, double out_
 }
 
 // Fusions the layer applies (bit 0: GELU inside the FFN up-projection; bit 1: scores, Softmax and context in one
-// kernel).  Results do not depend on it.
-static int32_t g_fusion = 3;
+// kernel; bit 2: LayerNorm inside the output projection and inside the FFN down-projection).  Results do not depend
+// on it.
+static int32_t g_fusion = 7;
+
+// Row statistics of the LayerNorm epilogue for `rows` tokens: two 64-bit words a row (sum, sum of squares, each with
+// its count of contributions), the sums of squares first; `words` 32-bit words in all.
+struct LnStats {
+    size_t words;
+    size_t sq_off, sum_off;               // in bytes from the start of a set
+};
+static LnStats ln_stats_shape(size_t rows)
+{
+    LnStats s;
+    s.sq_off = 0;
+    s.sum_off = 8 * rows;
+    s.words = 4 * rows;
+    return s;
+}
 
 static int layout(int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn,
                   ibert_layer_workspace_layout* o)
@@ -62,6 +78,8 @@ static int layout(int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int
     o->f1 = p;     p += align_up(T * F * 4);
     o->g = p;      p += align_up(T * F);
     o->r2 = p;     p += align_up(T * H * 4);
+    // two sets of LayerNorm row statistics (one per LayerNorm of the layer) and a status word behind them
+    o->ln_stats = p; p += align_up(2 * ln_stats_shape(T).words * 4 + 4);
     o->total = p;
     return IBERT_OK;
 }
@@ -148,6 +166,21 @@ static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, c
     int8_t* g = reinterpret_cast<int8_t*>(ws + lo.g);
     int32_t* r2 = reinterpret_cast<int32_t*>(ws + lo.r2);
 
+    // LayerNorm in the epilogue of steps 5 and 9: each needs its set of row statistics zero when it starts; the
+    // set of step 5 is cleared by step 1's kernel and the set of step 9 by step 5's, so nothing carries over
+    // between calls.  Whether a step fuses is only known once its launch accepts; a cleared set nobody uses is harmless.
+    const LnStats st = ln_stats_shape((size_t)T);
+    char* const set_a = ws + lo.ln_stats;
+    char* const set_b = set_a + st.words * 4;
+    uint32_t* const ln_status = reinterpret_cast<uint32_t*>(set_b + st.words * 4);
+    const bool try_ln = (g_fusion & 4) != 0 && H <= 1024;
+    const ZeroReq zero_a{reinterpret_cast<uint32_t*>(set_a), (int64_t)st.words};
+    const ZeroReq zero_b{reinterpret_cast<uint32_t*>(set_b), (int64_t)st.words};
+    auto ln_fuse = [&](char* set, const int32_t* gq, const int32_t* bq, int32_t shift, int8_t* out) {
+        return LnFuse{gq, bq, shift, out, H, reinterpret_cast<unsigned long long*>(set + st.sum_off),
+                      reinterpret_cast<unsigned long long*>(set + st.sq_off), ln_status};
+    };
+
     ibert_gemm_desc d;
     int rc;
 #define RUN_GEMM(A_, W_, b_, m_, s_, R_, C_)                                             \
@@ -157,13 +190,57 @@ static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, c
         rc = launch_gemm(d, A_, W_, b_, m_, s_, R_, C_, stream);                         \
         if (rc) return rc;                                                               \
     } while (0)
+    // A MatMul followed by LayerNorm: one kernel where the launch accepts it (then the INT32 tensor R32_ is never
+    // written), else the two steps.  ZERO_: statistics this launch clears for the next such pair (or nullptr).
+#define RUN_GEMM_LN(STEP_, A_, W_, b_, m_, s_, R_, R32_, SET_, GQ_, BQ_, SH_, OUT_, ZERO_, OPS_, K_)            \
+    do {                                                                                                     \
+        rc = check_gemm(d, A_, W_, m_, s_, R_, R32_);                                                        \
+        if (rc) return rc;                                                                                   \
+        bool fused_ln = false;                                                                               \
+        if (try_ln && ln_ready) {                                                                            \
+            const LnFuse lf = ln_fuse(SET_, GQ_, BQ_, SH_, OUT_);                                            \
+            prof_before(stream);                                                                             \
+            rc = launch_gemm(d, A_, W_, b_, m_, s_, R_, R32_, stream, nullptr, &lf, ZERO_);                  \
+            if (rc == IBERT_OK) {                                                                            \
+                fused_ln = true;                                                                             \
+                prof_after(stream, STEP_, OPS_, gemm_bytes(T, H, K_, 1, 1, true, true));                     \
+            } else if (rc != IBERT_ERR_NOT_IMPLEMENTED) {                                                    \
+                return rc;                                                                                   \
+            }                                                                                                \
+        }                                                                                                    \
+        if (!fused_ln) {                                                                                     \
+            prof_before(stream);                                                                             \
+            rc = launch_gemm(d, A_, W_, b_, m_, s_, R_, R32_, stream, nullptr, nullptr, ZERO_);              \
+            if (rc == IBERT_ERR_NOT_IMPLEMENTED && (ZERO_) != nullptr) {                                     \
+                zero_ok = false;                                                                             \
+                rc = launch_gemm(d, A_, W_, b_, m_, s_, R_, R32_, stream);                                   \
+            }                                                                                                \
+            if (rc) return rc;                                                                               \
+            prof_after(stream, STEP_, OPS_, gemm_bytes(T, H, K_, 1, 4, true, true));                         \
+            prof_before(stream);                                                                             \
+            rc = launch_layernorm(R32_, OUT_, T, (int32_t)H, H, H, GQ_, BQ_, SH_, stream);                   \
+            if (rc) return rc;                                                                               \
+            prof_after(stream, (STEP_) + 1, 0.0, 5.0 * T * H);                                               \
+        }                                                                                                    \
+    } while (0)
 
     // 1: QKV projection, one GEMM with N = 3H
     std::memset(&d, 0, sizeof d);
     d.M = (int32_t)T; d.N = (int32_t)(3 * H); d.K = (int32_t)H; d.batch_outer = d.batch_inner = 1;
     d.lda = H; d.ldw = H; d.ldc = 3 * H; d.per_channel = 1; d.out_dtype = IBERT_I8; d.out_clamp = 127;
     prof_before(stream);
-    RUN_GEMM(x, w.w_qkv, w.b_qkv, w.m_qkv, w.s_qkv, nullptr, qkv);
+    bool ln_ready = false;          // the statistics of the next LayerNorm epilogue have been cleared
+    bool zero_ok = true;
+    rc = check_gemm(d, x, w.w_qkv, w.m_qkv, w.s_qkv, nullptr, qkv);
+    if (rc) return rc;
+    rc = try_ln ? launch_gemm(d, x, w.w_qkv, w.b_qkv, w.m_qkv, w.s_qkv, nullptr, qkv, stream, nullptr, nullptr, &zero_a)
+                : IBERT_ERR_NOT_IMPLEMENTED;
+    if (rc == IBERT_OK) {
+        ln_ready = true;
+    } else if (rc == IBERT_ERR_NOT_IMPLEMENTED) {
+        rc = launch_gemm(d, x, w.w_qkv, w.b_qkv, w.m_qkv, w.s_qkv, nullptr, qkv, stream);
+    }
+    if (rc) return rc;
     prof_after(stream, 1, 2.0 * T * 3 * H * H, gemm_bytes(T, 3 * H, H, 1, 1, false, true));
 
     // 2-4: attention scores, Softmax, context
@@ -176,15 +253,10 @@ static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, c
     d.M = (int32_t)T; d.N = (int32_t)H; d.K = (int32_t)H; d.batch_outer = d.batch_inner = 1;
     d.lda = H; d.ldw = H; d.ldc = H; d.ldr = H; d.per_channel = 1; d.out_dtype = IBERT_I32; d.out_clamp = 32767;
     d.residual_dy = q.res1_dy;
-    prof_before(stream);
-    RUN_GEMM(ctx, w.w_o, w.b_o, w.m_o, w.s_o, x, r1);
-    prof_after(stream, 5, 2.0 * T * H * H, gemm_bytes(T, H, H, 1, 4, true, true));
-
-    // 6: LayerNorm
-    prof_before(stream);
-    rc = launch_layernorm(r1, h1, T, (int32_t)H, H, H, w.ln1_gamma_q, w.ln1_beta_q, q.ln1_shift, stream);
-    if (rc) return rc;
-    prof_after(stream, 6, 0.0, 5.0 * T * H);
+    // (+ 6: LayerNorm, in the same kernel where that is possible; the launch also clears the statistics of step 9)
+    RUN_GEMM_LN(5, ctx, w.w_o, w.b_o, w.m_o, w.s_o, x, r1, set_a, w.ln1_gamma_q, w.ln1_beta_q, q.ln1_shift, h1,
+                (try_ln ? &zero_b : nullptr), 2.0 * T * H * H, H);
+    ln_ready = try_ln && zero_ok;
 
     // 7: FFN up-projection, INT32 at the GELU input scale
     std::memset(&d, 0, sizeof d);
@@ -223,17 +295,12 @@ static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, c
     d.M = (int32_t)T; d.N = (int32_t)H; d.K = (int32_t)F; d.batch_outer = d.batch_inner = 1;
     d.lda = F; d.ldw = F; d.ldc = H; d.ldr = H; d.per_channel = 1; d.out_dtype = IBERT_I32; d.out_clamp = 32767;
     d.residual_dy = q.res2_dy;
-    prof_before(stream);
-    RUN_GEMM(g, w.w_2, w.b_2, w.m_2, w.s_2, h1, r2);
-    prof_after(stream, 9, 2.0 * T * H * F, gemm_bytes(T, H, F, 1, 4, true, true));
-
-    // 10: LayerNorm
-    prof_before(stream);
-    rc = launch_layernorm(r2, y, T, (int32_t)H, H, H, w.ln2_gamma_q, w.ln2_beta_q, q.ln2_shift, stream);
-    if (rc) return rc;
-    prof_after(stream, 10, 0.0, 5.0 * T * H);
+    // (+ 10: LayerNorm)
+    RUN_GEMM_LN(9, g, w.w_2, w.b_2, w.m_2, w.s_2, h1, r2, set_b, w.ln2_gamma_q, w.ln2_beta_q, q.ln2_shift, y,
+                (const ZeroReq*)nullptr, 2.0 * T * H * F, F);
     return IBERT_OK;
 #undef RUN_GEMM
+#undef RUN_GEMM_LN
 }
 
 static int check_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, int32_t seq, int32_t hidden)
@@ -262,7 +329,7 @@ extern "C" {
 int ibert_set_fusion(int32_t flags)
 {
     const int32_t old = ibert::g_fusion;
-    if (flags >= 0) ibert::g_fusion = flags & 3;
+    if (flags >= 0) ibert::g_fusion = flags & 7;
     return old;
 }
 
@@ -304,6 +371,48 @@ int ibert_attention_masked_i(const int8_t* qkv, int8_t* ctx, int32_t batch, int3
     }
     return run_attention(qkv, scores, probs, ctx, batch, seq, hidden, heads, *scores_dy, *softmax, *ctx_dy, key_lens,
                          (g_fusion & 2) != 0, (hipStream_t)stream);
+}
+
+size_t ibert_gemm_layernorm_scratch_bytes(int32_t M, int32_t N)
+{
+    if (M < 0 || N < 0) return 0;
+    return ibert::align_up((size_t)M * N * 4) + ibert::align_up(ibert::ln_stats_shape((size_t)M).words * 4 + 4);
+}
+
+int ibert_gemm_i8_layernorm(const ibert_gemm_desc* desc, const int8_t* A, const int8_t* W, const int32_t* bias,
+                            const int32_t* mult, const int32_t* shift, const int8_t* residual, const int32_t* gamma_q,
+                            const int32_t* beta_q, int32_t ln_shift, int8_t* y, int64_t ldy, void* scratch,
+                            size_t scratch_bytes, void* stream_)
+{
+    using namespace ibert;
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!desc) return IBERT_ERR_NULL;
+    ibert_gemm_desc d = *desc;
+    if (d.batch_outer != 1 || d.batch_inner != 1 || d.out_dtype != IBERT_I32 || d.out_clamp != 32767) return IBERT_ERR_SHAPE;
+    if (ldy < d.N) return IBERT_ERR_SHAPE;
+    int rc = check_layernorm(d.N, ln_shift);
+    if (rc) return rc;
+    if (!scratch || scratch_bytes < ibert_gemm_layernorm_scratch_bytes(d.M, d.N) || ((uintptr_t)scratch & 255)) return IBERT_ERR_WORKSPACE;
+    int32_t* r32 = static_cast<int32_t*>(scratch);
+    d.ldc = d.N;
+    rc = check_gemm(d, A, W, mult, shift, residual, r32);
+    if (rc) return rc;
+    if (d.M == 0) return IBERT_OK;
+    if (!gamma_q || !beta_q || !y) return IBERT_ERR_NULL;
+    const LnStats st = ln_stats_shape((size_t)d.M);
+    char* set = static_cast<char*>(scratch) + align_up((size_t)d.M * d.N * 4);
+    uint32_t* status = reinterpret_cast<uint32_t*>(set + st.words * 4);
+    if (g_fusion & 4) {
+        const LnFuse lf{gamma_q, beta_q, ln_shift, y, ldy, reinterpret_cast<unsigned long long*>(set + st.sum_off),
+                        reinterpret_cast<unsigned long long*>(set + st.sq_off), status};
+        rc = launch_zero_words(reinterpret_cast<uint32_t*>(set), (int64_t)st.words + 1, stream);   // statistics and status
+        if (rc) return rc;
+        rc = launch_gemm(d, A, W, bias, mult, shift, residual, r32, stream, nullptr, &lf, nullptr);
+        if (rc != IBERT_ERR_NOT_IMPLEMENTED) return rc;
+    }
+    rc = launch_gemm(d, A, W, bias, mult, shift, residual, r32, stream);
+    if (rc) return rc;
+    return launch_layernorm(r32, y, d.M, d.N, d.N, ldy, gamma_q, beta_q, ln_shift, stream);
 }
 
 int ibert_profile_begin(int32_t capacity)

@@ -10,6 +10,7 @@
 // an INT32 buffer but made on the fly from one row of the INT8 token table and one of the INT8 position table, each
 // rescaled by a dyadic number to the common INT32 scale of the sum, and then normalized as above.
 #include "common.h"
+#include "layernorm_math.h"
 
 namespace ibert {
 
@@ -33,29 +34,6 @@ struct LayerNormArgs {
     uint32_t magic_c;    // floor(2^32 / C) + 1 (0 for C == 1): reciprocal multiply for the divisions by C
     EmbedArgs emb;       // only read by the embedding instantiations
 };
-
-// floor(u / C) for u < 2^31: est = mulhi(u, magic) is the quotient or one more (the excess is below
-// u / 2^32 < 1); one fix-up step from the sign of the remainder.
-__device__ __forceinline__ uint32_t udiv_c(uint32_t u, uint32_t C, uint32_t magic)
-{
-    if (magic == 0) return u;
-    const uint32_t q = __umulhi(u, magic);
-    const int32_t r = (int32_t)(u - q * C);
-    return r < 0 ? q - 1 : q;
-}
-
-// floor(sqrt(n)), the value the Newton iteration of Alg. 4 ends on (started at or above the root, its integer
-// iterates decrease to exactly the floor of the root).  Here: a single-precision estimate -- n rounded to 24 bits
-// and a correctly rounded root are together less than 0.01 away from the true root, so the truncated estimate is
-// off by at most one -- and one exact correction step in integers.
-__device__ __forceinline__ uint32_t isqrt_floor(uint32_t n)
-{
-    uint32_t x = (uint32_t)__fsqrt_rn((float)n);
-    x = x > 65535u ? 65535u : x;                       // keeps the squares below inside 32 bits
-    if (x * x > n) return x - 1;
-    if (x < 65535u && (x + 1) * (x + 1) <= n) return x + 1;
-    return x;
-}
 
 template <int LPR>
 __device__ __forceinline__ int32_t group_sum_i32(int32_t v)
@@ -180,7 +158,7 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
 
     // mu = floor((sum + floor(C/2)) / C), computed on the non-negative number sum + C/2 + 32768 C
     const uint32_t Cu = (uint32_t)C;
-    const int32_t mu = (int32_t)udiv_c((uint32_t)(sum + (C >> 1) + (C << 15)), Cu, a.magic_c) - 32768;
+    const int32_t mu = ln_row_mean(sum, Cu, a.magic_c);
 
     // ss = sum d^2: |d| < 2^17, so d*d is a 24-bit multiply; each square is below 2^32, the total below 2^42
     uint64_t ss = 0;
@@ -197,15 +175,7 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
     }
     ss = group_sum_u64<LPR>(ss);
 
-    // var = floor(ss / C) < 2^32, with two 32-bit divisions: ss = (t << 11) + low, t < 2^31.
-    const uint32_t t = (uint32_t)(ss >> 11);
-    const uint32_t qa = udiv_c(t, Cu, a.magic_c);
-    const uint32_t rem = (uint32_t)(ss - (((uint64_t)qa * Cu) << 11));   // < C * 2^11 + 2^11
-    const uint32_t var = (qa << 11) + udiv_c(rem, Cu, a.magic_c);
-
-    uint32_t sigma = isqrt_floor(var);
-    sigma = sigma < 1u ? 1u : sigma;
-    const int32_t f = (int32_t)((1u << 24) / sigma);
+    const int32_t f = ln_row_factor(ss, Cu, a.magic_c);
     if (!live) return;
     // d*f: |d| < 2^17 always; f < 2^23 unless sigma <= 2, where the full 32-bit multiply is used instead
     const bool f24 = __builtin_amdgcn_ballot_w64(f >= (1 << 23)) == 0;
@@ -230,6 +200,21 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
                 if (col + e < C) yr[col + e] = (int8_t)o[e];
         }
     }
+}
+
+__global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* p, int64_t words)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < words; i += (int64_t)gridDim.x * 256) p[i] = 0u;
+}
+
+// Clears `words` 32-bit words with a kernel (a memset node may not be recorded into a captured graph).
+int launch_zero_words(uint32_t* p, int64_t words, hipStream_t stream)
+{
+    if (words <= 0) return IBERT_OK;
+    const int64_t blocks = (words + 1023) / 1024;
+    hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)(blocks > 1024 ? 1024 : blocks)), dim3(256), 0, stream, p, words);
+    IBERT_LAUNCH_CHECK("zero_words_kernel");
+    return IBERT_OK;
 }
 
 int check_layernorm(int32_t C, int32_t shift)
@@ -278,14 +263,12 @@ static int dispatch_rows(const LayerNormArgs& a, bool al, hipStream_t stream)
     return IBERT_OK;
 }
 
-static uint32_t magic_for(int32_t C) { return C == 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) / (uint32_t)C) + 1); }
-
 int launch_layernorm(const int32_t* x, int8_t* y, int64_t rows, int32_t C, int64_t ldx, int64_t ldy,
                      const int32_t* gamma_q, const int32_t* beta_q, int32_t shift, hipStream_t stream)
 {
     if (rows == 0) return IBERT_OK;
     if (rows > 0x7fffffffLL) return IBERT_ERR_SHAPE;
-    LayerNormArgs a{x, y, rows, C, ldx, ldy, gamma_q, beta_q, shift, magic_for(C), EmbedArgs{}};
+    LayerNormArgs a{x, y, rows, C, ldx, ldy, gamma_q, beta_q, shift, ln_magic_for(C), EmbedArgs{}};
     const bool al = aligned(x, 16) && ldx % 4 == 0 && aligned(y, 4) && ldy % 4 == 0 && C % 4 == 0 &&
                     aligned(gamma_q, 16) && aligned(beta_q, 16);
     return dispatch_rows(a, al, stream);
@@ -297,7 +280,7 @@ int launch_embedding(const int32_t* ids, const int8_t* tok, const int8_t* pos, i
 {
     if (tokens == 0) return IBERT_OK;
     if (tokens > 0x7fffffffLL) return IBERT_ERR_SHAPE;
-    LayerNormArgs a{nullptr, y, tokens, C, 0, ldy, gamma_q, beta_q, shift, magic_for(C),
+    LayerNormArgs a{nullptr, y, tokens, C, 0, ldy, gamma_q, beta_q, shift, ln_magic_for(C),
                     EmbedArgs{ids, tok, pos, seq, vocab, tok_dy.m, tok_dy.s, pos_dy.m, pos_dy.s}};
     const bool al = aligned(tok, 4) && aligned(pos, 4) && aligned(y, 4) && ldy % 4 == 0 && C % 4 == 0 &&
                     aligned(gamma_q, 16) && aligned(beta_q, 16);

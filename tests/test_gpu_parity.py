@@ -4,6 +4,8 @@ Bar: every integer output equal.  Dequantised outputs vs their float counterpart
 oracle pins (the GPU equals the oracle exactly, so the same tolerances hold); one end-to-end float check
 is repeated here on GPU outputs for the record.
 """
+import math
+
 import numpy as np
 import pytest
 
@@ -461,7 +463,7 @@ def _layer_case(G, cfg, n_layers=1, fusion=0):
     try:
         return _layer_case_body(G, cfg, n_layers, fusion)
     finally:
-        B.ibert_set_fusion(3)
+        B.ibert_set_fusion(7)
 
 
 def _layer_case_body(G, cfg, n_layers, fusion):
@@ -474,31 +476,154 @@ def _layer_case_body(G, cfg, n_layers, fusion):
         raw = synth.layer_raw(cfg, l)
         w, q = P.layer_params(raw, model.scales[l], cfg.hidden, cfg.heads)
         want, inter = oracle.encoder_layer(w, q, cur, cfg.batch, cfg.seq, cfg.hidden, cfg.heads, cfg.ffn, dump=True)
-        G.say("layer %s l=%d" % (cfg.name, l))
+        G.say("layer %s l=%d fusion=%d" % (cfg.name, l, fusion))
+        model.mark_unwritten()
         ty = model.layer_forward(l, tx)
         torch.cuda.synchronize()
         got_inter = model.intermediates()
         for k in ("qkv", "scores", "probs", "ctx", "r1", "h1", "f1", "g", "r2"):
             if k == "f1" and (fusion & 1):
                 continue                                     # not materialised when GELU runs in the MatMul epilogue
+            if k in ("r1", "r2") and (fusion & 4) and not model.was_written(k):
+                continue                                     # nor these when LayerNorm runs in the MatMul epilogue
+            if k in ("r1", "r2"):
+                assert model.was_written(k)
             if k in ("scores", "probs") and (fusion & 2) and cfg.seq in (128, 256, 384, 512) and cfg.hidden == 64 * cfg.heads:
                 continue                                     # nor these when attention is one kernel
             _eq(got_inter[k], inter[k], "%s layer %d %s" % (cfg.name, l, k))
         _eq(ty.cpu().numpy(), want, "%s layer %d output" % (cfg.name, l))
         cur, tx = want, ty
+    assert model.ln_status() == 0
     return model, x_q, cur
 
 
 def test_layer_tiny_every_intermediate(G):
     _layer_case(G, synth.CONFIGS["tiny"])
     _layer_case(G, synth.CONFIGS["tiny"], fusion=3)
+    _layer_case(G, synth.CONFIGS["tiny"], fusion=7)
 
 
 def test_layer_whole_tile_shape_fused_and_unfused(G):
-    # hidden/ffn/tokens that fit the whole-tile MatMul configurations, so that fusion=1 really runs the fused kernel
+    # hidden/ffn/tokens that fit the whole-tile MatMul configurations, so that every fusion really runs its fused kernel
     cfg = synth.EncoderConfig("tiles", 256, 4, 1024, 128, 16, 1)
-    for fusion in (0, 1, 2, 3):
+    for fusion in (0, 1, 2, 3, 4, 5, 7):
         _layer_case(G, cfg, fusion=fusion)
+    # the LayerNorm fusion is the library's own choice at about one 128-row tile per compute unit; force its tile
+    # configurations on small layers (128-wide column tiles at hidden 256, 96-wide at hidden 384; two layers)
+    for tile_cfg, cfg in ((7, cfg), (9, synth.EncoderConfig("tiles96", 384, 6, 1536, 128, 4, 2)),
+                          (11, synth.EncoderConfig("tiles96", 384, 6, 1536, 128, 4, 2))):
+        B_ = __import__("paper_2101_01321_amd.binding", fromlist=["lib"])
+        B_.lib().ibert_gemm_config_override(tile_cfg)
+        try:
+            for fusion in (4, 7):
+                model, _, _ = _layer_case(G, cfg, n_layers=cfg.layers, fusion=fusion)
+                assert not model.was_written("r1") and not model.was_written("r2")
+        finally:
+            B_.lib().ibert_gemm_config_override(-1)
+
+
+@pytest.mark.parametrize("M,N,K,cfg", [
+    (4096, 768, 768, -1), (4096, 768, 3072, -1), (4096, 1024, 1024, -1),       # the library's own choice: one kernel
+    (128, 96, 128, 9), (256, 768, 768, 9), (512, 768, 3072, 11), (384, 1024, 1024, 7), (256, 128, 256, 7),
+    (1024, 384, 2048, 11), (256, 1024, 4096, 12), (256, 96, 128, 11),           # forced tile configurations
+    (100, 96, 128, None), (128, 100, 128, None), (128, 96, 100, None), (130, 250, 64, None), (5, 3, 16, None),
+    (256, 768, 768, None)])                                                     # two kernels
+def test_gemm_layernorm_equals_matmul_then_layernorm(G, M, N, K, cfg):
+    # steps 5+6 / 9+10 in one call: shapes the one-kernel form takes (one to eight column tiles per row, several tile
+    # rows, two and three LDS stages) and shapes that fall back to two kernels
+    from paper_2101_01321_amd import binding as B
+    fused = cfg is not None
+    if fused and cfg >= 0:
+        assert B.lib().ibert_gemm_config_override(cfg) > cfg
+    try:
+        _gemm_layernorm_case(G, M, N, K, fused)
+    finally:
+        B.lib().ibert_gemm_config_override(-1)
+
+
+def _gemm_layernorm_case(G, M, N, K, fused):
+    from paper_2101_01321_amd import binding as B
+    A, W, sw, b = synth.gemm_operands(M, N, K, layer=M + N + K)
+    mult, shift = B.ibert_channel_dyadics_from_scales(0.03, sw, 2.5e-4 * math.sqrt(K))   # rows spread over the 16-bit range
+    R = np.random.default_rng(K).integers(-127, 128, size=(M, N), dtype=np.int8)
+    gamma = np.random.default_rng(N).normal(1.0, 0.1, size=N)
+    beta = np.random.default_rng(N + 1).normal(0.0, 0.1, size=N)
+    gq, bq, s = B.ibert_layernorm_params_from_float(gamma, beta, 5.0 / 127)
+    res_dy = (1717986918, 23)
+    kw = dict(M=M, N=N, K=K, batch_outer=1, batch_inner=1, lda=K, ldw=K, ldc=N, ldr=N, per_channel=1, out_dtype=I32,
+              out_clamp=32767, residual_dy=res_dy)
+    spec = GemmSpec(M, N, K, per_channel=1, dy=(1, 0), out_dtype=I32, out_clamp=32767, res_dy=res_dy)
+    r = oracle.gemm_requant(spec, A, W, b, mult, shift, R).reshape(M, N)
+    top, clamped = int(np.abs(r).max()), float((np.abs(r) == 32767).mean())
+    assert top > 2000 and clamped < 0.2, (top, clamped)                           # a real spread, few clamped values
+    want = oracle.layernorm(r, gq, bq, s)
+    for with_res in (True, False):
+        if not with_res:
+            r0 = oracle.gemm_requant(spec, A, W, b, mult, shift, None).reshape(M, N)
+            want = oracle.layernorm(r0, gq, bq, s)
+        G.say("gemm+layernorm M=%d N=%d K=%d residual=%s" % (M, N, K, with_res))
+        got, status, r_head = G.gemm_layernorm(kw, A, W, b, mult, shift, R if with_res else None, gq, bq, s)
+        assert status == 0 or not fused
+        _eq(got, want, "gemm+layernorm")
+        # the INT32 tensor is only written on the two-kernel route
+        assert bool(np.all(r_head == 0x5A5A5A5A)) == fused
+    if fused:
+        G.say("gemm+layernorm fusion off")
+        old = B.ibert_set_fusion(3)
+        try:
+            got, _, r_head = G.gemm_layernorm(kw, A, W, b, mult, shift, None, gq, bq, s)
+        finally:
+            B.ibert_set_fusion(old)
+        _eq(got, want, "gemm+layernorm, two kernels")
+        assert not np.all(r_head == 0x5A5A5A5A)
+        G.say("gemm+layernorm padded output rows")
+        got, status, _ = G.gemm_layernorm(kw, A, W, b, mult, shift, None, gq, bq, s, ldy=N + 16)
+        assert status == 0
+        _eq(got, want, "gemm+layernorm ldy")
+
+
+def test_gemm_layernorm_degenerate_rows_and_general_requantization(G):
+    # constant rows (sigma clamps to 1, the 32-bit multiply form), saturated rows, and multipliers / shifts outside the
+    # fast requantization form (shift below 33), all inside the one-kernel shape
+    from paper_2101_01321_amd import binding as B
+    M, N, K = 256, 192, 256
+    B.lib().ibert_gemm_config_override(9)
+    try:
+        _gemm_layernorm_degenerate(G, M, N, K)
+    finally:
+        B.lib().ibert_gemm_config_override(-1)
+
+
+def _gemm_layernorm_degenerate(G, M, N, K):
+    from paper_2101_01321_amd import binding as B
+    rng = np.random.default_rng(5)
+    A = rng.integers(-127, 128, size=(M, K), dtype=np.int8)
+    W = rng.integers(-127, 128, size=(N, K), dtype=np.int8)
+    A[0:3] = 0                                                # accumulator 0: the row is bias and residual only
+    b = rng.integers(-2 ** 15, 2 ** 15, size=N).astype(np.int32)
+    gamma, beta = rng.normal(1.0, 0.1, size=N), rng.normal(0.0, 0.1, size=N)
+    gq, bq, s = B.ibert_layernorm_params_from_float(gamma, beta, 5.0 / 127)
+    R = rng.integers(-127, 128, size=(M, N), dtype=np.int8)
+    R[0] = 5
+    R[1] = 0
+    for mult_v, shift_v, bias_on in ((1518500250, 36, True), (1518500250, 30, True), (3, 1, False), (1 << 30, 62, True),
+                                     (1518500250, 45, False)):
+        mult = np.full(N, mult_v, np.int32)
+        shift = np.full(N, shift_v, np.int32)
+        shift[::7] = max(0, shift_v - 3)                      # mixed shifts inside a tile
+        bias = b if bias_on else np.zeros(N, np.int32)
+        if not bias_on:
+            bias[:] = 0
+        res_dy = (1717986918, 23)
+        kw = dict(M=M, N=N, K=K, batch_outer=1, batch_inner=1, lda=K, ldw=K, ldc=N, ldr=N, per_channel=1, out_dtype=I32,
+                  out_clamp=32767, residual_dy=res_dy)
+        spec = GemmSpec(M, N, K, per_channel=1, dy=(1, 0), out_dtype=I32, out_clamp=32767, res_dy=res_dy)
+        r = oracle.gemm_requant(spec, A, W, bias, mult, shift, R).reshape(M, N)
+        want = oracle.layernorm(r, gq, bq, s)
+        G.say("gemm+layernorm degenerate m=%d s=%d" % (mult_v, shift_v))
+        got, status, r_head = G.gemm_layernorm(kw, A, W, bias, mult, shift, R, gq, bq, s)
+        assert status == 0 and np.all(r_head == 0x5A5A5A5A)                      # one kernel: the INT32 tensor was never written
+        _eq(got, want, "gemm+layernorm m=%d s=%d" % (mult_v, shift_v))
 
 
 def test_layer_ragged_every_intermediate(G):
@@ -623,7 +748,7 @@ def test_layer_masked_every_row(G, cfg, lens):
     x_q, S_x, _ = synth.input_activations(cfg)
     lens = np.array(lens, np.int32)
     tl = G.to_dev(lens)
-    for fusion in (3, 0):
+    for fusion in (7, 0):
         B.ibert_set_fusion(fusion)
         try:
             model = G.DeviceModel(cfg, S_x)
@@ -641,7 +766,7 @@ def test_layer_masked_every_row(G, cfg, lens):
             torch.cuda.synchronize()
             _eq(y.cpu().numpy(), cur, "%s encoder" % cfg.name)
         finally:
-            B.ibert_set_fusion(3)
+            B.ibert_set_fusion(7)
 
 
 def test_encoder_masked_full_size_sampled_sequences(G):
@@ -719,10 +844,16 @@ def test_dequantised_output_tracks_float_layer(G):
     import fpref
     cfg = synth.CONFIGS["tiny"]
     x_q, S_x, _ = synth.input_activations(cfg)
+    from paper_2101_01321_amd import binding as B
     model = G.DeviceModel(cfg, S_x)
-    y = model.layer_forward(0, G.to_dev(x_q))
-    torch.cuda.synchronize()
+    old = B.ibert_set_fusion(0)                               # every intermediate is materialised
+    try:
+        y = model.layer_forward(0, G.to_dev(x_q))
+        torch.cuda.synchronize()
+    finally:
+        B.ibert_set_fusion(old)
     d, sc, raw = model.intermediates(), model.scales[0], synth.layer_raw(cfg, 0)
+    assert np.abs(d["scores"]).max() > 0 and d["probs"].max() > 0 and np.abs(d["f1"]).max() > 0 and np.abs(d["r2"]).max() > 0
     assert np.max(np.abs(d["probs"] / 128.0 - fpref.softmax(d["scores"] * sc["S_s"]))) <= 0.02
     want = np.clip(fpref.gelu(d["f1"] * sc["S_g_in"]) / sc["S_g_out"], -127, 127)
     assert np.max(np.abs(d["g"] - want)) <= 0.6

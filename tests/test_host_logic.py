@@ -45,7 +45,7 @@ def test_struct_sizes_match_the_header_layout():
     assert C.sizeof(B.GeluParams) == 24
     assert C.sizeof(B.LayerWeights) == 20 * 8
     assert C.sizeof(B.LayerQuant) == 8 + 20 + 8 + 8 + 4 + 24 + 8 + 4
-    assert C.sizeof(B.WorkspaceLayout) == 10 * 8
+    assert C.sizeof(B.WorkspaceLayout) == 11 * 8
 
 
 def test_dyadic_helper_agrees_with_the_oracle_derivation():
@@ -113,7 +113,9 @@ def test_workspace_layout_is_aligned_and_disjoint():
     lo = B.ibert_encoder_layer_workspace_layout(32, 128, 768, 12, 3072)
     T, H, F, BH, L = 4096, 768, 3072, 384, 128
     sizes = {"qkv": T * 3 * H, "scores": BH * L * L * 4, "probs": BH * L * L, "ctx": T * H, "r1": T * H * 4,
-             "h1": T * H, "f1": T * F * 4, "g": T * F, "r2": T * H * 4}
+             "h1": T * H, "f1": T * F * 4, "g": T * F, "r2": T * H * 4,
+             # two sets of two 64-bit words a row, and a status word
+             "ln_stats": 2 * 16 * T + 4}
     spans = sorted((getattr(lo, k), getattr(lo, k) + v) for k, v in sizes.items())
     for (a0, a1), (b0, _) in zip(spans, spans[1:]):
         assert a1 <= b0
@@ -212,7 +214,7 @@ def test_fused_entry_points_reject_bad_arguments_before_touching_the_gpu():
     # the fusion mask: query, set, unknown bits dropped
     old = L.ibert_set_fusion(-1)
     assert L.ibert_set_fusion(0) == old and L.ibert_set_fusion(-1) == 0
-    assert L.ibert_set_fusion(0xff) == 0 and L.ibert_set_fusion(-1) == 3
+    assert L.ibert_set_fusion(0xff) == 0 and L.ibert_set_fusion(-1) == 7
     L.ibert_set_fusion(old)
 
 
