@@ -582,6 +582,34 @@ def _gemm_layernorm_case(G, M, N, K, fused):
         _eq(got, want, "gemm+layernorm ldy")
 
 
+def test_gemm_layernorm_many_tile_rows(G):
+    # far more tiles than the chip holds at once (2048 and 1280 workgroups, several rounds): tile rows that start late
+    # must still find their neighbours, and waiting tiles must not starve the ones they wait for
+    from paper_2101_01321_amd import binding as B
+    for M, N, K, cfg in ((32768, 768, 256, 9), (16384, 1024, 256, 7), (20480, 768, 2048, 11)):
+        rng = np.random.default_rng(M + N)
+        A = rng.integers(-127, 128, size=(M, K), dtype=np.int8)
+        W = rng.integers(-127, 128, size=(N, K), dtype=np.int8)
+        b = rng.integers(-2 ** 15, 2 ** 15, size=N).astype(np.int32)
+        R = rng.integers(-127, 128, size=(M, N), dtype=np.int8)
+        mult = np.full(N, 1518500250, np.int32)
+        shift = np.full(N, 36 + int(math.log2(K) // 2), np.int32)
+        gq, bq, s = B.ibert_layernorm_params_from_float(rng.normal(1.0, 0.1, size=N), rng.normal(0.0, 0.1, size=N), 5.0 / 127)
+        res_dy = (1717986918, 23)
+        kw = dict(M=M, N=N, K=K, batch_outer=1, batch_inner=1, lda=K, ldw=K, ldc=N, ldr=N, per_channel=1, out_dtype=I32,
+                  out_clamp=32767, residual_dy=res_dy)
+        spec = GemmSpec(M, N, K, per_channel=1, dy=(1, 0), out_dtype=I32, out_clamp=32767, res_dy=res_dy)
+        want = oracle.layernorm(oracle.gemm_requant(spec, A, W, b, mult, shift, R).reshape(M, N), gq, bq, s)
+        B.lib().ibert_gemm_config_override(cfg)
+        try:
+            G.say("gemm+layernorm M=%d N=%d K=%d cfg=%d" % (M, N, K, cfg))
+            got, status, r_head = G.gemm_layernorm(kw, A, W, b, mult, shift, R, gq, bq, s)
+        finally:
+            B.lib().ibert_gemm_config_override(-1)
+        assert status == 0 and np.all(r_head == 0x5A5A5A5A)
+        _eq(got, want, "gemm+layernorm M=%d" % M)
+
+
 def test_gemm_layernorm_degenerate_rows_and_general_requantization(G):
     # constant rows (sigma clamps to 1, the 32-bit multiply form), saturated rows, and multipliers / shifts outside the
     # fast requantization form (shift below 33), all inside the one-kernel shape
