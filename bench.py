@@ -381,6 +381,12 @@ def main():
                "sample": "%d of %d sequences through all %d layers (%.1f s); GPU output equal: %s"
                          % (n, c.batch, c.layers, dt, ok)}
 
+    # the fused MatMul + LayerNorm kernels record a wait that ran out in a status word of the workspace: must be 0
+    lo = B.ibert_encoder_layer_workspace_layout(c.batch, c.seq, c.hidden, c.heads, c.ffn)
+    st_off = lo.ln_stats + 2 * 16 * c.tokens
+    ln_status = int(ws[st_off:st_off + 4].view(torch.int32).item())
+    assert ln_status == 0, "a fused MatMul + LayerNorm tile gave up waiting for its neighbours"
+
     out = {
         "metric": "sequences/sec, int encoder (Base shape, seq128 b32)" if args.config == "base_b32"
                   else "sequences/sec, int encoder (%s)" % args.config,
