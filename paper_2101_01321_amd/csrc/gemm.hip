@@ -833,7 +833,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
 #pragma unroll
             for (int j = 0; j < FM; ++j) done = done && (uint32_t)(tsum[j] >> 40) == need && (uint32_t)(tsq[j] >> 48) == need;
             if (__builtin_amdgcn_ballot_w64(!done) == 0) break;
-            if (spins > (1 << 20)) {                               // seconds: never in a healthy run
+            if (spins > (1 << 16)) {                               // a tenth of a second: never in a healthy run
                 if (lane == 0) __hip_atomic_fetch_or(g.ln_status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 break;
             }
