@@ -610,6 +610,50 @@ def test_gemm_layernorm_many_tile_rows(G):
         _eq(got, want, "gemm+layernorm M=%d" % M)
 
 
+def test_fused_layer_replayed_from_a_graph(G):
+    # the whole layer with all three fusions captured into a HIP graph: the row statistics of the LayerNorm epilogues are
+    # cleared by kernels of the graph itself, so every replay (with eager work and synchronisation in between, and a
+    # different input each time) must give the oracle's result
+    import torch
+    from paper_2101_01321_amd import binding as B
+    cfg = synth.EncoderConfig("graph", 384, 6, 1536, 128, 4, 1)
+    x_q, S_x, _ = synth.input_activations(cfg)
+    model = G.DeviceModel(cfg, S_x)
+    w, q = P.layer_params(synth.layer_raw(cfg, 0), model.scales[0], cfg.hidden, cfg.heads)
+    B.lib().ibert_gemm_config_override(9)
+    try:
+        stream = torch.cuda.Stream()
+        tx = G.to_dev(x_q)
+        ty = torch.empty_like(tx)
+
+        def run():
+            B.ibert_encoder_layer_i(model.layers[0].weights, model.layers[0].quant, tx, ty, cfg.batch, cfg.seq, cfg.hidden,
+                                    cfg.heads, cfg.ffn, model.ws, stream=stream)
+        with torch.cuda.stream(stream):
+            model.mark_unwritten()
+            run()
+        torch.cuda.synchronize()
+        assert not model.was_written("r1") and not model.was_written("r2")       # the fused kernels did run
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            run()
+        rng = np.random.default_rng(11)
+        for rep in range(3):
+            x_rep = np.roll(x_q, rep * 7 + 1, axis=0) if rep else x_q
+            x_rep = np.ascontiguousarray(x_rep)
+            want = oracle.encoder_layer(w, q, x_rep, cfg.batch, cfg.seq, cfg.hidden, cfg.heads, cfg.ffn)
+            tx.copy_(G.to_dev(x_rep))
+            ty.zero_()
+            torch.cuda.synchronize()
+            G.say("graph replay %d of the fused layer" % rep)
+            graph.replay()
+            torch.cuda.synchronize()
+            _eq(ty.cpu().numpy(), want, "replay %d" % rep)
+            assert model.ln_status() == 0
+    finally:
+        B.lib().ibert_gemm_config_override(-1)
+
+
 def test_gemm_layernorm_degenerate_rows_and_general_requantization(G):
     # constant rows (sigma clamps to 1, the 32-bit multiply form), saturated rows, and multipliers / shifts outside the
     # fast requantization form (shift below 33), all inside the one-kernel shape
