@@ -164,19 +164,24 @@ struct EpiLayout {
 // complete or running and only the newest may be partly started; it is bounded all the same, and a wait that runs
 // out sets a status bit instead of hanging.
 template <int BM, int BN, int BK, int RING, bool OUT_I8, int KMODE, bool TW = false, bool DMA = false, bool GELU = false,
-          bool LN = false>
-__global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
+          bool LN = false, int NW = 4>
+__global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
 {
+    // NW wavefronts in two rows of NW/2: wavefront w owns rows [(w%2) BM/2, +BM/2) and columns [(w/2) WN, +WN) of the tile.
+    // Eight (two per SIMD) pay for INT8 tiles of 256x192: the second wavefront hides what the first waits for in the loop
+    // and in the packing epilogue (S1 of Large: 21.4 -> 19.9 us); with GELU in the epilogue they gain nothing.
+    constexpr int NT = 64 * NW;
+    static_assert(NW == 4 || (NW == 8 && DMA && !LN), "four wavefronts, or eight for the direct-to-LDS loader");
     static_assert(!GELU || OUT_I8, "the GELU epilogue writes INT8");
     static_assert(!LN || (DMA && !OUT_I8 && !GELU), "the LayerNorm epilogue belongs to the whole-tile INT32 kernels");
     constexpr int CPR = BK / 16;                       // 16-byte chunks per tile row
-    constexpr int RPP = GEMM_THREADS / CPR;            // tile rows loaded per pass of the workgroup
+    constexpr int RPP = NT / CPR;            // tile rows loaded per pass of the workgroup
     constexpr int LA = BM / RPP, LW = BN / RPP;        // chunks per lane per K step
-    constexpr int WM = BM / 2, WN = BN / 2;            // wavefront tile
+    constexpr int WM = BM / 2, WN = BN / (NW / 2);     // wavefront tile
     constexpr int FM = WM / 16, FN = WN / 16;
     constexpr int NS = BK / 64;                        // 64-wide K slices per step
     static_assert(BM % RPP == 0 && BN % RPP == 0 && WM % 16 == 0 && WN % 16 == 0, "tile shape");
-    static_assert(!TW || (BK / 4) * (BN / 4) == LW * GEMM_THREADS, "transposing loader covers the W tile exactly");
+    static_assert(!TW || (BK / 4) * (BN / 4) == LW * NT, "transposing loader covers the W tile exactly");
 
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     constexpr int STAGE = (BM + BN) * BK;
@@ -185,7 +190,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
     const int lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
     if (g.zero_words > 0) {
-        for (int64_t i = (int64_t)blockIdx.x * GEMM_THREADS + tid; i < g.zero_words; i += (int64_t)gridDim.x * GEMM_THREADS)
+        for (int64_t i = (int64_t)blockIdx.x * NT + tid; i < g.zero_words; i += (int64_t)gridDim.x * NT)
             g.zero_p[i] = 0u;
     }
 #ifdef IBERT_KERNEL_TIMING
@@ -225,7 +230,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
 #pragma unroll
     for (int i = 0; i < LW; ++i) {
         if (TW) {
-            const int q = i * GEMM_THREADS + tid;
+            const int q = i * NT + tid;
             tw_k[i] = (q / NB4) * 4;
             tw_n[i] = (q % NB4) * 4;
             const int ncol = n0 + tw_n[i];
@@ -305,11 +310,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
     };
 
     // Per-channel constants of this tile's BN columns, one or two columns per lane; used after the main loop.
-    constexpr int PPT = (BN + GEMM_THREADS - 1) / GEMM_THREADS;
+    constexpr int PPT = (BN + NT - 1) / NT;
     int32_t pb[PPT], pm[PPT], ps[PPT], pg[PPT], pe[PPT];
 #pragma unroll
     for (int q = 0; q < PPT; ++q) {
-        int nn = n0 + q * GEMM_THREADS + tid;
+        int nn = n0 + q * NT + tid;
         nn = nn < g.N ? nn : g.N - 1;
         pb[q] = 0; pm[q] = g.dy_m; ps[q] = g.dy_s; pg[q] = 0; pe[q] = 0;
         if (g.bias) pb[q] = g.bias[nn];
@@ -324,11 +329,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
     }
 
     if constexpr (DMA) {
-        static_assert(BK == 128 && !TW && KMODE == 0 && BM % 32 == 0 && BN % 32 == 0, "DMA loader: whole 1 KB blocks");
-        constexpr int NLA = BM / 32, NLW = BN / 32, NL = NLA + NLW;   // 1 KB blocks per wavefront and step
+        constexpr int RG = 8 * NW;                                    // tile rows the wavefronts fetch together
+        static_assert(BK == 128 && !TW && KMODE == 0 && BM % RG == 0 && BN % RG == 0, "DMA loader: whole 1 KB blocks");
+        constexpr int NLA = BM / RG, NLW = BN / RG, NL = NLA + NLW;   // 1 KB blocks per wavefront and step
         constexpr int NMF = FM * FN, NR = FM + FN;
         constexpr int SPC = NMF / NR > 0 ? NMF / NR : 1;              // MFMAs between two fragment reads
-        static_assert(NR == NL && (NMF + SPC - 1) / SPC >= NR, "one read and one load per slot");
+        static_assert(NL <= NR && (NMF + SPC - 1) / SPC >= NR, "one read and at most one load per slot");
         const int wv = __builtin_amdgcn_readfirstlane(wave);
         const int lr8 = lane >> 3, lp = lane & 7;
         const int lsw = lr8;                                          // swz<8> of the lane's row (blocks are 8 rows)
@@ -338,12 +344,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
         const int8_t* gw = W + (int64_t)(n0 + wv * 8) * g.ldw;
         const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t*)lds + (uint32_t)wv * 1024u;
 
-        // block q of the step: rows [32 i + 8 wave, +8) of A (q < NLA) or of W
+        // block q of the step: rows [RG i + 8 wave, +8) of A (q < NLA) or of W
         auto dma_one = [&](int q, int kt, int buf) {
             const bool is_a = q < NLA;
             const int i = is_a ? q : q - NLA;
-            const int8_t* sb = (is_a ? ga + (int64_t)i * 32 * g.lda : gw + (int64_t)i * 32 * g.ldw) + (int64_t)kt * BK;
-            const uint32_t la = lds0 + (uint32_t)(buf * STAGE + (is_a ? 0 : BM * BK) + i * 4096);
+            const int8_t* sb = (is_a ? ga + (int64_t)i * RG * g.lda : gw + (int64_t)i * RG * g.ldw) + (int64_t)kt * BK;
+            const uint32_t la = lds0 + (uint32_t)(buf * STAGE + (is_a ? 0 : BM * BK) + i * (RG * BK));
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :: "s"(la), "v"(is_a ? voff_a : voff_w), "s"(sb) : "memory", "m0");
         };
@@ -403,7 +409,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
             // read.  Every workgroup builds its own copy with the very function the table stands for.
             int8_t* lut = lds + EpiLayout<BM, BN, BK, RING>::LDS_BYTES;
             const int32_t rnd = 1 << ((g.gelu.s - 33) & 31), sh = (g.gelu.s - 32) & 31;
-            for (int e = tid; e < g.gelu_lut_n; e += GEMM_THREADS) {
+            for (int e = tid; e < g.gelu_lut_n; e += NT) {
                 const int32_t q = g.gelu_lut_lo + e;
                 lut[e] = (int8_t)(g.gelu_fast ? gelu_one_fast(q, g.gelu, rnd, sh) : gelu_one(q, g.gelu));
             }
@@ -503,7 +509,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
     using EL = EpiLayout<BM, BN, BK, (DMA ? RING : 2)>;
     constexpr int SP = EL::SP, JC = EL::JC;
     constexpr int G4 = BN / 4;                                     // 4-channel groups per row
-    constexpr int RPS = GEMM_THREADS / G4;                         // rows finished per pass of the workgroup
+    constexpr int RPS = NT / G4;                         // rows finished per pass of the workgroup
     static_assert(FM % JC == 0 && RPS >= 1, "epilogue layout");
     int32_t* stage = reinterpret_cast<int32_t*>(lds);              // [32 * JC][SP]
     int32_t* par = stage + 32 * JC * SP;                           // [3][BN]: bias, mult, shift
@@ -520,7 +526,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
     int bad = 0;
 #pragma unroll
     for (int q = 0; q < PPT; ++q) {
-        const int c = q * GEMM_THREADS + tid;
+        const int c = q * NT + tid;
         if (c < BN) {
             par[c] = pb[q];
             par[BN + c] = pm[q];
@@ -537,18 +543,18 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
         // residual tile -> LDS, 16 bytes per lane, rows of BN bytes
         constexpr int CH = BM * BN / 16;                           // 16-byte chunks in the tile
 #pragma unroll 1
-        for (int q0 = 0; q0 < CH; q0 += 4 * GEMM_THREADS) {
+        for (int q0 = 0; q0 < CH; q0 += 4 * NT) {
             v4i t[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int q = q0 + u * GEMM_THREADS + tid;
+                const int q = q0 + u * NT + tid;
                 const int qq = q < CH ? q : 0;
                 const int row = qq / (BN / 16), c16 = qq - row * (BN / 16);
                 t[u] = *reinterpret_cast<const v4i*>(R + (int64_t)(m0 + row) * g.ldr + n0 + c16 * 16);
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int q = q0 + u * GEMM_THREADS + tid;
+                const int q = q0 + u * NT + tid;
                 if (q < CH) *reinterpret_cast<v4i*>(resl + q * 4) = t[u];
             }
         }
@@ -733,9 +739,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
             constexpr int C16 = BN / 16, CH = BM * C16;            // 16-byte chunks per row, per tile
             char* const ct = reinterpret_cast<char*>(g.C) + c_off + (int64_t)m0 * g.ldc + n0;
 #pragma unroll
-            for (int q0 = 0; q0 < CH; q0 += GEMM_THREADS) {
+            for (int q0 = 0; q0 < CH; q0 += NT) {
                 const int q = q0 + tid;
-                if (CH % GEMM_THREADS == 0 || q < CH) {
+                if (CH % NT == 0 || q < CH) {
                     const int row = q / C16, c16 = q - row * C16;
                     *reinterpret_cast<v4i*>(ct + (uint32_t)row * c_pitch + c16 * 16) =
                         *reinterpret_cast<const v4i*>(ostage + row * SPB + c16 * 16);
@@ -880,9 +886,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
         constexpr int C16 = BN / 16, CH = BM * C16;
         int8_t* const yt = g.ln_y + (int64_t)m0 * g.ln_ldy + n0;
 #pragma unroll
-        for (int q0 = 0; q0 < CH; q0 += GEMM_THREADS) {
+        for (int q0 = 0; q0 < CH; q0 += NT) {
             const int q = q0 + tid;
-            if (CH % GEMM_THREADS == 0 || q < CH) {
+            if (CH % NT == 0 || q < CH) {
                 const int row = q / C16, c16 = q - row * C16;
                 *reinterpret_cast<v4i*>(yt + (int64_t)row * g.ln_ldy + c16 * 16) = *reinterpret_cast<const v4i*>(ostage + row * SPB + c16 * 16);
             }
@@ -912,7 +918,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_nt_mfma_kernel(GemmArgs g)
 #ifdef IBERT_KERNEL_TIMING
     IBERT_TS(4);
     if (g.dbg && lane == 0) {
-        long long* o = g.dbg + ((long long)blockIdx.x * 4 + wave) * 8;
+        long long* o = g.dbg + ((long long)blockIdx.x * NW + wave) * 8;
         for (int i = 0; i < 8; ++i) o[i] = tstamp[i];
     }
 #endif
@@ -995,6 +1001,7 @@ static const GemmConfig kConfigs[] = {      // index = configuration number of i
     {256, 128, 128, 2, true},
     {128, 96, 128, 3, true},
     {128, 128, 128, 3, true},
+    {256, 192, 128, 2, true},       // with eight wavefronts (no GELU epilogue)
 };
 constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 #ifdef IBERT_KERNEL_TIMING
@@ -1002,7 +1009,7 @@ static long long* g_dbg_buf = nullptr;
 #endif
 static int g_config_override = -1;
 
-template <int BM, int BN, int BK, int RING, bool TW = false, bool DMA = false, bool GELU = false, bool LN = false>
+template <int BM, int BN, int BK, int RING, bool TW = false, bool DMA = false, bool GELU = false, bool LN = false, int NW = 4>
 static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
 {
     g.tiles_m = (g.M + BM - 1) / BM;
@@ -1022,14 +1029,14 @@ static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
     }
 #define IBERT_GEMM_LAUNCH(I8_, KT_)                                                                       \
     do {                                                                                                  \
-        auto kern = gemm_nt_mfma_kernel<BM, BN, BK, RING, I8_, KT_, TW, DMA, GELU && I8_, LN && !I8_>;       \
+        auto kern = gemm_nt_mfma_kernel<BM, BN, BK, RING, I8_, KT_, TW, DMA, GELU && I8_, LN && !I8_, NW>;   \
         static size_t attr_bytes = 0;                                                                     \
         if (lds_bytes > attr_bytes) {                                                                     \
             IBERT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                      \
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes)); \
             attr_bytes = lds_bytes;                                                                       \
         }                                                                                                 \
-        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(GEMM_THREADS), lds_bytes, stream, g);       \
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * NW), lds_bytes, stream, g);            \
     } while (0)
     if constexpr (GELU) {
         if (!i8 || g.K % BK != 0) return IBERT_ERR_NOT_IMPLEMENTED;
@@ -1052,9 +1059,9 @@ static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
     static char label[2][2][96];
     char* l = label[i8 ? 1 : 0][g.K % BK == 0 ? 0 : 1];
     if (!l[0])
-        std::snprintf(l, sizeof label[0][0], "gemm_nt_mfma_kernel<%d, %d, %d, %d, %s, %d, %s, %s, %s, %s>", BM, BN, BK, RING,
+        std::snprintf(l, sizeof label[0][0], "gemm_nt_mfma_kernel<%d, %d, %d, %d, %s, %d, %s, %s, %s, %s, %d>", BM, BN, BK, RING,
                       i8 ? "true" : "false", g.K % BK == 0 ? 0 : 1, TW ? "true" : "false", DMA ? "true" : "false",
-                      GELU ? "true" : "false", LN ? "true" : "false");
+                      GELU ? "true" : "false", LN ? "true" : "false", NW);
     g_last_kernel = l;
     return IBERT_OK;
 }
@@ -1138,7 +1145,7 @@ static int choose_config(const ibert_gemm_desc& d, int64_t nb, bool gelu)
     auto tiles = [&](int bm, int bn) -> int64_t { return dma_ok(d, bm, bn) ? (int64_t)(d.M / bm) * (d.N / bn) * nb : 0; };
     // (256x256 pays only when K is long enough to amortise its 256-value-per-lane epilogue, and never with GELU in it)
     if (tiles(256, 256) >= 512 && d.K >= 8192 && !gelu) return 8;
-    if (tiles(256, 192) >= 224) return 6;
+    if (tiles(256, 192) >= 224) return gelu ? 6 : 13;             // (eight wavefronts: see the kernel's note)
     // (one workgroup per CU and a long K: a third LDS stage lets the requests spread over the whole step)
     if (tiles(128, 96) >= 256) return tiles(128, 96) <= 256 && d.K >= 2048 ? 11 : 9;
     if (tiles(256, 128) >= 448) return 10;
@@ -1256,6 +1263,7 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
             case 10: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 2, false, true>(g, i8, stream); break;
             case 11: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 3, false, true>(g, i8, stream); break;
             case 12: if (dma_ok(d, 128, 128)) return launch_mfma<128, 128, 128, 3, false, true>(g, i8, stream); break;
+            case 13: if (dma_ok(d, 256, 192)) return launch_mfma<256, 192, 128, 2, false, true, false, false, 8>(g, i8, stream); break;
             default: break;
         }
         return launch_mfma<128, 128, 64, 2>(g, i8, stream);

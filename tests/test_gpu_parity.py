@@ -339,7 +339,9 @@ def test_gemm_trans_w_mfma_path(G, M, N, K, ldw):
                                        # three LDS stages: every step count around the ring depth
                                        (11, 128, 96, 128), (11, 256, 96, 256), (11, 128, 192, 384), (11, 128, 96, 512),
                                        (11, 256, 192, 1280), (12, 128, 128, 128), (12, 128, 128, 256), (12, 256, 128, 384),
-                                       (12, 128, 256, 512), (12, 128, 256, 1024)])
+                                       (12, 128, 256, 512), (12, 128, 256, 1024),
+                                       # 256x192 with eight wavefronts
+                                       (13, 256, 192, 128), (13, 512, 384, 256), (13, 256, 576, 640), (13, 768, 192, 1152)])
 def test_gemm_direct_to_lds_tiles(G, cfg, M, N, K):
     # the tile configurations whose loader writes LDS straight from global memory (whole tiles only), forced
     # through the configuration override; 1, 2, odd and even numbers of K steps
