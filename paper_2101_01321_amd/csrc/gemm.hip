@@ -845,19 +845,28 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
             }
             __builtin_amdgcn_s_sleep(2);
         }
-        // 4: per-row mean and factor (every lane of a row repeats them)
+        // 4: per-row mean and factor.  The four lanes that share rows 16 j + l%16 (j = 0..3) split them: lane l works out
+        //    row l alone (j = l/16) and the results are handed round, so the divisions and the root are done once per row
+        //    and wavefront instead of four times.
+        static_assert(FM == 4, "one row per lane");
         const uint32_t Nu = (uint32_t)g.N;
         int32_t mu[FM], fr[FM];
-        bool big = false;
-#pragma unroll
-        for (int j = 0; j < FM; ++j) {
-            const int32_t S = (int32_t)(uint32_t)(tsum[j] & (((unsigned long long)1 << 40) - 1)) - (int32_t)(need << 21);
-            const unsigned long long Q = tsq[j] & (((unsigned long long)1 << 48) - 1);
-            mu[j] = ln_row_mean(S, Nu, g.ln_magic);
+        bool big;
+        {
+            const unsigned long long ts = fch == 0 ? tsum[0] : (fch == 1 ? tsum[1] : (fch == 2 ? tsum[2] : tsum[3]));
+            const unsigned long long tq = fch == 0 ? tsq[0] : (fch == 1 ? tsq[1] : (fch == 2 ? tsq[2] : tsq[3]));
+            const int32_t S = (int32_t)(uint32_t)(ts & (((unsigned long long)1 << 40) - 1)) - (int32_t)(need << 21);
+            const unsigned long long Q = tq & (((unsigned long long)1 << 48) - 1);
+            const int32_t mu_own = ln_row_mean(S, Nu, g.ln_magic);
             // sum (x - mu)^2 = Q - 2 mu S + N mu^2: exact in 64 bits, never negative
-            const int64_t ssd = (int64_t)Q - 2 * (int64_t)mu[j] * S + (int64_t)Nu * mu[j] * mu[j];
-            fr[j] = ln_row_factor((uint64_t)ssd, Nu, g.ln_magic);
-            big |= fr[j] >= (1 << 23);
+            const int64_t ssd = (int64_t)Q - 2 * (int64_t)mu_own * S + (int64_t)Nu * mu_own * mu_own;
+            const int32_t f_own = ln_row_factor((uint64_t)ssd, Nu, g.ln_magic);
+            big = f_own >= (1 << 23);
+#pragma unroll
+            for (int j = 0; j < FM; ++j) {
+                mu[j] = __shfl(mu_own, 16 * j + frow, 64);
+                fr[j] = __shfl(f_own, 16 * j + frow, 64);
+            }
         }
         const bool f24 = __builtin_amdgcn_ballot_w64(big) == 0;   // else sigma <= 2 somewhere: full 32-bit multiplies
         // 5: normalize, pack, and go through LDS once so that the stores are whole 16-byte pieces of rows
