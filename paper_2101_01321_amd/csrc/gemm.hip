@@ -169,7 +169,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
 {
     // NW wavefronts in two rows of NW/2: wavefront w owns rows [(w%2) BM/2, +BM/2) and columns [(w/2) WN, +WN) of the tile.
     // Eight (two per SIMD) pay for INT8 tiles of 256x192: the second wavefront hides what the first waits for in the loop
-    // and in the packing epilogue (S1 of Large: 21.4 -> 19.9 us); with GELU in the epilogue they gain nothing.
+    // and in the packing epilogue (inside the encoder: S1 of Large 21.4 -> 19.9 us, S7+S8 of Base 20.6 -> 19.3 us).
     constexpr int NT = 64 * NW;
     static_assert(NW == 4 || (NW == 8 && DMA && !LN), "four wavefronts, or eight for the direct-to-LDS loader");
     static_assert(!GELU || OUT_I8, "the GELU epilogue writes INT8");
@@ -1154,8 +1154,8 @@ static int choose_config(const ibert_gemm_desc& d, int64_t nb, bool gelu)
     auto tiles = [&](int bm, int bn) -> int64_t { return dma_ok(d, bm, bn) ? (int64_t)(d.M / bm) * (d.N / bn) * nb : 0; };
     // (256x256 pays only when K is long enough to amortise its 256-value-per-lane epilogue, and never with GELU in it)
     if (tiles(256, 256) >= 512 && d.K >= 8192 && !gelu) return 8;
-    // (with eight wavefronts the tile also pays at three quarters of a wave of tiles: S1 of Base, 192 tiles, 17.1 -> 15.1 us)
-    if (tiles(256, 192) >= (gelu ? 224 : 192)) return gelu ? 6 : 13;
+    // (with eight wavefronts; it pays from three quarters of a wave of tiles on: S1 of Base, 192 tiles, 17.1 -> 15.1 us)
+    if (tiles(256, 192) >= (gelu ? 224 : 192)) return 13;
     // (one workgroup per CU and a long K: a third LDS stage lets the requests spread over the whole step)
     if (tiles(128, 96) >= 256) return tiles(128, 96) <= 256 && d.K >= 2048 ? 11 : 9;
     if (tiles(256, 128) >= 448) return 10;
@@ -1255,6 +1255,7 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
                 case 7: if (dma_ok(d, 128, 128)) return launch_mfma<128, 128, 128, 2, false, true, true>(g, i8, stream); break;
                 case 9: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 2, false, true, true>(g, i8, stream); break;
                 case 10: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 2, false, true, true>(g, i8, stream); break;
+                case 13: if (dma_ok(d, 256, 192)) return launch_mfma<256, 192, 128, 2, false, true, true, false, 8>(g, i8, stream); break;
                 default: break;
             }
             return IBERT_ERR_NOT_IMPLEMENTED;

@@ -356,6 +356,7 @@ def test_gemm_direct_to_lds_tiles(G, cfg, M, N, K):
 
 
 @pytest.mark.parametrize("cfg,M,N,K", [(-1, 4096, 3072, 768), (6, 512, 384, 256), (7, 256, 384, 128), (10, 256, 384, 384),
+                                       (13, 512, 384, 256), (13, 256, 576, 640),
                                        (9, 384, 288, 256), (10, 512, 256, 128), (-1, 100, 72, 48), (-1, 130, 64, 128)])
 @pytest.mark.parametrize("S_in,S_out", [(2.0 ** -7, 8.0 / 127), (0.011, 0.02)])
 def test_gemm_gelu_equals_matmul_then_gelu(G, cfg, M, N, K, S_in, S_out):
