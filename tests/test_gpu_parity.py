@@ -341,7 +341,8 @@ def test_gemm_trans_w_mfma_path(G, M, N, K, ldw):
                                        (11, 256, 192, 1280), (12, 128, 128, 128), (12, 128, 128, 256), (12, 256, 128, 384),
                                        (12, 128, 256, 512), (12, 128, 256, 1024),
                                        # 256x192 with eight wavefronts
-                                       (13, 256, 192, 128), (13, 512, 384, 256), (13, 256, 576, 640), (13, 768, 192, 1152)])
+                                       (13, 256, 192, 128), (13, 512, 384, 256), (13, 256, 576, 640), (13, 768, 192, 1152),
+                                       (14, 256, 128, 128), (14, 512, 384, 256), (14, 256, 256, 896)])
 def test_gemm_direct_to_lds_tiles(G, cfg, M, N, K):
     # the tile configurations whose loader writes LDS straight from global memory (whole tiles only), forced
     # through the configuration override; 1, 2, odd and even numbers of K steps
@@ -356,7 +357,7 @@ def test_gemm_direct_to_lds_tiles(G, cfg, M, N, K):
 
 
 @pytest.mark.parametrize("cfg,M,N,K", [(-1, 4096, 3072, 768), (6, 512, 384, 256), (7, 256, 384, 128), (10, 256, 384, 384),
-                                       (13, 512, 384, 256), (13, 256, 576, 640),
+                                       (13, 512, 384, 256), (13, 256, 576, 640), (14, 512, 256, 384),
                                        (9, 384, 288, 256), (10, 512, 256, 128), (-1, 100, 72, 48), (-1, 130, 64, 128)])
 @pytest.mark.parametrize("S_in,S_out", [(2.0 ** -7, 8.0 / 127), (0.011, 0.02)])
 def test_gemm_gelu_equals_matmul_then_gelu(G, cfg, M, N, K, S_in, S_out):
