@@ -11,7 +11,9 @@
 //   * Two tile loaders: global memory straight into LDS (whole tiles, K a multiple of 128), or through a ring
 //     of registers (everything else that is 16-byte aligned, and W given as [K,N] with aligned rows).
 //   * Integer accumulation is exact, so any consistent K order gives the oracle's bits.
-//   * The epilogue can also apply integer GELU (Alg. 2) to its own INT8 output.
+//   * The epilogue can also apply integer GELU (Alg. 2) to its own INT8 output, or integer LayerNorm (Sec. 3.6) to its
+//     own INT32 result (the column tiles of a row exchange the row's sum and sum of squares through atomics).
+//   * Four wavefronts per workgroup, or eight (two per SIMD) for the big INT8 tiles.
 // Generic path (unaligned operands): one output element per lane, byte loads.
 #include <cstdio>
 #include <type_traits>
