@@ -3,8 +3,7 @@
 // A row (C <= 1024 int32) is owned by LPR lanes of one wavefront and kept in registers, so HBM is
 // read once.  Sum and sum of squared deviations are butterfly reductions inside the lane group; the
 // per-row scalar work (mean, variance, Newton integer square root, reciprocal factor) is done
-// redundantly by the lanes of the group, which is why short groups (16 lanes, 4 rows per wave) are
-// preferred when there are enough rows to fill the chip.
+// redundantly by the lanes of the group.
 //
 // The same kernel also serves the INT8 embedding (Sec. 1, contribution 3; App. C.1): there the row is not read from
 // an INT32 buffer but made on the fly from one row of the INT8 token table and one of the INT8 position table, each
@@ -45,12 +44,11 @@ __device__ __forceinline__ int32_t group_sum_i32(int32_t v)
 template <int LPR>
 __device__ __forceinline__ uint64_t group_sum_u64(uint64_t v)
 {
-    // every lane value is below 2^38 here (<= 64 squares below 2^32); split into 19-bit limbs so that a sum of
-    // 64 limbs stays below 2^25 and plain 32-bit all-reduces are exact
-    const int32_t l0 = (int32_t)(v & 0x7ffff), l1 = (int32_t)((v >> 19) & 0x7ffff), l2 = (int32_t)(v >> 38);
-    const uint64_t s0 = (uint32_t)group_sum_i32<LPR>(l0), s1 = (uint32_t)group_sum_i32<LPR>(l1),
-                   s2 = (uint32_t)group_sum_i32<LPR>(l2);
-    return s0 + (s1 << 19) + (s2 << 38);
+    // every lane value is below 2^34 here (at most 16 squares below 2^30); split at bit 19 so that both parts,
+    // summed over 64 lanes, stay below 2^25 and plain 32-bit all-reduces are exact
+    const int32_t l0 = (int32_t)(v & 0x7ffff), l1 = (int32_t)(v >> 19);
+    const uint64_t s0 = (uint32_t)group_sum_i32<LPR>(l0), s1 = (uint32_t)group_sum_i32<LPR>(l1);
+    return s0 + (s1 << 19);
 }
 
 constexpr int LN_THREADS = 256;
@@ -58,10 +56,12 @@ constexpr int LN_THREADS = 256;
 // ALIGNED: rows 16-byte (x) / 4-byte (y) aligned, C % 4 == 0, gamma/beta 16-byte aligned: every 4-element
 // chunk is either entirely inside the row or entirely outside, and moves as one vector.
 // EMB: the row is DY(tok[id]) + DY(pos[row mod seq]) instead of x[row] (ALIGNED then means 4-byte aligned table rows).
-template <int LPR, int NCH, bool ALIGNED, bool EMB = false>
+// FULL: C == NCH * LPR * 4 (and ALIGNED), so no chunk lies outside the row and the column masks fold away.
+template <int LPR, int NCH, bool ALIGNED, bool EMB = false, bool FULL = false>
 __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArgs a)
 {
     constexpr int ROWS_PER_BLOCK = LN_THREADS / LPR;
+    static_assert(NCH * 4 <= 16, "a lane's sum of squares must stay below 2^34");
     const int lane = threadIdx.x % LPR;
     const int64_t row = (int64_t)blockIdx.x * ROWS_PER_BLOCK + threadIdx.x / LPR;
     const bool live = row < a.rows;
@@ -77,16 +77,6 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
     }
     const int32_t rnd = 1 << (a.shift - 1);
 
-    // gamma and beta are shared by every row of the workgroup: one coalesced copy into LDS
-    __shared__ __attribute__((aligned(16))) int32_t s_gamma[1024];
-    __shared__ __attribute__((aligned(16))) int32_t s_beta[1024];
-    if (ALIGNED) {
-        for (int i = threadIdx.x * 4; i < C; i += LN_THREADS * 4) {
-            *reinterpret_cast<int4*>(s_gamma + i) = *reinterpret_cast<const int4*>(a.gamma_q + i);
-            *reinterpret_cast<int4*>(s_beta + i) = *reinterpret_cast<const int4*>(a.beta_q + i);
-        }
-    }
-
     int32_t v[NCH][4], gm[NCH][4], bt[NCH][4];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
@@ -94,7 +84,7 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
         if (EMB) {
             int32_t tv[4], pv[4];
             if (ALIGNED) {
-                const int cc = col < C ? col : 0;
+                const int cc = (FULL || col < C) ? col : 0;
                 const uint32_t t4 = *reinterpret_cast<const uint32_t*>(tr + cc), p4 = *reinterpret_cast<const uint32_t*>(pr + cc);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -114,7 +104,7 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
             for (int e = 0; e < 4; ++e)
                 v[c][e] = clamp_i64_to_i32(dyadic64(tv[e], a.emb.tok_m, a.emb.tok_s) + dyadic64(pv[e], a.emb.pos_m, a.emb.pos_s), 32767);
         } else if (ALIGNED) {
-            const int cc = col < C ? col : 0;          // out-of-row chunks re-read chunk 0 and are masked below
+            const int cc = (FULL || col < C) ? col : 0; // out-of-row chunks re-read chunk 0 and are masked below
             const int4 t = *reinterpret_cast<const int4*>(xr + cc);
             v[c][0] = t.x; v[c][1] = t.y; v[c][2] = t.z; v[c][3] = t.w;
         } else {
@@ -122,14 +112,15 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
             for (int e = 0; e < 4; ++e) v[c][e] = (live && col + e < C) ? xr[col + e] : 0;
         }
     }
-    if (ALIGNED) __syncthreads();
+    // gamma and beta after the row itself, so that the row is the first thing in flight; every wavefront of a
+    // compute unit reads the same few KB, which the vector cache serves after the first
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         const int col = (c * LPR + lane) * 4;
         if (ALIGNED) {
-            const int cc = col < C ? col : 0;
-            const int4 g4 = *reinterpret_cast<const int4*>(s_gamma + cc);
-            const int4 b4 = *reinterpret_cast<const int4*>(s_beta + cc);
+            const int cc = (FULL || col < C) ? col : 0;
+            const int4 g4 = *reinterpret_cast<const int4*>(a.gamma_q + cc);
+            const int4 b4 = *reinterpret_cast<const int4*>(a.beta_q + cc);
             gm[c][0] = g4.x; gm[c][1] = g4.y; gm[c][2] = g4.z; gm[c][3] = g4.w;
             bt[c][0] = b4.x + rnd; bt[c][1] = b4.y + rnd; bt[c][2] = b4.z + rnd; bt[c][3] = b4.w + rnd;
         } else {
@@ -142,38 +133,30 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
         }
     }
 
-    // clamp on load, sum
+    // clamp on load; the sum and the sum of squares in one sweep, so that their reductions overlap
     int32_t sum = 0;
+    uint64_t sq = 0;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         const int col = (c * LPR + lane) * 4;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const bool in = ALIGNED ? col < C : col + e < C;
-            v[c][e] = in ? med3_i32(v[c][e], -32767, 32767) : 0;
+            const int32_t keep = (FULL || (ALIGNED ? col < C : col + e < C)) ? -1 : 0;
+            v[c][e] = med3_i32(v[c][e], -32767, 32767) & keep;
             sum += v[c][e];                            // |sum| <= 1024 * 32767 < 2^25
+            sq += (uint32_t)smul24(v[c][e], v[c][e]);  // |v| < 2^15: a 24-bit multiply; the total is below 2^40
         }
     }
     sum = group_sum_i32<LPR>(sum);
+    sq = group_sum_u64<LPR>(sq);
 
     // mu = floor((sum + floor(C/2)) / C), computed on the non-negative number sum + C/2 + 32768 C
     const uint32_t Cu = (uint32_t)C;
     const int32_t mu = ln_row_mean(sum, Cu, a.magic_c);
 
-    // ss = sum d^2: |d| < 2^17, so d*d is a 24-bit multiply; each square is below 2^32, the total below 2^42
-    uint64_t ss = 0;
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        const int col = (c * LPR + lane) * 4;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const bool in = ALIGNED ? col < C : col + e < C;
-            const int32_t d = in ? v[c][e] - mu : 0;
-            v[c][e] = d;
-            ss += (uint32_t)smul24(d, d);
-        }
-    }
-    ss = group_sum_u64<LPR>(ss);
+    // sum of squared deviations from the two totals: sum (v - mu)^2 = sq - 2 mu sum + C mu^2, exact in 64 bits
+    // (|2 mu sum| < 2^42, C mu^2 <= 2^40)
+    const uint64_t ss = (uint64_t)((int64_t)sq - 2 * (int64_t)mu * sum + (int64_t)C * ((int64_t)mu * mu));
 
     const int32_t f = ln_row_factor(ss, Cu, a.magic_c);
     if (!live) return;
@@ -184,11 +167,12 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         const int col = (c * LPR + lane) * 4;
-        if (col >= C) continue;
+        if (!FULL && col >= C) continue;
         int32_t o[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int32_t n = (f24 ? smul24(v[c][e], f) : v[c][e] * f) >> 14;   // |d*f| < 2^30; |n| < 2^16
+            const int32_t d = v[c][e] - mu;                                        // |d| < 2^17
+            const int32_t n = (f24 ? smul24(d, f) : d * f) >> 14;                  // |d*f| < 2^30; |n| < 2^16
             const int32_t acc = smad24(n, gm[c][e], bt[c][e]);                     // |gamma_q| < 2^14: 24-bit multiply
             o[e] = med3_i32(acc >> a.shift, -127, 127);
         }
@@ -229,35 +213,26 @@ static void launch_rows(const LayerNormArgs& a, bool al, hipStream_t stream)
 {
     constexpr int rpb = LN_THREADS / LPR;
     const unsigned blocks = (unsigned)((a.rows + rpb - 1) / rpb);
+    const bool full = al && a.C == NCH * LPR * 4;
     if (a.emb.ids) {
-        if (al) hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, true, true>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
+        if (full) hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, true, true, true>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
+        else if (al) hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, true, true>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
         else hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, false, true>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
-    } else if (al) hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, true>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
+    } else if (full) hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, true, false, true>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
+    else if (al) hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, true>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
     else hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, false>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
 }
 
 static int dispatch_rows(const LayerNormArgs& a, bool al, hipStream_t stream)
 {
-    const int64_t rows = a.rows;
     const int32_t C = a.C;
-    // Lanes per row: the per-row scalar work (mean, variance, square root, reciprocal) is repeated by every
-    // lane of a row, so short groups are cheaper, but the chip needs about two wavefronts per SIMD (2048 in
-    // all) to overlap the load, reduce and store phases of different rows.
-    if (rows < 2048) {
-        if (C <= 256) launch_rows<64, 1>(a, al, stream);
-        else if (C <= 512) launch_rows<64, 2>(a, al, stream);
-        else launch_rows<64, 4>(a, al, stream);
-    } else if (rows < 16384) {
-        if (C <= 256) launch_rows<32, 2>(a, al, stream);
-        else if (C <= 512) launch_rows<32, 4>(a, al, stream);
-        else if (C <= 768) launch_rows<32, 6>(a, al, stream);
-        else launch_rows<32, 8>(a, al, stream);
-    } else {
-        if (C <= 256) launch_rows<16, 4>(a, al, stream);
-        else if (C <= 512) launch_rows<16, 8>(a, al, stream);
-        else if (C <= 768) launch_rows<16, 12>(a, al, stream);
-        else launch_rows<16, 16>(a, al, stream);
-    }
+    // One wavefront per row (two rows for short ones): the per-row scalar work (mean, variance, square root,
+    // reciprocal) is repeated by every lane of a row, but few registers per lane let many rows be in flight on a
+    // compute unit, which is what hides the memory latency; shorter groups measured slower at every size.
+    if (C <= 256) launch_rows<32, 2>(a, al, stream);
+    else if (C <= 512) launch_rows<64, 2>(a, al, stream);
+    else if (C <= 768) launch_rows<64, 3>(a, al, stream);
+    else launch_rows<64, 4>(a, al, stream);
     IBERT_LAUNCH_CHECK("layernorm kernel");
     g_last_kernel = a.emb.ids ? "layernorm_rows_kernel<embedding>" : "layernorm_rows_kernel";
     return IBERT_OK;
