@@ -356,6 +356,21 @@ def test_gemm_direct_to_lds_tiles(G, cfg, M, N, K):
         B.lib().ibert_gemm_config_override(-1)
 
 
+@pytest.mark.parametrize("cfg", [15, -1])
+@pytest.mark.parametrize("M,N,K", [(128, 768, 3072), (32, 32, 128), (33, 65, 144), (100, 200, 512), (7, 40, 16), (160, 96, 1000)])
+def test_gemm_small_tiles(G, cfg, M, N, K):
+    # the 32-row tiles of the small-batch regime, forced through the configuration override and by the launcher's
+    # own choice: whole and ragged tiles, one to many K steps, a K tail
+    from paper_2101_01321_amd import binding as B
+    assert B.lib().ibert_gemm_config_override(cfg) > 15
+    try:
+        for out_dtype, pc, bias, res in [(I8, 1, True, False), (I32, 1, True, True), (I8, 0, False, True)]:
+            G.say("gemm small tiles cfg=%d M=%d N=%d K=%d out=%d" % (cfg, M, N, K, out_dtype))
+            _gemm_case(G, M, N, K, out_dtype, pc, bias, res, seed=cfg + M + N + K)
+    finally:
+        B.lib().ibert_gemm_config_override(-1)
+
+
 @pytest.mark.parametrize("cfg,M,N,K", [(-1, 4096, 3072, 768), (6, 512, 384, 256), (7, 256, 384, 128), (10, 256, 384, 384),
                                        (13, 512, 384, 256), (13, 256, 576, 640), (14, 512, 256, 384),
                                        (9, 384, 288, 256), (10, 512, 256, 128), (-1, 100, 72, 48), (-1, 130, 64, 128)])
