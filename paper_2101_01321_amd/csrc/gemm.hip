@@ -1037,7 +1037,8 @@ static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
         // the GELU table rides behind the tile's LDS if it fits the CU's 160 KB (and, for tiles that share a CU,
         // stays small enough not to cost a resident workgroup)
         const size_t room = lds_tile >= 81920 ? 160000 - lds_tile : (163840 / 2 - lds_tile);
-        if (g.gelu_lut_n > 0 && (size_t)g.gelu_lut_n <= room) lds_bytes += ((size_t)g.gelu_lut_n + 255) & ~(size_t)255;
+        // (small tiles have fewer values than the table has entries: they take the arithmetic form)
+        if (DMA && g.gelu_lut_n > 0 && (size_t)g.gelu_lut_n <= room) lds_bytes += ((size_t)g.gelu_lut_n + 255) & ~(size_t)255;
         else g.gelu_lut_n = 0;
     }
 #define IBERT_GEMM_LAUNCH(I8_, KT_)                                                                       \
@@ -1260,6 +1261,8 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
         }
         if (gelu) {
             switch (cfg) {
+                case 3: return launch_mfma<64, 64, 128, 3, false, false, true>(g, i8, stream);
+                case 15: return launch_mfma<32, 32, 128, 4, false, false, true>(g, i8, stream);
                 case 6: if (dma_ok(d, 256, 192)) return launch_mfma<256, 192, 128, 2, false, true, true>(g, i8, stream); break;
                 case 7: if (dma_ok(d, 128, 128)) return launch_mfma<128, 128, 128, 2, false, true, true>(g, i8, stream); break;
                 case 9: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 2, false, true, true>(g, i8, stream); break;

@@ -373,7 +373,9 @@ def test_gemm_small_tiles(G, cfg, M, N, K):
 
 @pytest.mark.parametrize("cfg,M,N,K", [(-1, 4096, 3072, 768), (6, 512, 384, 256), (7, 256, 384, 128), (10, 256, 384, 384),
                                        (13, 512, 384, 256), (13, 256, 576, 640), (14, 512, 256, 384),
-                                       (9, 384, 288, 256), (10, 512, 256, 128), (-1, 100, 72, 48), (-1, 130, 64, 128)])
+                                       (9, 384, 288, 256), (10, 512, 256, 128), (-1, 100, 72, 48), (-1, 130, 64, 128),
+                                       # the small tiles of the few-sequence regime carry it too, ragged edges included
+                                       (3, 200, 136, 256), (15, 100, 72, 640), (15, 32, 32, 128), (-1, 128, 3072, 768)])
 @pytest.mark.parametrize("S_in,S_out", [(2.0 ** -7, 8.0 / 127), (0.011, 0.02)])
 def test_gemm_gelu_equals_matmul_then_gelu(G, cfg, M, N, K, S_in, S_out):
     # steps 7+8 in one call: every tile configuration that carries the GELU epilogue, the built-in choice at the
@@ -396,7 +398,7 @@ def test_gemm_gelu_equals_matmul_then_gelu(G, cfg, M, N, K, S_in, S_out):
     finally:
         B.lib().ibert_gemm_config_override(-1)
     _eq(got, want, "gemm+gelu")
-    one_kernel = M % 128 == 0 and K % 128 == 0
+    one_kernel = K % 128 == 0 and (M % 128 == 0 or cfg in (3, 15))
     assert np.all(scratch == -5) == one_kernel                              # scratch untouched iff GELU ran in the epilogue
     if not one_kernel:
         _eq(scratch, f.reshape(-1), "scratch holds the MatMul result")
