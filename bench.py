@@ -145,7 +145,8 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 256 MiB device copies (reference for the FETCH_SIZE/WRITE_SIZE counters)")
     ap.add_argument("--fusion", type=int, default=-1,
-                    help="fusion mask of the layer (bit 0 GELU, bit 1 attention, bit 2 LayerNorm); default: the library's (7)")
+                    help="fusion mask of the layer (bit 0 GELU, bit 1 attention, bit 2 LayerNorm, bit 3 16-bit LayerNorm inputs); "
+                         "default: the library's (11)")
     ap.add_argument("--latency-grid", action="store_true",
                     help="instead of the headline workload: Base/Large x seq 128/256 x batch 1/2/4/8, integer path vs a PyTorch float encoder")
     args = ap.parse_args()

@@ -38,7 +38,7 @@ enum {
     IBERT_ERR_NOT_IMPLEMENTED = -7
 };
 
-enum { IBERT_I8 = 0, IBERT_I32 = 1 };
+enum { IBERT_I8 = 0, IBERT_I32 = 1, IBERT_I16 = 2 };
 
 /* A real multiplier M represented as m / 2^s.  0 <= s <= 62, m signed. */
 typedef struct { int32_t m; int32_t s; } ibert_dyadic;
@@ -58,7 +58,9 @@ typedef struct { int32_t m; int32_t s; } ibert_dyadic;
  *   v        = DY(acc; mult[n], shift[n])            (per_channel = 1)
  *            = DY(acc; requant.m, requant.s)         (per_channel = 0)
  *   v       += DY(residual[i,n]; residual_dy)        (iff residual != NULL)
- *   C[i,n]   = clamp(v, -out_clamp, +out_clamp)      stored as int8 (IBERT_I8) or int32 (IBERT_I32)
+ *   C[i,n]   = clamp(v, -out_clamp, +out_clamp)      stored as int8 (IBERT_I8), int32 (IBERT_I32) or int16
+ *                                                    (IBERT_I16: the same values as IBERT_I32 in half the bytes, for
+ *                                                    results clamped to 16 bits such as the LayerNorm input)
  *
  * W(n,k) = W[n*ldw + k] when trans_w = 0 (W is [N,K], the layout of a linear layer's weight) and
  * W[k*ldw + n] when trans_w = 1 (W is [K,N], used for probabilities x values).
@@ -71,7 +73,7 @@ typedef struct { int32_t m; int32_t s; } ibert_dyadic;
  * every shift in [0, 62].
  * Preconditions: M, N, K >= 0 (an empty problem is a no-op); K <= 2^17 so that the INT32 accumulator
  * cannot wrap (K * 127^2 + 2^31-ish bias is the caller's responsibility: |bias| + K*16129 < 2^31);
- * out_clamp >= 0, and <= 127 for IBERT_I8.  No alignment is required; 16-byte aligned A/W rows
+ * out_clamp >= 0, and <= 127 for IBERT_I8, <= 32767 for IBERT_I16.  No alignment is required; 16-byte aligned A/W rows
  * (pointers and lda/ldw/batch strides multiples of 16) select the fast MFMA path.
  * Output rows of different (z, i) must not overlap.  C must not alias the inputs.
  * ---------------------------------------------------------------------------------------------- */
@@ -86,7 +88,7 @@ typedef struct {
     int32_t trans_w;
     int32_t per_channel;
     ibert_dyadic requant;        /* used iff per_channel == 0 */
-    int32_t out_dtype;           /* IBERT_I8 | IBERT_I32 */
+    int32_t out_dtype;           /* IBERT_I8 | IBERT_I32 | IBERT_I16 */
     int32_t out_clamp;
     ibert_dyadic residual_dy;    /* used iff residual != NULL */
 } ibert_gemm_desc;
@@ -203,6 +205,10 @@ int ibert_gemm_i8_gelu(const ibert_gemm_desc* desc, const int8_t* A, const int8_
  * ---------------------------------------------------------------------------------------------- */
 int ibert_layernorm_i(const int32_t* x, int8_t* y, int64_t rows, int32_t C, int64_t ldx, int64_t ldy,
                       const int32_t* gamma_q, const int32_t* beta_q, int32_t shift, void* stream);
+/* The same on x: device int16 [rows, ldx] (the first step's clamp makes 16 bits lossless; an IBERT_I16 MatMul output
+ * is such a tensor).  Bit-identical to ibert_layernorm_i on the widened values. */
+int ibert_layernorm_i16(const int16_t* x, int8_t* y, int64_t rows, int32_t C, int64_t ldx, int64_t ldy,
+                        const int32_t* gamma_q, const int32_t* beta_q, int32_t shift, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
  * ibert_embedding_i -- the INT8 embedding that feeds the first layer (Sec. 1, third contribution; App. C.1: the
@@ -397,8 +403,13 @@ int ibert_gemm_i8_layernorm(const ibert_gemm_desc* desc, const int8_t* A, const 
  *          and probs are then left untouched (profile records: one, numbered 2);
  *   bit 2: steps 5+6 and steps 9+10 (projection with residual, then LayerNorm) each run as one kernel where
  *          ibert_gemm_i8_layernorm can do so; the workspace regions r1 / r2 are then left untouched (profile records:
- *          one per pair, numbered 5 / 9).
- * Default: 7.  flags >= 0 sets the mask (unknown bits are dropped), a negative value only queries.  Returns the
+ *          one per pair, numbered 5 / 9);
+ *   bit 3: where steps 5 / 9 run as kernels of their own, r1 / r2 are stored as int16 [T, hidden] (IBERT_I16) at the
+ *          start of their workspace regions instead of int32, and steps 6 / 10 read that (ibert_layernorm_i16): the
+ *          values are clamped to 16 bits anyway, and the two kernels move half the bytes.
+ * Default: 11 (bits 0, 1 and 3: measured, the two-kernel route with 16-bit r1 / r2 is as fast as the one-kernel route of
+ * bit 2 or faster at every size tried; bit 2 takes precedence where both are set and the one-kernel form applies).
+ * flags >= 0 sets the mask (unknown bits are dropped), a negative value only queries.  Returns the
  * previous mask.  Outputs do not depend on the mask.  Not thread-safe. */
 int ibert_set_fusion(int32_t flags);
 

@@ -15,7 +15,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libibert.so")
 
-I8, I32 = 0, 1
+I8, I32, I16 = 0, 1, 2
 OK = 0
 _P = C.c_void_p
 
@@ -114,6 +114,7 @@ SIGNATURES = {
     "ibert_hgelu_i": (C.c_int, [_P, _P, C.c_int64, C.POINTER(HGeluParams), _P]),
     "ibert_hgelu_params_from_scale": (C.c_int, [C.c_double, C.c_double, C.POINTER(HGeluParams)]),
     "ibert_layernorm_i": (C.c_int, [_P, _P, C.c_int64, C.c_int32, C.c_int64, C.c_int64, _P, _P, C.c_int32, _P]),
+    "ibert_layernorm_i16": (C.c_int, [_P, _P, C.c_int64, C.c_int32, C.c_int64, C.c_int64, _P, _P, C.c_int32, _P]),
     "ibert_encoder_layer_workspace_bytes": (C.c_size_t, [C.c_int32] * 5),
     "ibert_encoder_layer_workspace_layout": (C.c_int, [C.c_int32] * 5 + [C.POINTER(WorkspaceLayout)]),
     "ibert_encoder_layer_i": (C.c_int, [C.POINTER(LayerWeights), C.POINTER(LayerQuant), _P, _P] + [C.c_int32] * 5 +
@@ -300,6 +301,11 @@ def ibert_hgelu_i(x, y, n: int, params: HGeluParams, stream=None):
 def ibert_layernorm_i(x, y, rows: int, Cc: int, ldx: int, ldy: int, gamma_q, beta_q, shift: int, stream=None):
     _chk(lib().ibert_layernorm_i(_dp(x), _dp(y), rows, Cc, ldx, ldy, _dp(gamma_q), _dp(beta_q), shift,
                                  _stream(stream)), "ibert_layernorm_i")
+
+
+def ibert_layernorm_i16(x, y, rows: int, Cc: int, ldx: int, ldy: int, gamma_q, beta_q, shift: int, stream=None):
+    _chk(lib().ibert_layernorm_i16(_dp(x), _dp(y), rows, Cc, ldx, ldy, _dp(gamma_q), _dp(beta_q), shift,
+                                   _stream(stream)), "ibert_layernorm_i16")
 
 
 def ibert_encoder_layer_workspace_bytes(batch, seq, hidden, heads, ffn) -> int:

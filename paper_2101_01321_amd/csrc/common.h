@@ -154,6 +154,8 @@ int launch_gelu(const int32_t* x, int8_t* y, int64_t n, const ibert_gelu_params&
 int launch_hgelu(const int32_t* x, int8_t* y, int64_t n, const ibert_hgelu_params& p, hipStream_t stream);
 int launch_layernorm(const int32_t* x, int8_t* y, int64_t rows, int32_t C, int64_t ldx, int64_t ldy,
                      const int32_t* gamma_q, const int32_t* beta_q, int32_t shift, hipStream_t stream);
+int launch_layernorm16(const int16_t* x, int8_t* y, int64_t rows, int32_t C, int64_t ldx, int64_t ldy,
+                       const int32_t* gamma_q, const int32_t* beta_q, int32_t shift, hipStream_t stream);
 int launch_zero_words(uint32_t* p, int64_t words, hipStream_t stream);
 int launch_embedding(const int32_t* ids, const int8_t* tok, const int8_t* pos, int64_t tokens, int32_t seq, int32_t C,
                      int32_t vocab, ibert_dyadic tok_dy, ibert_dyadic pos_dy, const int32_t* gamma_q,

@@ -46,6 +46,7 @@ struct GemmArgs {
     int32_t c_vec;     // output rows allow one vector store per lane (4 bytes INT8, 16 bytes INT32)
     int32_t r_vec;     // residual rows allow 16-byte loads
     int32_t c_vec16;   // INT8 output rows allow 16-byte stores
+    int32_t c16;       // the INT32 kernels store 16-bit elements (IBERT_I16: |value| <= out_clamp <= 32767)
     int32_t res_fast;  // residual absent, or its shift is in [8, 62]: its requantized value fits 32 bits
     int64_t res_rnd;   // 2^(res_s - 1), or 0 when res_s == 0
     int32_t xcd_chunk; // tiles per XCD when the grid divides by 8, else 0 (no remap)
@@ -618,8 +619,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
         }
     };
     // Output pointer of the lane's channel group in tile row 0; row offsets inside a tile fit 32 bits.
-    char* const c_lane = reinterpret_cast<char*>(g.C) + (c_off + (int64_t)m0 * g.ldc + n) * (OUT_I8 ? 1 : 4);
-    const uint32_t c_pitch = (uint32_t)g.ldc * (OUT_I8 ? 1u : 4u);
+    const uint32_t esz = OUT_I8 ? 1u : (g.c16 ? 2u : 4u);          // bytes per output element
+    char* const c_lane = reinterpret_cast<char*>(g.C) + (c_off + (int64_t)m0 * g.ldc + n) * (int64_t)esz;
+    const uint32_t c_pitch = (uint32_t)g.ldc * esz;
+    auto pack2_i16 = [](int32_t a, int32_t b) { return ((uint32_t)a & 0xffffu) | ((uint32_t)b << 16); };
     auto finish_interior = [&](int jc0, auto fast_tag) {
         if (tid >= RPS * G4) return;
         constexpr int U = 4;                                       // rows in flight: LDS reads first, then math and stores
@@ -646,6 +649,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
                     requant4(a4[u], res, R != nullptr, fast_tag, o);
                     char* cp = c_lane + (uint32_t)tr[u] * c_pitch;
                     if (OUT_I8) *reinterpret_cast<uint32_t*>(cp) = pack4_i8(o[0], o[1], o[2], o[3]);
+                    else if (g.c16) *reinterpret_cast<uint2*>(cp) = uint2{pack2_i16(o[0], o[1]), pack2_i16(o[2], o[3])};
                     else *reinterpret_cast<v4i*>(cp) = v4i{o[0], o[1], o[2], o[3]};
                 }
             }
@@ -671,6 +675,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
             for (int e = 0; e < 4; ++e) {
                 if (n + e < g.N) {
                     if (OUT_I8) (reinterpret_cast<int8_t*>(g.C) + off)[e] = (int8_t)o[e];
+                    else if (g.c16) (reinterpret_cast<int16_t*>(g.C) + off)[e] = (int16_t)o[e];
                     else (reinterpret_cast<int32_t*>(g.C) + off)[e] = o[e];
                 }
             }
@@ -694,7 +699,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
         const bool use_ost = OST && g.c_vec16;
         int8_t* const ostage = lds;
         char* const c_base = reinterpret_cast<char*>(g.C) +
-                             (c_off + (int64_t)(m0 + wm0 + frow) * g.ldc + n0 + wn0 + 4 * fch) * (OUT_I8 ? 1 : 4);
+                             (c_off + (int64_t)(m0 + wm0 + frow) * g.ldc + n0 + wn0 + 4 * fch) * (int64_t)esz;
         const uint32_t* const r_base = resl + (wm0 + frow) * G4 + (wn0 >> 2) + fch;
 #pragma clang loop unroll(full)
         for (int i = 0; i < FN; ++i) {
@@ -726,11 +731,13 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
                     if (LUT) o[e] = lut[med3_i32(v - g.gelu_lut_lo, 0, lut_hi)];
                     else o[e] = GF ? post_fast(v) : post(v);
                 }
-                char* cp = c_base + ((uint32_t)(j * 16) * c_pitch + (uint32_t)(i * 16 * (OUT_I8 ? 1 : 4)));
+                char* cp = c_base + ((uint32_t)(j * 16) * c_pitch + (uint32_t)(i * 16) * esz);
                 if (OUT_I8) {
                     const uint32_t pk4 = pack4_i8(o[0], o[1], o[2], o[3]);
                     if (use_ost) *reinterpret_cast<uint32_t*>(ostage + (wm0 + 16 * j + frow) * SPB + wn0 + 16 * i + 4 * fch) = pk4;
                     else *reinterpret_cast<uint32_t*>(cp) = pk4;
+                } else if (g.c16) {
+                    *reinterpret_cast<uint2*>(cp) = uint2{pack2_i16(o[0], o[1]), pack2_i16(o[2], o[3])};
                 } else {
                     *reinterpret_cast<v4i*>(cp) = v4i{o[0], o[1], o[2], o[3]};
                 }
@@ -967,6 +974,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_generic_kernel(GemmArgs g)
     const int32_t o = finish(acc, m, s, g.R != nullptr, res, g);
     const int64_t off = zo * g.sC_o + zi * g.sC_i + (int64_t)i * g.ldc + n;
     if (OUT_I8) reinterpret_cast<int8_t*>(g.C)[off] = (int8_t)o;
+    else if (g.c16) reinterpret_cast<int16_t*>(g.C)[off] = (int16_t)o;
     else reinterpret_cast<int32_t*>(g.C)[off] = o;
 }
 
@@ -977,8 +985,9 @@ int check_gemm(const ibert_gemm_desc& d, const void* A, const void* W, const voi
     (void)residual;
     if (d.M < 0 || d.N < 0 || d.K < 0 || d.batch_outer < 0 || d.batch_inner < 0) return IBERT_ERR_SHAPE;
     if (d.K > (1 << 17)) return IBERT_ERR_SHAPE;
-    if (d.out_dtype != IBERT_I8 && d.out_dtype != IBERT_I32) return IBERT_ERR_PARAM_RANGE;
+    if (d.out_dtype != IBERT_I8 && d.out_dtype != IBERT_I32 && d.out_dtype != IBERT_I16) return IBERT_ERR_PARAM_RANGE;
     if (d.out_clamp < 0 || (d.out_dtype == IBERT_I8 && d.out_clamp > 127)) return IBERT_ERR_PARAM_RANGE;
+    if (d.out_dtype == IBERT_I16 && d.out_clamp > 32767) return IBERT_ERR_PARAM_RANGE;
     if (d.trans_w != 0 && d.trans_w != 1) return IBERT_ERR_PARAM_RANGE;
     if (!d.per_channel && !dyadic_ok(d.requant)) return IBERT_ERR_PARAM_RANGE;
     if (residual && !dyadic_ok(d.residual_dy)) return IBERT_ERR_PARAM_RANGE;
@@ -1208,6 +1217,7 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
     g.res_fast = (!residual || (d.residual_dy.s >= 8 && d.residual_dy.s <= 62)) ? 1 : 0;
     g.res_rnd = (residual && d.residual_dy.s >= 1 && d.residual_dy.s <= 62) ? ((int64_t)1 << (d.residual_dy.s - 1)) : 0;
     const bool i8 = d.out_dtype == IBERT_I8;
+    g.c16 = d.out_dtype == IBERT_I16 ? 1 : 0;
     g.gelu_fast = 0;
     g.gelu = GeluConst{0, 0, 0, 0, 0, 0};
     g.gelu_lut_lo = g.gelu_lut_n = 0;
@@ -1230,7 +1240,7 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
         g.ln_sum = ln->sum; g.ln_sq = ln->sq; g.ln_status = ln->status;
         g.ln_shift = ln->shift; g.ln_magic = ln_magic_for(d.N);
     }
-    g.c_vec = ln ? 1 : aligned(C, i8 ? 4 : 16) && d.ldc % 4 == 0 && d.strideC_outer % 4 == 0 && d.strideC_inner % 4 == 0;
+    g.c_vec = ln ? 1 : aligned(C, i8 ? 4 : (g.c16 ? 8 : 16)) && d.ldc % 4 == 0 && d.strideC_outer % 4 == 0 && d.strideC_inner % 4 == 0;
     g.c_vec16 = i8 && aligned(C, 16) && d.ldc % 16 == 0 && d.strideC_outer % 16 == 0 && d.strideC_inner % 16 == 0;
     g.r_vec = residual && aligned(residual, 16) && d.ldr % 16 == 0 && d.strideR_outer % 16 == 0 && d.strideR_inner % 16 == 0;
 

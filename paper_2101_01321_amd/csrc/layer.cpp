@@ -46,7 +46,7 @@ static double gemm_bytes(double M, double N, double K, double batch, double out_
 // Fusions the layer applies (bit 0: GELU inside the FFN up-projection; bit 1: scores, Softmax and context in one
 // kernel; bit 2: LayerNorm inside the output projection and inside the FFN down-projection).  Results do not depend
 // on it.
-static int32_t g_fusion = 7;
+static int32_t g_fusion = 11;
 
 // Row statistics of the LayerNorm epilogue for `rows` tokens: two 64-bit words a row (sum, sum of squares, each with
 // its count of contributions), the sums of squares first; `words` 32-bit words in all.
@@ -209,6 +209,8 @@ static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, c
             }                                                                                                \
         }                                                                                                    \
         if (!fused_ln) {                                                                                     \
+            const bool half = (g_fusion & 8) != 0;           /* r as int16: half the bytes both ways */      \
+            if (half) d.out_dtype = IBERT_I16;                                                               \
             prof_before(stream);                                                                             \
             rc = launch_gemm(d, A_, W_, b_, m_, s_, R_, R32_, stream, nullptr, nullptr, ZERO_);              \
             if (rc == IBERT_ERR_NOT_IMPLEMENTED && (ZERO_) != nullptr) {                                     \
@@ -216,11 +218,15 @@ static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, c
                 rc = launch_gemm(d, A_, W_, b_, m_, s_, R_, R32_, stream);                                   \
             }                                                                                                \
             if (rc) return rc;                                                                               \
-            prof_after(stream, STEP_, OPS_, gemm_bytes(T, H, K_, 1, 4, true, true));                         \
+            prof_after(stream, STEP_, OPS_, gemm_bytes(T, H, K_, 1, half ? 2 : 4, true, true));              \
             prof_before(stream);                                                                             \
-            rc = launch_layernorm(R32_, OUT_, T, (int32_t)H, H, H, GQ_, BQ_, SH_, stream);                   \
+            if (half)                                                                                        \
+                rc = launch_layernorm16(reinterpret_cast<const int16_t*>(R32_), OUT_, T, (int32_t)H, H, H,   \
+                                        GQ_, BQ_, SH_, stream);                                              \
+            else                                                                                             \
+                rc = launch_layernorm(R32_, OUT_, T, (int32_t)H, H, H, GQ_, BQ_, SH_, stream);               \
             if (rc) return rc;                                                                               \
-            prof_after(stream, (STEP_) + 1, 0.0, 5.0 * T * H);                                               \
+            prof_after(stream, (STEP_) + 1, 0.0, (half ? 3.0 : 5.0) * T * H);                                \
         }                                                                                                    \
     } while (0)
 
@@ -329,7 +335,7 @@ extern "C" {
 int ibert_set_fusion(int32_t flags)
 {
     const int32_t old = ibert::g_fusion;
-    if (flags >= 0) ibert::g_fusion = flags & 7;
+    if (flags >= 0) ibert::g_fusion = flags & 15;
     return old;
 }
 

@@ -22,7 +22,7 @@ struct EmbedArgs {
 };
 
 struct LayerNormArgs {
-    const int32_t* x;
+    const int32_t* x;    // rows of int32, or of int16 (X16 instantiations: same values in half the bytes)
     int8_t* y;
     int64_t rows;
     int32_t C;
@@ -44,7 +44,7 @@ __device__ __forceinline__ int32_t group_sum_i32(int32_t v)
 template <int LPR>
 __device__ __forceinline__ uint64_t group_sum_u64(uint64_t v)
 {
-    // every lane value is below 2^34 here (at most 16 squares below 2^30); split at bit 19 so that both parts,
+    // every lane value is below 2^35 here (at most 32 squares below 2^30); split at bit 19 so that both parts,
     // summed over 64 lanes, stay below 2^25 and plain 32-bit all-reduces are exact
     const int32_t l0 = (int32_t)(v & 0x7ffff), l1 = (int32_t)(v >> 19);
     const uint64_t s0 = (uint32_t)group_sum_i32<LPR>(l0), s1 = (uint32_t)group_sum_i32<LPR>(l1);
@@ -57,16 +57,22 @@ constexpr int LN_THREADS = 256;
 // chunk is either entirely inside the row or entirely outside, and moves as one vector.
 // EMB: the row is DY(tok[id]) + DY(pos[row mod seq]) instead of x[row] (ALIGNED then means 4-byte aligned table rows).
 // FULL: C == NCH * LPR * 4 (and ALIGNED), so no chunk lies outside the row and the column masks fold away.
-template <int LPR, int NCH, bool ALIGNED, bool EMB = false, bool FULL = false>
+// X16: the row is int16 (8-byte aligned rows when ALIGNED).
+// WIDE (X16, ALIGNED, NCH even, C % 8 == 0, 16-byte aligned x rows, 8-byte aligned y rows): a lane's chunks 2k and 2k+1
+// are neighbours, eight columns that come in with one 16-byte load and leave with one 8-byte store.
+template <int LPR, int NCH, bool ALIGNED, bool EMB = false, bool FULL = false, bool X16 = false, bool WIDE = false>
 __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArgs a)
 {
     constexpr int ROWS_PER_BLOCK = LN_THREADS / LPR;
-    static_assert(NCH * 4 <= 16, "a lane's sum of squares must stay below 2^34");
+    static_assert(NCH * 4 <= 32, "a lane's sum of squares must stay below 2^35");
+    static_assert(!WIDE || (X16 && ALIGNED && NCH % 2 == 0), "wide chunks: pairs of int16 chunks");
     const int lane = threadIdx.x % LPR;
+    auto col_of = [&](int c) { return WIDE ? ((c >> 1) * LPR + lane) * 8 + (c & 1) * 4 : (c * LPR + lane) * 4; };
     const int64_t row = (int64_t)blockIdx.x * ROWS_PER_BLOCK + threadIdx.x / LPR;
     const bool live = row < a.rows;
     const int32_t C = a.C;
-    const int32_t* xr = EMB ? nullptr : a.x + (live ? row : 0) * a.ldx;
+    const int32_t* xr = (EMB || X16) ? nullptr : a.x + (live ? row : 0) * a.ldx;
+    const int16_t* xh = X16 ? reinterpret_cast<const int16_t*>(a.x) + (live ? row : 0) * a.ldx : nullptr;
     const int8_t *tr = nullptr, *pr = nullptr;
     if (EMB) {
         const int64_t r0 = live ? row : 0;
@@ -80,7 +86,7 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
     int32_t v[NCH][4], gm[NCH][4], bt[NCH][4];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-        const int col = (c * LPR + lane) * 4;
+        const int col = col_of(c);
         if (EMB) {
             int32_t tv[4], pv[4];
             if (ALIGNED) {
@@ -105,18 +111,30 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
                 v[c][e] = clamp_i64_to_i32(dyadic64(tv[e], a.emb.tok_m, a.emb.tok_s) + dyadic64(pv[e], a.emb.pos_m, a.emb.pos_s), 32767);
         } else if (ALIGNED) {
             const int cc = (FULL || col < C) ? col : 0; // out-of-row chunks re-read chunk 0 and are masked below
-            const int4 t = *reinterpret_cast<const int4*>(xr + cc);
-            v[c][0] = t.x; v[c][1] = t.y; v[c][2] = t.z; v[c][3] = t.w;
+            if (WIDE) {
+                if ((c & 1) == 0) {
+                    const int4 t = *reinterpret_cast<const int4*>(xh + cc);
+                    v[c][0] = (int16_t)(t.x & 0xffff); v[c][1] = t.x >> 16; v[c][2] = (int16_t)(t.y & 0xffff); v[c][3] = t.y >> 16;
+                    v[c + (NCH > 1 ? 1 : 0)][0] = (int16_t)(t.z & 0xffff); v[c + (NCH > 1 ? 1 : 0)][1] = t.z >> 16;
+                    v[c + (NCH > 1 ? 1 : 0)][2] = (int16_t)(t.w & 0xffff); v[c + (NCH > 1 ? 1 : 0)][3] = t.w >> 16;
+                }
+            } else if (X16) {
+                const int2 t = *reinterpret_cast<const int2*>(xh + cc);
+                v[c][0] = (int16_t)(t.x & 0xffff); v[c][1] = t.x >> 16; v[c][2] = (int16_t)(t.y & 0xffff); v[c][3] = t.y >> 16;
+            } else {
+                const int4 t = *reinterpret_cast<const int4*>(xr + cc);
+                v[c][0] = t.x; v[c][1] = t.y; v[c][2] = t.z; v[c][3] = t.w;
+            }
         } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[c][e] = (live && col + e < C) ? xr[col + e] : 0;
+            for (int e = 0; e < 4; ++e) v[c][e] = (live && col + e < C) ? (X16 ? (int32_t)xh[col + e] : xr[col + e]) : 0;
         }
     }
     // gamma and beta after the row itself, so that the row is the first thing in flight; every wavefront of a
     // compute unit reads the same few KB, which the vector cache serves after the first
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-        const int col = (c * LPR + lane) * 4;
+        const int col = col_of(c);
         if (ALIGNED) {
             const int cc = (FULL || col < C) ? col : 0;
             const int4 g4 = *reinterpret_cast<const int4*>(a.gamma_q + cc);
@@ -138,7 +156,7 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
     uint64_t sq = 0;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-        const int col = (c * LPR + lane) * 4;
+        const int col = col_of(c);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int32_t keep = (FULL || (ALIGNED ? col < C : col + e < C)) ? -1 : 0;
@@ -164,9 +182,10 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
     const bool f24 = __builtin_amdgcn_ballot_w64(f >= (1 << 23)) == 0;
 
     int8_t* yr = a.y + row * a.ldy;
+    uint32_t even_pack = 0;                                    // WIDE: the packed bytes of the pair's first chunk
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-        const int col = (c * LPR + lane) * 4;
+        const int col = col_of(c);
         if (!FULL && col >= C) continue;
         int32_t o[4];
 #pragma unroll
@@ -176,7 +195,11 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
             const int32_t acc = smad24(n, gm[c][e], bt[c][e]);                     // |gamma_q| < 2^14: 24-bit multiply
             o[e] = med3_i32(acc >> a.shift, -127, 127);
         }
-        if (ALIGNED) {
+        if (WIDE) {
+            const uint32_t pk = pack4_perm(o[0], o[1], o[2], o[3]);
+            if ((c & 1) == 0) even_pack = pk;
+            else *reinterpret_cast<uint2*>(yr + col - 4) = uint2{even_pack, pk};
+        } else if (ALIGNED) {
             *reinterpret_cast<uint32_t*>(yr + col) = pack4_perm(o[0], o[1], o[2], o[3]);
         } else {
 #pragma unroll
@@ -209,30 +232,46 @@ int check_layernorm(int32_t C, int32_t shift)
 }
 
 template <int LPR, int NCH>
-static void launch_rows(const LayerNormArgs& a, bool al, hipStream_t stream)
+static void launch_rows(const LayerNormArgs& a, bool al, bool x16, bool wide, hipStream_t stream)
 {
     constexpr int rpb = LN_THREADS / LPR;
-    const unsigned blocks = (unsigned)((a.rows + rpb - 1) / rpb);
+    const dim3 grid((unsigned)((a.rows + rpb - 1) / rpb)), block(LN_THREADS);
     const bool full = al && a.C == NCH * LPR * 4;
+#define IBERT_LN_LAUNCH(...) hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, __VA_ARGS__>), grid, block, 0, stream, a)
     if (a.emb.ids) {
-        if (full) hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, true, true, true>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
-        else if (al) hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, true, true>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
-        else hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, false, true>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
-    } else if (full) hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, true, false, true>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
-    else if (al) hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, true>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
-    else hipLaunchKernelGGL((layernorm_rows_kernel<LPR, NCH, false>), dim3(blocks), dim3(LN_THREADS), 0, stream, a);
+        if (full) IBERT_LN_LAUNCH(true, true, true);
+        else if (al) IBERT_LN_LAUNCH(true, true);
+        else IBERT_LN_LAUNCH(false, true);
+    } else if (x16) {
+        if constexpr (NCH % 2 == 0) {
+            if (wide && full) { IBERT_LN_LAUNCH(true, false, true, true, true); return; }
+            if (wide) { IBERT_LN_LAUNCH(true, false, false, true, true); return; }
+        }
+        if (full) IBERT_LN_LAUNCH(true, false, true, true);
+        else if (al) IBERT_LN_LAUNCH(true, false, false, true);
+        else IBERT_LN_LAUNCH(false, false, false, true);
+    } else if (full) IBERT_LN_LAUNCH(true, false, true);
+    else if (al) IBERT_LN_LAUNCH(true);
+    else IBERT_LN_LAUNCH(false);
+#undef IBERT_LN_LAUNCH
 }
 
-static int dispatch_rows(const LayerNormArgs& a, bool al, hipStream_t stream)
+static int dispatch_rows(const LayerNormArgs& a, bool al, bool x16, bool wide, hipStream_t stream)
 {
     const int32_t C = a.C;
     // One wavefront per row (two rows for short ones): the per-row scalar work (mean, variance, square root,
     // reciprocal) is repeated by every lane of a row, but few registers per lane let many rows be in flight on a
     // compute unit, which is what hides the memory latency; shorter groups measured slower at every size.
-    if (C <= 256) launch_rows<32, 2>(a, al, stream);
-    else if (C <= 512) launch_rows<64, 2>(a, al, stream);
-    else if (C <= 768) launch_rows<64, 3>(a, al, stream);
-    else launch_rows<64, 4>(a, al, stream);
+    // int16 rows with wide chunks: the same bytes per lane (two rows per wavefront up to 768 columns).
+    if (x16 && wide) {
+        if (C <= 256) launch_rows<32, 2>(a, al, x16, true, stream);
+        else if (C <= 512) launch_rows<64, 2>(a, al, x16, true, stream);
+        else if (C <= 768) launch_rows<32, 6>(a, al, x16, true, stream);
+        else launch_rows<64, 4>(a, al, x16, true, stream);
+    } else if (C <= 256) launch_rows<32, 2>(a, al, x16, false, stream);
+    else if (C <= 512) launch_rows<64, 2>(a, al, x16, false, stream);
+    else if (C <= 768) launch_rows<64, 3>(a, al, x16, false, stream);
+    else launch_rows<64, 4>(a, al, x16, false, stream);
     IBERT_LAUNCH_CHECK("layernorm kernel");
     g_last_kernel = a.emb.ids ? "layernorm_rows_kernel<embedding>" : "layernorm_rows_kernel";
     return IBERT_OK;
@@ -246,7 +285,21 @@ int launch_layernorm(const int32_t* x, int8_t* y, int64_t rows, int32_t C, int64
     LayerNormArgs a{x, y, rows, C, ldx, ldy, gamma_q, beta_q, shift, ln_magic_for(C), EmbedArgs{}};
     const bool al = aligned(x, 16) && ldx % 4 == 0 && aligned(y, 4) && ldy % 4 == 0 && C % 4 == 0 &&
                     aligned(gamma_q, 16) && aligned(beta_q, 16);
-    return dispatch_rows(a, al, stream);
+    return dispatch_rows(a, al, false, false, stream);
+}
+
+// The same on int16 rows (the 16-bit form the MatMul can store its clamped LayerNorm input in).
+int launch_layernorm16(const int16_t* x, int8_t* y, int64_t rows, int32_t C, int64_t ldx, int64_t ldy,
+                       const int32_t* gamma_q, const int32_t* beta_q, int32_t shift, hipStream_t stream)
+{
+    if (rows == 0) return IBERT_OK;
+    if (rows > 0x7fffffffLL) return IBERT_ERR_SHAPE;
+    LayerNormArgs a{reinterpret_cast<const int32_t*>(x), y, rows, C, ldx, ldy, gamma_q, beta_q, shift, ln_magic_for(C), EmbedArgs{}};
+    const bool al = aligned(x, 8) && ldx % 4 == 0 && aligned(y, 4) && ldy % 4 == 0 && C % 4 == 0 &&
+                    aligned(gamma_q, 16) && aligned(beta_q, 16);
+    // (wide chunks pay from about 8192 rows on: [32768,768] 19.3 -> 17.2 us; a few hundred rows lose half a microsecond)
+    const bool wide = rows >= 8192 && al && aligned(x, 16) && ldx % 8 == 0 && aligned(y, 8) && ldy % 8 == 0 && C % 8 == 0;
+    return dispatch_rows(a, al, true, wide, stream);
 }
 
 int launch_embedding(const int32_t* ids, const int8_t* tok, const int8_t* pos, int64_t tokens, int32_t seq, int32_t C,
@@ -259,7 +312,7 @@ int launch_embedding(const int32_t* ids, const int8_t* tok, const int8_t* pos, i
                     EmbedArgs{ids, tok, pos, seq, vocab, tok_dy.m, tok_dy.s, pos_dy.m, pos_dy.s}};
     const bool al = aligned(tok, 4) && aligned(pos, 4) && aligned(y, 4) && ldy % 4 == 0 && C % 4 == 0 &&
                     aligned(gamma_q, 16) && aligned(beta_q, 16);
-    return dispatch_rows(a, al, stream);
+    return dispatch_rows(a, al, false, false, stream);
 }
 
 }  // namespace ibert
@@ -273,6 +326,17 @@ extern "C" int ibert_layernorm_i(const int32_t* x, int8_t* y, int64_t rows, int3
     if (rows == 0) return IBERT_OK;
     if (!x || !y || !gamma_q || !beta_q) return IBERT_ERR_NULL;
     return ibert::launch_layernorm(x, y, rows, C, ldx, ldy, gamma_q, beta_q, shift, (hipStream_t)stream);
+}
+
+extern "C" int ibert_layernorm_i16(const int16_t* x, int8_t* y, int64_t rows, int32_t C, int64_t ldx, int64_t ldy,
+                                   const int32_t* gamma_q, const int32_t* beta_q, int32_t shift, void* stream)
+{
+    if (rows < 0 || C < 1 || ldx < C || ldy < C) return IBERT_ERR_SHAPE;
+    const int rc = ibert::check_layernorm(C, shift);
+    if (rc) return rc;
+    if (rows == 0) return IBERT_OK;
+    if (!x || !y || !gamma_q || !beta_q) return IBERT_ERR_NULL;
+    return ibert::launch_layernorm16(x, y, rows, C, ldx, ldy, gamma_q, beta_q, shift, (hipStream_t)stream);
 }
 
 extern "C" int ibert_embedding_i(const int32_t* ids, const int8_t* tok, const int8_t* pos, int64_t tokens, int32_t seq,

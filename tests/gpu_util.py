@@ -36,7 +36,8 @@ def gemm(desc_kwargs, A, W, bias=None, mult=None, shift=None, residual=None, out
     ts = None if shift is None else to_dev(shift, np.int32)
     tR = None if residual is None else to_dev(residual, np.int8).reshape(-1)
     sentinel = 77
-    tC = torch.full((out_elems + offsets.get("C", 0),), sentinel, dtype=torch.int8 if i8 else torch.int32, device=DEV)
+    out_t = torch.int8 if i8 else (torch.int16 if d.out_dtype == B.I16 else torch.int32)
+    tC = torch.full((out_elems + offsets.get("C", 0),), sentinel, dtype=out_t, device=DEV)
 
     def off(t, key):
         return None if t is None else t[offsets.get(key, 0):]
@@ -153,15 +154,17 @@ def hgelu(x, params, x_off=0, y_off=0):
     return out[y_off:y_off + x.size]
 
 
-def layernorm(x, gamma_q, beta_q, shift, ldx=None, ldy=None, x_off=0, y_off=0):
-    x = np.ascontiguousarray(x, np.int32)
+def layernorm(x, gamma_q, beta_q, shift, ldx=None, ldy=None, x_off=0, y_off=0, half=False):
+    """ibert_layernorm_i, or ibert_layernorm_i16 on the same values stored as int16 (half=True)."""
+    x = np.ascontiguousarray(x, np.int16 if half else np.int32)
     rows, Cc = x.shape
     ldx = Cc if ldx is None else ldx
     ldy = ldx if ldy is None else ldy
-    tx = torch.zeros(rows * ldx + x_off, dtype=torch.int32, device=DEV)
+    tx = torch.zeros(rows * ldx + x_off, dtype=torch.int16 if half else torch.int32, device=DEV)
     tx[x_off:].view(rows, ldx)[:, :Cc] = to_dev(x)
     ty = torch.full((rows * ldy + y_off,), 77, dtype=torch.int8, device=DEV)
-    B.ibert_layernorm_i(tx[x_off:], ty[y_off:], rows, Cc, ldx, ldy, to_dev(gamma_q, np.int32), to_dev(beta_q, np.int32), shift)
+    call = B.ibert_layernorm_i16 if half else B.ibert_layernorm_i
+    call(tx[x_off:], ty[y_off:], rows, Cc, ldx, ldy, to_dev(gamma_q, np.int32), to_dev(beta_q, np.int32), shift)
     torch.cuda.synchronize()
     return ty[y_off:].view(rows, ldy).cpu().numpy()
 
@@ -236,7 +239,8 @@ class DeviceModel:
         off = getattr(self.layout, name)
         return not bool(torch.all(self.ws[off:off + 16] == 0x7B).item())
 
-    def intermediates(self) -> dict:
+    def intermediates(self, r_half: bool = False) -> dict:
+        """r_half: r1 / r2 were stored as int16 (fusion bit 3); they are returned widened."""
         c, lo = self.cfg, self.layout
         T, H, F, BH, L = c.tokens, c.hidden, c.ffn, c.batch * c.heads, c.seq
         spec = {"qkv": (lo.qkv, (T, 3 * H), torch.int8), "scores": (lo.scores, (BH, L, L), torch.int32),
@@ -245,6 +249,10 @@ class DeviceModel:
                 "f1": (lo.f1, (T, F), torch.int32), "g": (lo.g, (T, F), torch.int8), "r2": (lo.r2, (T, H), torch.int32)}
         out = {}
         for k, (off, shape, dt) in spec.items():
+            if r_half and k in ("r1", "r2"):
+                n = int(np.prod(shape)) * 2
+                out[k] = self.ws[off:off + n].view(torch.int16).view(*shape).cpu().numpy().astype(np.int32)
+                continue
             n = int(np.prod(shape)) * (4 if dt == torch.int32 else 1)
             out[k] = self.ws[off:off + n].view(dt).view(*shape).cpu().numpy()
         return out

@@ -13,6 +13,8 @@ pytestmark = pytest.mark.gpu
 
 import oracle
 from oracle import params as P, GemmSpec, I8, I32
+
+I16 = 2     # the library's 16-bit MatMul output type (same values as I32)
 from paper_2101_01321_amd import synth
 
 
@@ -30,6 +32,16 @@ def _eq(got, want, what):
         first = tuple(bad[0])
         raise AssertionError("%s: %d of %d differ; first at %s: got %s want %s" % (
             what, len(bad), np.asarray(want).size, first, np.asarray(got)[first], np.asarray(want)[first]))
+
+
+@pytest.fixture(autouse=True)
+def _every_kernel_fusion_on():
+    # the cases below were written against "all three kernel fusions on" (mask 7) and say so where they look at which
+    # kernels ran; the library's own default (mask 11) is one of the masks the layer tests go through
+    from paper_2101_01321_amd import binding as B
+    old = B.ibert_set_fusion(7)
+    yield
+    B.ibert_set_fusion(old)
 
 
 # ------------------------------------------------------------------------------------------- GELU
@@ -161,6 +173,15 @@ def test_layernorm_matches_oracle(G, C, rows):
     gq, bq, s = B.ibert_layernorm_params_from_float(gamma, beta, 5.0 / 127)
     G.say("layernorm C=%d rows=%d" % (C, rows))
     _eq(G.layernorm(x, gq, bq, s), oracle.layernorm(x, gq, bq, s), "layernorm C=%d rows=%d" % (C, rows))
+    # the same rows stored as int16 (clamped first: that is all 16 bits can hold, and what the kernel's own clamp makes of them)
+    xc = np.clip(x, -32767, 32767)
+    G.say("layernorm int16 C=%d rows=%d" % (C, rows))
+    _eq(G.layernorm(xc, gq, bq, s, half=True), oracle.layernorm(x, gq, bq, s), "layernorm int16 C=%d rows=%d" % (C, rows))
+    if C in (3, 257, 1000):
+        G.say("layernorm int16 C=%d rows=%d unaligned" % (C, rows))
+        got = G.layernorm(xc, gq, bq, s, ldx=C + 1, ldy=C + 3, x_off=3, y_off=1, half=True)
+        _eq(got[:, :C], oracle.layernorm(x, gq, bq, s), "layernorm int16 unaligned")
+        assert np.all(got[:, C:] == 77)
     if C in (3, 257, 1000):
         G.say("layernorm C=%d rows=%d unaligned" % (C, rows))
         got = G.layernorm(x, gq, bq, s, ldx=C + 1, ldy=C + 3, x_off=3, y_off=1)
@@ -174,6 +195,19 @@ def test_layernorm_full_shape_and_small_sigma(G):
     gq, bq, s = B.ibert_layernorm_params_from_float(gamma, beta, 5.0 / 127)
     G.say("layernorm full [4096,768]")
     _eq(G.layernorm(x, gq, bq, s), oracle.layernorm(x, gq, bq, s), "layernorm full")
+    _eq(G.layernorm(np.clip(x, -32767, 32767), gq, bq, s, half=True), oracle.layernorm(x, gq, bq, s), "layernorm full, int16 rows")
+    # int16 rows, many of them: the wide-chunk form of the kernel (whole rows, and rows that end inside a lane's reach)
+    for rows, C in ((8200, 768), (8197, 1024), (9000, 512), (8300, 256), (8200, 640), (8192, 1000), (8200, 8)):
+        x, S, gamma, beta = synth.layernorm_inputs(rows, C, seed=rows + C)
+        x[::5] *= 40                                                     # rows that saturate the 16-bit clamp
+        xc = np.clip(x, -32767, 32767)
+        gq2, bq2, s2 = B.ibert_layernorm_params_from_float(gamma, beta, 5.0 / 127)
+        G.say("layernorm int16 [%d,%d]" % (rows, C))
+        _eq(G.layernorm(xc, gq2, bq2, s2, half=True), oracle.layernorm(x, gq2, bq2, s2), "layernorm int16 [%d,%d]" % (rows, C))
+        G.say("layernorm int16 [%d,%d], padded rows" % (rows, C))
+        got = G.layernorm(xc, gq2, bq2, s2, ldx=C + 8, ldy=C + 16, half=True)
+        _eq(got[:, :C], oracle.layernorm(x, gq2, bq2, s2), "layernorm int16 padded [%d,%d]" % (rows, C))
+        assert np.all(got[:, C:] == 77)
     rng = np.random.default_rng(5)
     x = rng.integers(-3, 4, size=(3000, 768)).astype(np.int32)       # tiny variances: sqrt of small numbers
     x[::7] *= 9000
@@ -194,16 +228,21 @@ def _gemm_case(G, M, N, K, out_dtype, per_channel, bias, residual, seed, clamp=N
               requant=dy, out_dtype=out_dtype, out_clamp=clamp, residual_dy=res_dy)
     got = G.gemm(kw, A, W, b if bias else None, mult if per_channel else None, shift if per_channel else None, R,
                  out_elems=M * N)
-    spec = GemmSpec(M, N, K, per_channel=per_channel, dy=dy, out_dtype=out_dtype, out_clamp=clamp, res_dy=res_dy)
+    # (the 16-bit output holds the values of the 32-bit one: the oracle has no type of its own for it)
+    spec = GemmSpec(M, N, K, per_channel=per_channel, dy=dy, out_dtype=I32 if out_dtype == I16 else out_dtype,
+                    out_clamp=clamp, res_dy=res_dy)
     want = oracle.gemm_requant(spec, A, W, b if bias else None, mult if per_channel else None,
                                shift if per_channel else None, R)
+    if out_dtype == I16:
+        assert got.dtype == np.int16 and np.abs(want).max() > 300       # not a case that would fit 8 bits
     _eq(got, want, "gemm %dx%dx%d" % (M, N, K))
 
 
 @pytest.mark.parametrize("M,N,K", [(128, 128, 64), (128, 128, 128), (256, 384, 192), (200, 136, 80), (1, 16, 16),
                                    (77, 50, 48), (130, 250, 1024), (64, 64, 32), (300, 48, 160), (5, 5, 16)])
 def test_gemm_mfma_path_matches_oracle(G, M, N, K):
-    for out_dtype, pc, bias, res in [(I8, 1, True, False), (I32, 1, True, True), (I32, 0, False, False), (I8, 0, True, True)]:
+    for out_dtype, pc, bias, res in [(I8, 1, True, False), (I32, 1, True, True), (I32, 0, False, False), (I8, 0, True, True),
+                                     (I16, 1, True, True)]:
         G.say("gemm M=%d N=%d K=%d out=%d pc=%d bias=%d res=%d" % (M, N, K, out_dtype, pc, bias, res))
         _gemm_case(G, M, N, K, out_dtype, pc, bias, res, seed=M + N + K)
 
@@ -211,7 +250,7 @@ def test_gemm_mfma_path_matches_oracle(G, M, N, K):
 @pytest.mark.parametrize("M,N,K", [(33, 21, 70), (64, 64, 17), (9, 130, 5), (16, 16, 0)])
 def test_gemm_generic_path_matches_oracle(G, M, N, K):
     # K not a multiple of 16 -> row stride unaligned -> the byte-load kernel
-    for out_dtype, pc, bias, res in [(I8, 1, True, True), (I32, 0, True, False)]:
+    for out_dtype, pc, bias, res in [(I8, 1, True, True), (I32, 0, True, False), (I16, 1, True, True)]:
         G.say("gemm generic M=%d N=%d K=%d out=%d" % (M, N, K, out_dtype))
         _gemm_case(G, M, N, K, out_dtype, pc, bias, res, seed=7 * M + K)
 
@@ -349,7 +388,7 @@ def test_gemm_direct_to_lds_tiles(G, cfg, M, N, K):
     from paper_2101_01321_amd import binding as B
     assert B.lib().ibert_gemm_config_override(cfg) > cfg
     try:
-        for out_dtype, pc, bias, res in [(I8, 1, True, False), (I32, 1, True, True), (I8, 0, False, True)]:
+        for out_dtype, pc, bias, res in [(I8, 1, True, False), (I32, 1, True, True), (I8, 0, False, True), (I16, 1, True, True)]:
             G.say("gemm direct-to-LDS cfg=%d M=%d N=%d K=%d out=%d" % (cfg, M, N, K, out_dtype))
             _gemm_case(G, M, N, K, out_dtype, pc, bias, res, seed=cfg + M + N + K)
     finally:
@@ -364,7 +403,7 @@ def test_gemm_small_tiles(G, cfg, M, N, K):
     from paper_2101_01321_amd import binding as B
     assert B.lib().ibert_gemm_config_override(cfg) > 15
     try:
-        for out_dtype, pc, bias, res in [(I8, 1, True, False), (I32, 1, True, True), (I8, 0, False, True)]:
+        for out_dtype, pc, bias, res in [(I8, 1, True, False), (I32, 1, True, True), (I8, 0, False, True), (I16, 0, True, True)]:
             G.say("gemm small tiles cfg=%d M=%d N=%d K=%d out=%d" % (cfg, M, N, K, out_dtype))
             _gemm_case(G, M, N, K, out_dtype, pc, bias, res, seed=cfg + M + N + K)
     finally:
@@ -501,7 +540,7 @@ def _layer_case_body(G, cfg, n_layers, fusion):
         model.mark_unwritten()
         ty = model.layer_forward(l, tx)
         torch.cuda.synchronize()
-        got_inter = model.intermediates()
+        got_inter = model.intermediates(r_half=bool(fusion & 8))
         for k in ("qkv", "scores", "probs", "ctx", "r1", "h1", "f1", "g", "r2"):
             if k == "f1" and (fusion & 1):
                 continue                                     # not materialised when GELU runs in the MatMul epilogue
@@ -522,12 +561,14 @@ def test_layer_tiny_every_intermediate(G):
     _layer_case(G, synth.CONFIGS["tiny"])
     _layer_case(G, synth.CONFIGS["tiny"], fusion=3)
     _layer_case(G, synth.CONFIGS["tiny"], fusion=7)
+    _layer_case(G, synth.CONFIGS["tiny"], fusion=8)
+    _layer_case(G, synth.CONFIGS["tiny"], fusion=15)
 
 
 def test_layer_whole_tile_shape_fused_and_unfused(G):
     # hidden/ffn/tokens that fit the whole-tile MatMul configurations, so that every fusion really runs its fused kernel
     cfg = synth.EncoderConfig("tiles", 256, 4, 1024, 128, 16, 1)
-    for fusion in (0, 1, 2, 3, 4, 5, 7):
+    for fusion in (0, 1, 2, 3, 4, 5, 7, 8, 11, 15):
         _layer_case(G, cfg, fusion=fusion)
     # the LayerNorm fusion is the library's own choice at about one 128-row tile per compute unit; force its tile
     # configurations on small layers (128-wide column tiles at hidden 256, 96-wide at hidden 384; two layers)
@@ -722,6 +763,9 @@ def _gemm_layernorm_degenerate(G, M, N, K):
 def test_layer_ragged_every_intermediate(G):
     _layer_case(G, synth.EncoderConfig("ragged", 192, 3, 320, 40, 2, 1))
     _layer_case(G, synth.EncoderConfig("ragged2", 320, 5, 200, 77, 3, 2), n_layers=2)
+    # 16-bit LayerNorm inputs on shapes that take the ragged-tile, K-tail and byte-load MatMul kernels
+    _layer_case(G, synth.EncoderConfig("ragged", 192, 3, 320, 40, 2, 1), fusion=8)
+    _layer_case(G, synth.EncoderConfig("ragged2", 320, 5, 200, 77, 3, 2), n_layers=2, fusion=11)
 
 
 def test_encoder_base_b1_all_layers(G):

@@ -152,6 +152,10 @@ def test_entry_points_reject_bad_arguments_before_touching_the_gpu():
     assert L.ibert_layernorm_i(dummy, dummy, 4, 768, 768, 768, dummy, dummy, 0, None) == -3
     assert L.ibert_layernorm_i(dummy, dummy, 4, 768, 768, 768, None, dummy, 18, None) == -1
     assert L.ibert_layernorm_i(None, None, 0, 768, 768, 768, None, None, 18, None) == 0
+    assert L.ibert_layernorm_i16(dummy, dummy, 4, 2048, 2048, 2048, dummy, dummy, 18, None) == -3
+    assert L.ibert_layernorm_i16(dummy, dummy, 4, 768, 700, 768, dummy, dummy, 18, None) == -2
+    assert L.ibert_layernorm_i16(dummy, dummy, 4, 768, 768, 768, None, dummy, 18, None) == -1
+    assert L.ibert_layernorm_i16(None, None, 0, 768, 768, 768, None, None, 18, None) == 0
     d = B.GemmDesc()
     d.M, d.N, d.K, d.batch_outer, d.batch_inner = 4, 4, 4, 1, 1
     d.lda = d.ldw = d.ldc = 4
@@ -213,8 +217,9 @@ def test_fused_entry_points_reject_bad_arguments_before_touching_the_gpu():
     assert gg(C.byref(d), None, None, C.byref(gp), None, None) == 0                                        # empty problem
     # the fusion mask: query, set, unknown bits dropped
     old = L.ibert_set_fusion(-1)
+    assert old == 11                                                 # the library's default
     assert L.ibert_set_fusion(0) == old and L.ibert_set_fusion(-1) == 0
-    assert L.ibert_set_fusion(0xff) == 0 and L.ibert_set_fusion(-1) == 7
+    assert L.ibert_set_fusion(0xff) == 0 and L.ibert_set_fusion(-1) == 15
     L.ibert_set_fusion(old)
 
 
