@@ -697,6 +697,14 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
         // gain nothing from it and 256x128 loses, so those keep the lane's own stores)
         constexpr bool OST = OUT_I8 && !GELU && BM * SPB <= 32 * JC * SP * 4;   // fits the staging area in front of the constants
         const bool use_ost = OST && g.c_vec16;
+        // 16-bit outputs of the eight-wavefront tiles likewise (8-byte pieces: the row pitch 2 BN + 8 is what fits in
+        // front of the constants whenever BM <= 64 JC).  Measured inside the encoder: 256x192 with eight wavefronts,
+        // [32768,768] outputs: K 768 48.3 -> 43.5 us, K 3072 91.7 -> 89.5 us; the four-wavefront tiles lose by it
+        // (128x96: 9.6 -> 11.0 us; 256x128: 66.5 -> 76.4 us), their lanes' own 8-byte stores stay.
+        constexpr int SPH = 2 * BN + 8;
+        constexpr bool OST16 = !OUT_I8 && !LN && NW == 8 && BM <= 64 * JC;
+        static_assert(!OST16 || BM * SPH <= 32 * JC * SP * 4, "the 16-bit staging tile ends where the constants begin");
+        const bool use_ost16 = OST16 && g.c16;
         int8_t* const ostage = lds;
         char* const c_base = reinterpret_cast<char*>(g.C) +
                              (c_off + (int64_t)(m0 + wm0 + frow) * g.ldc + n0 + wn0 + 4 * fch) * (int64_t)esz;
@@ -737,9 +745,25 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
                     if (use_ost) *reinterpret_cast<uint32_t*>(ostage + (wm0 + 16 * j + frow) * SPB + wn0 + 16 * i + 4 * fch) = pk4;
                     else *reinterpret_cast<uint32_t*>(cp) = pk4;
                 } else if (g.c16) {
-                    *reinterpret_cast<uint2*>(cp) = uint2{pack2_i16(o[0], o[1]), pack2_i16(o[2], o[3])};
+                    const uint2 pk2 = uint2{pack2_i16(o[0], o[1]), pack2_i16(o[2], o[3])};
+                    if (use_ost16) *reinterpret_cast<uint2*>(ostage + (wm0 + 16 * j + frow) * SPH + (wn0 + 16 * i + 4 * fch) * 2) = pk2;
+                    else *reinterpret_cast<uint2*>(cp) = pk2;
                 } else {
                     *reinterpret_cast<v4i*>(cp) = v4i{o[0], o[1], o[2], o[3]};
+                }
+            }
+        }
+        if (use_ost16) {
+            __syncthreads();
+            constexpr int P8 = BN / 4, CH = BM * P8;               // 8-byte pieces per row, per tile
+            char* const ct = reinterpret_cast<char*>(g.C) + (c_off + (int64_t)m0 * g.ldc + n0) * 2;
+#pragma unroll 4
+            for (int q0 = 0; q0 < CH; q0 += NT) {
+                const int q = q0 + tid;
+                if (CH % NT == 0 || q < CH) {
+                    const int row = q / P8, c8 = q - row * P8;
+                    *reinterpret_cast<uint2*>(ct + (uint32_t)row * c_pitch + c8 * 8) =
+                        *reinterpret_cast<const uint2*>(ostage + row * SPH + c8 * 8);
                 }
             }
         }
