@@ -141,7 +141,7 @@ def main():
     ap.add_argument("--config", default="base_b32")
     ap.add_argument("--no-graph", action="store_true", help="launch every step from the host instead of a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--cpu-seqs", type=int, default=8, help="sequences of the workload the CPU oracle runs")
+    ap.add_argument("--cpu-seqs", type=int, default=32, help="sequences of the workload the CPU oracle runs (about 9 s for Base)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 256 MiB device copies (reference for the FETCH_SIZE/WRITE_SIZE counters)")
     ap.add_argument("--fusion", type=int, default=-1,

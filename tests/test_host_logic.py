@@ -163,6 +163,11 @@ def test_entry_points_reject_bad_arguments_before_touching_the_gpu():
     assert L.ibert_gemm_i8_requant(C.byref(d), None, dummy, None, None, None, None, dummy, None) == -1
     d.out_clamp = 128
     assert L.ibert_gemm_i8_requant(C.byref(d), dummy, dummy, None, None, None, None, dummy, None) == -3
+    d.out_dtype, d.out_clamp = B.I16, 32768                      # a 16-bit output cannot hold a wider clamp
+    assert L.ibert_gemm_i8_requant(C.byref(d), dummy, dummy, None, None, None, None, dummy, None) == -3
+    d.out_dtype = 3                                              # no such type
+    assert L.ibert_gemm_i8_requant(C.byref(d), dummy, dummy, None, None, None, None, dummy, None) == -3
+    d.out_dtype = B.I8
     d.out_clamp, d.requant = 127, B.Dyadic(1, 63)
     assert L.ibert_gemm_i8_requant(C.byref(d), dummy, dummy, None, None, None, None, dummy, None) == -3
     d.requant, d.lda = B.Dyadic(1, 0), 3
