@@ -693,9 +693,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
         // INT8 tiles go through LDS once more, packed: a lane's own store would be 4 bytes in each of 16 rows per
         // instruction, which the address unit takes an order of magnitude longer over than whole rows.
         constexpr int SPB = BN + 16;                               // staged row pitch in bytes (16-byte aligned rows)
-        // (measured: a gain of 1.5-2 us on the QKV projections; with GELU in the epilogue the big one-per-CU tiles
-        // gain nothing from it and 256x128 loses, so those keep the lane's own stores)
-        constexpr bool OST = OUT_I8 && !GELU && BM * SPB <= 32 * JC * SP * 4;   // fits the staging area in front of the constants
+        // (measured: a gain of 1.5-2 us on the QKV projections; with GELU in the epilogue the four-wavefront tiles
+        // gain nothing from it and 256x128 loses, so those keep the lane's own stores; the eight-wavefront GELU tiles
+        // gain -- S7+S8 of Base 18.9 -> 17.9 us, of Base at 512 tokens x 64: 133.8 -> 125.5 us)
+        constexpr bool OST = OUT_I8 && (!GELU || NW == 8) && BM * SPB <= 32 * JC * SP * 4;   // fits the staging area in front of the constants
         const bool use_ost = OST && g.c_vec16;
         // 16-bit outputs of the eight-wavefront tiles likewise (8-byte pieces: the row pitch 2 BN + 8 is what fits in
         // front of the constants whenever BM <= 64 JC).  Measured inside the encoder: 256x192 with eight wavefronts,
