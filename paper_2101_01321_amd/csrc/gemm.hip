@@ -1049,6 +1049,7 @@ static const GemmConfig kConfigs[] = {      // index = configuration number of i
     {256, 192, 128, 2, true},       // with eight wavefronts
     {256, 128, 128, 2, true},       // with eight wavefronts
     {32, 32, 128, 4, false},
+    {256, 256, 128, 2, true},       // with eight wavefronts
 };
 constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 #ifdef IBERT_KERNEL_TIMING
@@ -1192,6 +1193,9 @@ static int choose_config(const ibert_gemm_desc& d, int64_t nb, bool gelu)
     if (g_config_override >= 0 && g_config_override < kNumConfigs) return g_config_override;
     auto tiles = [&](int bm, int bn) -> int64_t { return dma_ok(d, bm, bn) ? (int64_t)(d.M / bm) * (d.N / bn) * nb : 0; };
     // (256x256 pays only when K is long enough to amortise its 256-value-per-lane epilogue, and never with GELU in it)
+    // (with eight wavefronts for 16- and 32-bit outputs from two rounds of tiles on: [32768,1024] x K 4096 154 -> 131 us,
+    //  2.1 POP/s; K 1024 67.8 -> 65.2 us; INT8 outputs lose -- their packed rows do not fit beside this tile)
+    if (tiles(256, 256) >= 512 && d.out_dtype != IBERT_I8 && !gelu) return 16;
     if (tiles(256, 256) >= 512 && d.K >= 8192 && !gelu) return 8;
     // (with eight wavefronts; it pays from three quarters of a wave of tiles on: S1 of Base, 192 tiles, 17.1 -> 15.1 us)
     if (tiles(256, 192) >= (gelu ? 224 : 192)) return 13;
@@ -1325,6 +1329,7 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
             case 13: if (dma_ok(d, 256, 192)) return launch_mfma<256, 192, 128, 2, false, true, false, false, 8>(g, i8, stream); break;
             case 14: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 2, false, true, false, false, 8>(g, i8, stream); break;
             case 15: return launch_mfma<32, 32, 128, 4>(g, i8, stream);
+            case 16: if (dma_ok(d, 256, 256)) return launch_mfma<256, 256, 128, 2, false, true, false, false, 8>(g, i8, stream); break;
             default: break;
         }
         return launch_mfma<128, 128, 64, 2>(g, i8, stream);

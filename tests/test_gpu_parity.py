@@ -381,7 +381,9 @@ def test_gemm_trans_w_mfma_path(G, M, N, K, ldw):
                                        (12, 128, 256, 512), (12, 128, 256, 1024),
                                        # 256x192 with eight wavefronts
                                        (13, 256, 192, 128), (13, 512, 384, 256), (13, 256, 576, 640), (13, 768, 192, 1152),
-                                       (14, 256, 128, 128), (14, 512, 384, 256), (14, 256, 256, 896)])
+                                       (14, 256, 128, 128), (14, 512, 384, 256), (14, 256, 256, 896),
+                                       # 256x256 with eight wavefronts
+                                       (16, 256, 256, 128), (16, 512, 256, 256), (16, 256, 768, 384), (16, 512, 512, 1024)])
 def test_gemm_direct_to_lds_tiles(G, cfg, M, N, K):
     # the tile configurations whose loader writes LDS straight from global memory (whole tiles only), forced
     # through the configuration override; 1, 2, odd and even numbers of K steps
