@@ -269,7 +269,9 @@ typedef struct {
     int32_t ln2_shift;
 } ibert_layer_quant;
 
-/* Byte offsets of the intermediates inside the workspace (each 256-byte aligned). */
+/* Byte offsets of the intermediates inside the workspace (each 256-byte aligned).  Element types are those of the step
+ * list above, except that r1 / r2 hold int16 [T, hidden] (at the start of regions sized for int32) under fusion bit 3,
+ * and that a region whose tensor a fusion never materialises is left untouched (see ibert_set_fusion). */
 typedef struct {
     size_t qkv, scores, probs, ctx, r1, h1, f1, g, r2;
     size_t ln_stats;   /* row statistics shared by the column tiles of a fused MatMul + LayerNorm; its last 4 bytes are a
