@@ -692,11 +692,20 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
         const int32_t lut_hi = g.gelu_lut_n - 1;
         // INT8 tiles go through LDS once more, packed: a lane's own store would be 4 bytes in each of 16 rows per
         // instruction, which the address unit takes an order of magnitude longer over than whole rows.
-        constexpr int SPB = BN + 16;                               // staged row pitch in bytes (16-byte aligned rows)
+        // staged row pitch in bytes (16-byte aligned rows): padded by one piece, or -- where only the bare tile fits and
+        // a row is a whole number of 256-byte bank cycles -- unpadded with the pieces of a row permuted by the row
+        // number, so that the 16 rows a wavefront writes at once still land on 16 different bank groups
+        constexpr bool OST_PAD = BM * (BN + 16) <= 32 * JC * SP * 4;
+        constexpr bool OST_SWZ = !OST_PAD && BN == 256 && BM * BN <= 32 * JC * SP * 4;
+        constexpr int SPB = OST_PAD ? BN + 16 : BN;
+        auto ost_at = [&](int row, int col) {                      // byte offset of column col (a multiple of 4) of a staged row
+            const int piece = OST_SWZ ? ((col >> 4) ^ (row & 15)) : (col >> 4);
+            return row * SPB + (piece << 4) + (col & 15);
+        };
         // (measured: a gain of 1.5-2 us on the QKV projections; with GELU in the epilogue the four-wavefront tiles
         // gain nothing from it and 256x128 loses, so those keep the lane's own stores; the eight-wavefront GELU tiles
         // gain -- S7+S8 of Base 18.9 -> 17.9 us, of Base at 512 tokens x 64: 133.8 -> 125.5 us)
-        constexpr bool OST = OUT_I8 && (!GELU || NW == 8) && BM * SPB <= 32 * JC * SP * 4;   // fits the staging area in front of the constants
+        constexpr bool OST = OUT_I8 && (!GELU || NW == 8) && (OST_PAD || OST_SWZ);   // fits the staging area in front of the constants
         const bool use_ost = OST && g.c_vec16;
         // 16-bit outputs of the eight-wavefront tiles likewise (8-byte pieces: the row pitch 2 BN + 8 is what fits in
         // front of the constants whenever BM <= 64 JC).  Measured inside the encoder: 256x192 with eight wavefronts,
@@ -743,7 +752,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
                 char* cp = c_base + ((uint32_t)(j * 16) * c_pitch + (uint32_t)(i * 16) * esz);
                 if (OUT_I8) {
                     const uint32_t pk4 = pack4_i8(o[0], o[1], o[2], o[3]);
-                    if (use_ost) *reinterpret_cast<uint32_t*>(ostage + (wm0 + 16 * j + frow) * SPB + wn0 + 16 * i + 4 * fch) = pk4;
+                    if (use_ost) *reinterpret_cast<uint32_t*>(ostage + ost_at(wm0 + 16 * j + frow, wn0 + 16 * i + 4 * fch)) = pk4;
                     else *reinterpret_cast<uint32_t*>(cp) = pk4;
                 } else if (g.c16) {
                     const uint2 pk2 = uint2{pack2_i16(o[0], o[1]), pack2_i16(o[2], o[3])};
@@ -778,7 +787,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
                 if (CH % NT == 0 || q < CH) {
                     const int row = q / C16, c16 = q - row * C16;
                     *reinterpret_cast<v4i*>(ct + (uint32_t)row * c_pitch + c16 * 16) =
-                        *reinterpret_cast<const v4i*>(ostage + row * SPB + c16 * 16);
+                        *reinterpret_cast<const v4i*>(ostage + ost_at(row, c16 * 16));
                 }
             }
         }
@@ -1194,8 +1203,11 @@ static int choose_config(const ibert_gemm_desc& d, int64_t nb, bool gelu)
     auto tiles = [&](int bm, int bn) -> int64_t { return dma_ok(d, bm, bn) ? (int64_t)(d.M / bm) * (d.N / bn) * nb : 0; };
     // (256x256 pays only when K is long enough to amortise its 256-value-per-lane epilogue, and never with GELU in it)
     // (with eight wavefronts for 16- and 32-bit outputs from two rounds of tiles on: [32768,1024] x K 4096 154 -> 131 us,
-    //  2.1 POP/s; K 1024 67.8 -> 65.2 us; INT8 outputs lose -- their packed rows do not fit beside this tile)
+    //  2.1 POP/s; K 1024 67.8 -> 65.2 us)
     if (tiles(256, 256) >= 512 && d.out_dtype != IBERT_I8 && !gelu) return 16;
+    // (INT8 outputs without GELU, whose rows leave packed through LDS, when the tiles come in whole rounds:
+    //  [32768,3072] x K 1024 134 -> 120 us; with a ragged last round, or GELU in the epilogue, it loses)
+    if (tiles(256, 256) >= 512 && tiles(256, 256) % 256 == 0 && d.out_dtype == IBERT_I8 && !gelu) return 16;
     if (tiles(256, 256) >= 512 && d.K >= 8192 && !gelu) return 8;
     // (with eight wavefronts; it pays from three quarters of a wave of tiles on: S1 of Base, 192 tiles, 17.1 -> 15.1 us)
     if (tiles(256, 192) >= (gelu ? 224 : 192)) return 13;
