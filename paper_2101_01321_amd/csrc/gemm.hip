@@ -1059,6 +1059,8 @@ static const GemmConfig kConfigs[] = {      // index = configuration number of i
     {256, 128, 128, 2, true},       // with eight wavefronts
     {32, 32, 128, 4, false},
     {256, 256, 128, 2, true},       // with eight wavefronts
+    {64, 96, 128, 3, true},
+    {64, 96, 128, 2, true},
 };
 constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 #ifdef IBERT_KERNEL_TIMING
@@ -1197,7 +1199,7 @@ static bool dma_ok(const ibert_gemm_desc& d, int bm, int bn)
 // so that one workgroup's requantization overlaps another's MFMAs.
 // Everything else takes the register-ring loader: 128x128 tiles with a 64-wide K step while that gives every
 // CU something to do, below that 64x64 tiles.
-static int choose_config(const ibert_gemm_desc& d, int64_t nb, bool gelu)
+static int choose_config(const ibert_gemm_desc& d, int64_t nb, bool gelu, bool ln)
 {
     if (g_config_override >= 0 && g_config_override < kNumConfigs) return g_config_override;
     auto tiles = [&](int bm, int bn) -> int64_t { return dma_ok(d, bm, bn) ? (int64_t)(d.M / bm) * (d.N / bn) * nb : 0; };
@@ -1212,7 +1214,14 @@ static int choose_config(const ibert_gemm_desc& d, int64_t nb, bool gelu)
     // (with eight wavefronts; it pays from three quarters of a wave of tiles on: S1 of Base, 192 tiles, 17.1 -> 15.1 us)
     if (tiles(256, 192) >= (gelu ? 224 : 192)) return 13;
     // (one workgroup per CU and a long K: a third LDS stage lets the requests spread over the whole step)
-    if (tiles(128, 96) >= 256) return tiles(128, 96) <= 256 && d.K >= 2048 ? 11 : 9;
+    if (tiles(128, 96) >= 256) {
+        // (exactly one 128x96 tile per CU and a 16- or 32-bit output: 64x96 tiles, three or four of which share a CU, so
+        //  that one's epilogue overlaps another's loop -- inside the encoder S5 of Base 9.7 -> 8.9 us, S9 17.9 -> 17.3 us;
+        //  a fourth LDS stage leaves room for one workgroup per CU only and loses, 24 us.  The LayerNorm epilogue keeps
+        //  the 128-row tiles: it needs few, large contributions per row.)
+        if (tiles(128, 96) <= 256 && d.out_dtype != IBERT_I8 && !gelu && !ln) return d.K >= 2048 ? 17 : 18;
+        return tiles(128, 96) <= 256 && d.K >= 2048 ? 11 : 9;
+    }
     // (eight wavefronts for INT8 outputs: S7+S8 of Large 34.7 -> 32.5 us; INT32 outputs lose 5 % with them)
     if (tiles(256, 128) >= 448) return (gelu || d.out_dtype == IBERT_I8) ? 14 : 10;
     if (tiles(128, 128) >= 128) return tiles(128, 128) <= 256 && d.K >= 2048 ? 12 : 7;
@@ -1292,7 +1301,7 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
     if (zero && !(fast && d.K % 16 == 0)) return IBERT_ERR_NOT_IMPLEMENTED;
     if (fast) {
         if (d.K % 16 != 0) return launch_tail(g, i8, stream);       // bytewise K tail
-        const int cfg = choose_config(d, nb, gelu != nullptr);
+        const int cfg = choose_config(d, nb, gelu != nullptr, ln != nullptr);
         if (ln) {
             g.ldc = d.N;                                            // (unused: keeps the epilogue's row offsets small)
             // Only where a 128-row tile is the choice for this problem anyway: measured, the exchange between the column
@@ -1342,6 +1351,8 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
             case 14: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 2, false, true, false, false, 8>(g, i8, stream); break;
             case 15: return launch_mfma<32, 32, 128, 4>(g, i8, stream);
             case 16: if (dma_ok(d, 256, 256)) return launch_mfma<256, 256, 128, 2, false, true, false, false, 8>(g, i8, stream); break;
+            case 17: if (dma_ok(d, 64, 96)) return launch_mfma<64, 96, 128, 3, false, true>(g, i8, stream); break;
+            case 18: if (dma_ok(d, 64, 96)) return launch_mfma<64, 96, 128, 2, false, true>(g, i8, stream); break;
             default: break;
         }
         return launch_mfma<128, 128, 64, 2>(g, i8, stream);

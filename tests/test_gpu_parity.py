@@ -383,7 +383,10 @@ def test_gemm_trans_w_mfma_path(G, M, N, K, ldw):
                                        (13, 256, 192, 128), (13, 512, 384, 256), (13, 256, 576, 640), (13, 768, 192, 1152),
                                        (14, 256, 128, 128), (14, 512, 384, 256), (14, 256, 256, 896),
                                        # 256x256 with eight wavefronts
-                                       (16, 256, 256, 128), (16, 512, 256, 256), (16, 256, 768, 384), (16, 512, 512, 1024)])
+                                       (16, 256, 256, 128), (16, 512, 256, 256), (16, 256, 768, 384), (16, 512, 512, 1024),
+                                       # 64x96, three and two LDS stages
+                                       (17, 64, 96, 128), (17, 128, 192, 256), (17, 192, 96, 384), (17, 256, 288, 1024),
+                                       (18, 64, 96, 128), (18, 128, 192, 256), (18, 64, 96, 512), (18, 128, 96, 640)])
 def test_gemm_direct_to_lds_tiles(G, cfg, M, N, K):
     # the tile configurations whose loader writes LDS straight from global memory (whole tiles only), forced
     # through the configuration override; 1, 2, odd and even numbers of K steps
