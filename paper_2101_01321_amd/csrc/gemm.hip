@@ -1061,6 +1061,7 @@ static const GemmConfig kConfigs[] = {      // index = configuration number of i
     {256, 256, 128, 2, true},       // with eight wavefronts
     {64, 96, 128, 3, true},
     {64, 96, 128, 2, true},
+    {64, 128, 128, 2, true},
 };
 constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 #ifdef IBERT_KERNEL_TIMING
@@ -1224,7 +1225,11 @@ static int choose_config(const ibert_gemm_desc& d, int64_t nb, bool gelu, bool l
     }
     // (eight wavefronts for INT8 outputs: S7+S8 of Large 34.7 -> 32.5 us; INT32 outputs lose 5 % with them)
     if (tiles(256, 128) >= 448) return (gelu || d.out_dtype == IBERT_I8) ? 14 : 10;
-    if (tiles(128, 128) >= 128) return tiles(128, 128) <= 256 && d.K >= 2048 ? 12 : 7;
+    if (tiles(128, 128) >= 128) {
+        // (likewise 64x128 tiles for a short K: S5 of Large 14.4 -> 12.9 us; with K 4096 they lose, 25.9 -> 30 us)
+        if (tiles(128, 128) <= 256 && d.K < 2048 && d.out_dtype != IBERT_I8 && !gelu && !ln) return 19;
+        return tiles(128, 128) <= 256 && d.K >= 2048 ? 12 : 7;
+    }
     const int64_t tiles128 = (((int64_t)d.M + 127) / 128) * (((int64_t)d.N + 127) / 128) * nb;
     if (tiles128 >= 384) return 2;
     // (a handful of sequences: 32x32 tiles put four times as many compute units on a long K than 64x64 do;
@@ -1353,6 +1358,7 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
             case 16: if (dma_ok(d, 256, 256)) return launch_mfma<256, 256, 128, 2, false, true, false, false, 8>(g, i8, stream); break;
             case 17: if (dma_ok(d, 64, 96)) return launch_mfma<64, 96, 128, 3, false, true>(g, i8, stream); break;
             case 18: if (dma_ok(d, 64, 96)) return launch_mfma<64, 96, 128, 2, false, true>(g, i8, stream); break;
+            case 19: if (dma_ok(d, 64, 128)) return launch_mfma<64, 128, 128, 2, false, true>(g, i8, stream); break;
             default: break;
         }
         return launch_mfma<128, 128, 64, 2>(g, i8, stream);

@@ -386,7 +386,9 @@ def test_gemm_trans_w_mfma_path(G, M, N, K, ldw):
                                        (16, 256, 256, 128), (16, 512, 256, 256), (16, 256, 768, 384), (16, 512, 512, 1024),
                                        # 64x96, three and two LDS stages
                                        (17, 64, 96, 128), (17, 128, 192, 256), (17, 192, 96, 384), (17, 256, 288, 1024),
-                                       (18, 64, 96, 128), (18, 128, 192, 256), (18, 64, 96, 512), (18, 128, 96, 640)])
+                                       (18, 64, 96, 128), (18, 128, 192, 256), (18, 64, 96, 512), (18, 128, 96, 640),
+                                       # 64x128
+                                       (19, 64, 128, 128), (19, 128, 256, 256), (19, 192, 128, 384), (19, 256, 384, 1024)])
 def test_gemm_direct_to_lds_tiles(G, cfg, M, N, K):
     # the tile configurations whose loader writes LDS straight from global memory (whole tiles only), forced
     # through the configuration override; 1, 2, odd and even numbers of K steps
