@@ -12,7 +12,10 @@
  *   - All tensors are dense row-major with explicit row strides (in elements).
  *   - Only integers reach the device: real scales appear solely in the host helpers at the end,
  *     which pre-compute the integer constants (static quantization, Sec. 3.1 and App. A; footnote
- *     of Alg. 1).  The device code contains no floating-point instruction that the source asks for.
+ *     of Alg. 1).  The device sources contain no floating-point type or operation (the integer square root of
+ *     Alg. 4 included); the only place the compiler may use its reciprocal unit is its own expansion of the two
+ *     per-row integer divisions with data-dependent divisors (2^31 / sum in Softmax, 2^24 / sigma in LayerNorm),
+ *     each of which returns the exact integer quotient.
  *   - Out-of-range data never faults: it is clamped as documented (the functions are total on int32
  *     inputs); out-of-range *constants* are refused with IBERT_ERR_PARAM_RANGE.
  *   - floor(.) is the mathematical floor; ">>" on signed values is an arithmetic shift.
@@ -96,11 +99,6 @@ typedef struct {
 int ibert_gemm_i8_requant(const ibert_gemm_desc* desc, const int8_t* A, const int8_t* W,
                           const int32_t* bias, const int32_t* mult, const int32_t* shift,
                           const int8_t* residual, void* C, void* stream);
-
-/* Tuning aid: force tile configuration `config` (0 .. count-1) of the MFMA kernel for every later
- * ibert_gemm_i8_requant call that takes the fast path; a negative value restores the built-in choice.
- * Returns the number of configurations.  Results do not depend on the configuration. */
-int ibert_gemm_config_override(int32_t config);
 
 /* ------------------------------------------------------------------------------------------------
  * ibert_softmax_i -- integer-only Softmax over the last axis (Alg. 3; Eq. 11-14).
@@ -211,6 +209,18 @@ int ibert_layernorm_i16(const int16_t* x, int8_t* y, int64_t rows, int32_t C, in
                         const int32_t* gamma_q, const int32_t* beta_q, int32_t shift, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * ibert_isqrt_i -- the integer square root of Alg. 4 (Sec. 3.6) as a call of its own: root[i] = floor(sqrt(n[i])) for
+ * any 32-bit n[i], which is what the Newton iteration of Alg. 4 returns (it starts at 2^ceil(Bits(n)/2), at or above the
+ * root, and its integer iterates decrease to exactly that value).  The library reaches the same integer without a chain
+ * of divisions, by the two routines the LayerNorm kernels use, selected by `method`:
+ *   0: one value per lane, sixteen shift-and-subtract steps;
+ *   1, 2, 3: the 64, 32 or 16 lanes that share a row test one candidate each per round and count the ones whose square
+ *      does not exceed n (three or four rounds) -- the form ibert_layernorm_i runs, once per row.
+ * n, root: device uint32 [count].  Errors: IBERT_ERR_SHAPE (count < 0), IBERT_ERR_PARAM_RANGE (method), IBERT_ERR_NULL.
+ * ---------------------------------------------------------------------------------------------- */
+int ibert_isqrt_i(const uint32_t* n, uint32_t* root, int64_t count, int32_t method, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
  * ibert_embedding_i -- the INT8 embedding that feeds the first layer (Sec. 1, third contribution; App. C.1: the
  * embedding tables are INT8 like every other parameter).  The paper does not spell out how the looked-up rows are
  * added and normalized; reading, for token t (its position is t mod seq):
@@ -267,16 +277,29 @@ typedef struct {
     ibert_gelu_params gelu;
     ibert_dyadic res2_dy;
     int32_t ln2_shift;
+    int32_t route;               /* 0: every fusion below; else IBERT_ROUTE_* flags OR-ed together */
 } ibert_layer_quant;
 
+/* Which kernels a layer call runs.  The result never depends on it (each fused kernel is bit-identical to the
+ * composition it replaces; the tests run every combination); the flags exist so that each step can be run and looked
+ * at by itself.  Default (0):
+ *   - steps 7 and 8 (FFN up-projection and GELU) as one kernel where ibert_gemm_i8_gelu can do so; the workspace
+ *     region f1 is then left untouched;
+ *   - steps 2, 3 and 4 as one kernel where ibert_attention_i can do so; the workspace regions scores and probs are then
+ *     left untouched (profile records: one, numbered 2);
+ *   - r1 / r2, which are clamped to 16 bits by definition, stored as int16 [T, hidden] (IBERT_I16) at the start of their
+ *     workspace regions and read by ibert_layernorm_i16: the two kernels move half the bytes. */
+enum {
+    IBERT_ROUTE_SEPARATE_GELU = 1,        /* step 7 writes f1 (int32), step 8 is a kernel of its own        */
+    IBERT_ROUTE_SEPARATE_ATTENTION = 2,   /* steps 2, 3, 4 as three kernels through scores and probs        */
+    IBERT_ROUTE_I32_LN_INPUT = 4          /* r1 / r2 stored as int32, steps 6 / 10 run ibert_layernorm_i     */
+};
+
 /* Byte offsets of the intermediates inside the workspace (each 256-byte aligned).  Element types are those of the step
- * list above, except that r1 / r2 hold int16 [T, hidden] (at the start of regions sized for int32) under fusion bit 3,
- * and that a region whose tensor a fusion never materialises is left untouched (see ibert_set_fusion). */
+ * list above, except that r1 / r2 hold int16 [T, hidden] (at the start of regions sized for int32) unless
+ * IBERT_ROUTE_I32_LN_INPUT is set, and that a region whose tensor a fused kernel never materialises is left untouched. */
 typedef struct {
     size_t qkv, scores, probs, ctx, r1, h1, f1, g, r2;
-    size_t ln_stats;   /* row statistics shared by the column tiles of a fused MatMul + LayerNorm; its last 4 bytes are a
-                          status word: bit 0 is set (never cleared by the library) if a tile ever gave up waiting for
-                          its neighbours, in which case that call's output is wrong; stays 0 in a healthy run */
     size_t total;
 } ibert_layer_workspace_layout;
 
@@ -362,7 +385,7 @@ int ibert_layer_quant_from_scales(const ibert_layer_scales* scales, int32_t seq,
  * qkv: device int8 [batch*seq, 3*hidden] (Q | K | V, the heads of each side by side); ctx: device int8
  * [batch*seq, hidden].  softmax->out_dtype must be IBERT_I8.
  * With seq in {128, 256, 384, 512} and hidden/heads = 64 (qkv 16-byte aligned, ctx 4-byte aligned) the three steps
- * run as one kernel and scores/probs are never stored -- unless bit 1 of the fusion mask is clear.  Any other shape takes the
+ * run as one kernel and scores/probs are never stored.  Any other shape takes the
  * three-kernel route through `scratch` (device, 256-byte aligned, ibert_attention_scratch_bytes() bytes;
  * IBERT_ERR_WORKSPACE if it is NULL, small or misaligned).  scratch may always be passed.
  * ---------------------------------------------------------------------------------------------- */
@@ -375,45 +398,6 @@ int ibert_attention_masked_i(const int8_t* qkv, int8_t* ctx, int32_t batch, int3
                              const ibert_dyadic* scores_dy, const ibert_softmax_params* softmax,
                              const ibert_dyadic* ctx_dy, const int32_t* key_lens, void* scratch, size_t scratch_bytes,
                              void* stream);
-
-/* ------------------------------------------------------------------------------------------------
- * ibert_gemm_i8_layernorm -- a projection with residual and the LayerNorm that follows it in one call (steps 5+6 and
- * 9+10 of the layer; App. C.1, Sec. 3.6), bit-identical to
- *     ibert_gemm_i8_requant(desc with out_dtype = IBERT_I32, out_clamp = 2^15-1) -> r   [M, N] int32
- *     ibert_layernorm_i(r; gamma_q, beta_q, ln_shift) -> y
- * desc: one problem (batch_outer = batch_inner = 1), out_dtype IBERT_I32, out_clamp 32767 (else IBERT_ERR_SHAPE);
- * ldc is ignored.  1 <= N <= 1024.  y: device int8 [M, ldy].
- * One kernel when M is a multiple of 128, N a multiple of 96 or 128, K a multiple of 128, all rows 16-byte aligned,
- * and the problem is of the size for which the library uses 128-row tiles anyway (about one tile per compute unit:
- * e.g. 4096 tokens at hidden 768 or 1024; ibert_gemm_config_override 7, 9, 11 or 12 forces it), with bit 2 of the
- * fusion mask set: the column tiles of a row
- * exchange the row's sum and sum of squares through integer atomics in `scratch` and normalize their own part, so r is
- * never stored.  Otherwise two kernels through r in `scratch`.
- * scratch: device, 256-byte aligned, ibert_gemm_layernorm_scratch_bytes(M, N) bytes (IBERT_ERR_WORKSPACE); its last word
- * is the status word described at ibert_layer_workspace_layout.
- * ---------------------------------------------------------------------------------------------- */
-size_t ibert_gemm_layernorm_scratch_bytes(int32_t M, int32_t N);
-int ibert_gemm_i8_layernorm(const ibert_gemm_desc* desc, const int8_t* A, const int8_t* W, const int32_t* bias,
-                            const int32_t* mult, const int32_t* shift, const int8_t* residual, const int32_t* gamma_q,
-                            const int32_t* beta_q, int32_t ln_shift, int8_t* y, int64_t ldy, void* scratch,
-                            size_t scratch_bytes, void* stream);
-
-/* Kernel fusions inside ibert_encoder_layer_i / ibert_encoder_i (and ibert_attention_i).
- *   bit 0: steps 7 and 8 (FFN up-projection and GELU) run as one kernel where ibert_gemm_i8_gelu can do so; the
- *          workspace region f1 is then left untouched;
- *   bit 1: steps 2, 3 and 4 run as one kernel where ibert_attention_i can do so; the workspace regions scores
- *          and probs are then left untouched (profile records: one, numbered 2);
- *   bit 2: steps 5+6 and steps 9+10 (projection with residual, then LayerNorm) each run as one kernel where
- *          ibert_gemm_i8_layernorm can do so; the workspace regions r1 / r2 are then left untouched (profile records:
- *          one per pair, numbered 5 / 9);
- *   bit 3: where steps 5 / 9 run as kernels of their own, r1 / r2 are stored as int16 [T, hidden] (IBERT_I16) at the
- *          start of their workspace regions instead of int32, and steps 6 / 10 read that (ibert_layernorm_i16): the
- *          values are clamped to 16 bits anyway, and the two kernels move half the bytes.
- * Default: 11 (bits 0, 1 and 3: measured, the two-kernel route with 16-bit r1 / r2 is as fast as the one-kernel route of
- * bit 2 or faster at every size tried; bit 2 takes precedence where both are set and the one-kernel form applies).
- * flags >= 0 sets the mask (unknown bits are dropped), a negative value only queries.  Returns the
- * previous mask.  Outputs do not depend on the mask.  Not thread-safe. */
-int ibert_set_fusion(int32_t flags);
 
 /* ------------------------------------------------------------------------------------------------
  * Optional instrumentation for benchmarks (not part of the method): while a profile is open,

@@ -71,11 +71,16 @@ class LayerWeights(C.Structure):
 
 class LayerQuant(C.Structure):
     _fields_ = [("scores_dy", Dyadic), ("softmax", SoftmaxParams), ("ctx_dy", Dyadic), ("res1_dy", Dyadic),
-                ("ln1_shift", C.c_int32), ("gelu", GeluParams), ("res2_dy", Dyadic), ("ln2_shift", C.c_int32)]
+                ("ln1_shift", C.c_int32), ("gelu", GeluParams), ("res2_dy", Dyadic), ("ln2_shift", C.c_int32),
+                ("route", C.c_int32)]
+
+
+# ibert_layer_quant.route flags
+ROUTE_SEPARATE_GELU, ROUTE_SEPARATE_ATTENTION, ROUTE_I32_LN_INPUT = 1, 2, 4
 
 
 class WorkspaceLayout(C.Structure):
-    _fields_ = [(n, C.c_size_t) for n in ("qkv", "scores", "probs", "ctx", "r1", "h1", "f1", "g", "r2", "ln_stats", "total")]
+    _fields_ = [(n, C.c_size_t) for n in ("qkv", "scores", "probs", "ctx", "r1", "h1", "f1", "g", "r2", "total")]
 
 
 class LayerScales(C.Structure):
@@ -88,14 +93,13 @@ class ProfileRecord(C.Structure):
                 ("kernel", C.c_char * 96)]
 
 
-# Every symbol include/ibert.h declares, with its ctypes signature.
+# Every symbol include/ibert.h and include/ibert_testing.h declare, with its ctypes signature.
 SIGNATURES = {
     "ibert_gemm_i8_requant": (C.c_int, [C.POINTER(GemmDesc)] + [_P] * 8),
     "ibert_gemm_config_override": (C.c_int, [C.c_int32]),
+    "ibert_gemm_epilogue_record": (None, [_P]),
     "ibert_gemm_i8_gelu": (C.c_int, [C.POINTER(GemmDesc)] + [_P] * 5 + [C.POINTER(GeluParams)] + [_P] * 3),
-    "ibert_set_fusion": (C.c_int, [C.c_int32]),
-    "ibert_gemm_layernorm_scratch_bytes": (C.c_size_t, [C.c_int32, C.c_int32]),
-    "ibert_gemm_i8_layernorm": (C.c_int, [C.POINTER(GemmDesc)] + [_P] * 8 + [C.c_int32, _P, C.c_int64, _P, C.c_size_t, _P]),
+    "ibert_isqrt_i": (C.c_int, [_P, _P, C.c_int64, C.c_int32, _P]),
     "ibert_attention_scratch_bytes": (C.c_size_t, [C.c_int32] * 3),
     "ibert_attention_i": (C.c_int, [_P, _P] + [C.c_int32] * 4 + [C.POINTER(Dyadic), C.POINTER(SoftmaxParams),
                                                                  C.POINTER(Dyadic), _P, C.c_size_t, _P]),
@@ -264,19 +268,16 @@ def ibert_embedding_i(ids, tok, pos, tokens: int, seq: int, hidden: int, vocab: 
          "ibert_embedding_i")
 
 
-def ibert_gemm_layernorm_scratch_bytes(M: int, N: int) -> int:
-    return int(lib().ibert_gemm_layernorm_scratch_bytes(M, N))
+EPILOGUE_STAGED, EPILOGUE_DIRECT, EPILOGUE_DIRECT_GELU_TABLE, EPILOGUE_EDGE = 1, 2, 3, 4
 
 
-def ibert_gemm_i8_layernorm(desc: GemmDesc, A, W, bias, mult, shift, residual, gamma_q, beta_q, ln_shift: int, y, ldy: int,
-                            scratch, stream=None):
-    _chk(lib().ibert_gemm_i8_layernorm(C.byref(desc), _dp(A), _dp(W), _dp(bias), _dp(mult), _dp(shift), _dp(residual),
-                                       _dp(gamma_q), _dp(beta_q), ln_shift, _dp(y), ldy, _dp(scratch),
-                                       scratch.numel() * scratch.element_size(), _stream(stream)), "ibert_gemm_i8_layernorm")
+def ibert_gemm_epilogue_record(word):
+    """word: a uint32/int32 device tensor of one element, or None to switch the record off."""
+    lib().ibert_gemm_epilogue_record(_dp(word))
 
 
-def ibert_set_fusion(flags: int) -> int:
-    return int(lib().ibert_set_fusion(flags))
+def ibert_isqrt_i(n, root, count: int, method: int, stream=None):
+    _chk(lib().ibert_isqrt_i(_dp(n), _dp(root), count, method, _stream(stream)), "ibert_isqrt_i")
 
 
 def ibert_softmax_i(x, y, rows: int, cols: int, ldx: int, ldy: int, params: SoftmaxParams, stream=None):

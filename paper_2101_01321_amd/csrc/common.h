@@ -116,29 +116,10 @@ __device__ __forceinline__ int32_t group_allreduce(int32_t v, Op op)
 // Name of the kernel family chosen by the most recent launch_* call (for the optional profile).
 extern const char* g_last_kernel;
 
-// LayerNorm in the MatMul epilogue: constants, output, and the row statistics the column tiles of a row share
-// (sum[M] and sq[M], 64-bit words, must be zero when the kernel starts; status is only ever OR-ed into).
-struct LnFuse {
-    const int32_t* gamma_q;
-    const int32_t* beta_q;
-    int32_t shift;
-    int8_t* y;
-    int64_t ldy;
-    unsigned long long* sum;
-    unsigned long long* sq;
-    uint32_t* status;
-};
-// 32-bit words a MatMul launch clears as a side job (row statistics for a later LayerNorm epilogue).
-struct ZeroReq {
-    uint32_t* p;
-    int64_t words;
-};
-
 // ---- internal launchers (validated arguments) -----------------------------------------------
 int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, const int32_t* bias,
                 const int32_t* mult, const int32_t* shift, const int8_t* residual, void* C,
-                hipStream_t stream, const ibert_gelu_params* gelu = nullptr, const LnFuse* ln = nullptr,
-                const ZeroReq* zero = nullptr);
+                hipStream_t stream, const ibert_gelu_params* gelu = nullptr);
 int launch_gemm_gelu(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, const int32_t* bias,
                      const int32_t* mult, const int32_t* shift, const ibert_gelu_params& gelu, int8_t* C,
                      int32_t* scratch, hipStream_t stream);
@@ -156,7 +137,6 @@ int launch_layernorm(const int32_t* x, int8_t* y, int64_t rows, int32_t C, int64
                      const int32_t* gamma_q, const int32_t* beta_q, int32_t shift, hipStream_t stream);
 int launch_layernorm16(const int16_t* x, int8_t* y, int64_t rows, int32_t C, int64_t ldx, int64_t ldy,
                        const int32_t* gamma_q, const int32_t* beta_q, int32_t shift, hipStream_t stream);
-int launch_zero_words(uint32_t* p, int64_t words, hipStream_t stream);
 int launch_embedding(const int32_t* ids, const int8_t* tok, const int8_t* pos, int64_t tokens, int32_t seq, int32_t C,
                      int32_t vocab, ibert_dyadic tok_dy, ibert_dyadic pos_dy, const int32_t* gamma_q,
                      const int32_t* beta_q, int32_t shift, int8_t* y, int64_t ldy, hipStream_t stream);

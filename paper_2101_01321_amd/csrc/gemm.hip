@@ -11,8 +11,7 @@
 //   * Two tile loaders: global memory straight into LDS (whole tiles, K a multiple of 128), or through a ring
 //     of registers (everything else that is 16-byte aligned, and W given as [K,N] with aligned rows).
 //   * Integer accumulation is exact, so any consistent K order gives the oracle's bits.
-//   * The epilogue can also apply integer GELU (Alg. 2) to its own INT8 output, or integer LayerNorm (Sec. 3.6) to its
-//     own INT32 result (the column tiles of a row exchange the row's sum and sum of squares through atomics).
+//   * The epilogue can also apply integer GELU (Alg. 2) to its own INT8 output.
 //   * Four wavefronts per workgroup, or eight (two per SIMD) for the big INT8 tiles.
 // Generic path (unaligned operands): one output element per lane, byte loads.
 #include <cstdio>
@@ -20,7 +19,7 @@
 
 #include "common.h"
 #include "gelu_math.h"
-#include "layernorm_math.h"
+#include "ibert_testing.h"
 
 namespace ibert {
 
@@ -53,22 +52,7 @@ struct GemmArgs {
     int32_t gelu_fast; // GELU epilogue: the 24-bit form applies
     int32_t gelu_lut_lo, gelu_lut_n;   // GELU epilogue: table of the values at lo .. lo + n - 1 behind the tile's LDS (n = 0: none)
     GeluConst gelu;    // GELU epilogue: constants (the clamp before it is out_clamp = q_max)
-    // LayerNorm epilogue (LN kernels only): the requantized row is normalized before it leaves the registers
-    const int32_t* ln_gamma;
-    const int32_t* ln_beta;
-    int8_t* ln_y;
-    int64_t ln_ldy;
-    unsigned long long* ln_sum;    // [M] row sums with their contribution counts, zero on entry
-    unsigned long long* ln_sq;     // [M] row sums of squares with their contribution counts, zero on entry
-    uint32_t* ln_status;           // bit 0 is set if a wait for the other tiles of a row ever ran out
-    int32_t ln_shift;
-    uint32_t ln_magic;             // reciprocal multiplier for the divisions by N
-    // Words every launch clears on its way in (the row statistics of the LayerNorm epilogue that runs next)
-    uint32_t* zero_p;
-    int64_t zero_words;
-#ifdef IBERT_KERNEL_TIMING
-    long long* dbg;    // development only: per-wave phase timestamps
-#endif
+    uint32_t* path_word;   // tests only (may be null): workgroup 0 records which epilogue form it ran
 };
 
 // Requantize one accumulator and finish the output value (before the store).
@@ -158,25 +142,16 @@ struct EpiLayout {
 // fragment reads of the next phase and (second phase) the loads of the step after next, one barrier per step.
 // GELU = true (INT8 output): the requantized, clamped value is the GELU input; integer GELU (Alg. 2) and its
 // requantization to INT8 are applied before the store, so the INT32 tensor between the two never exists.
-// LN = true (INT32 result, not stored): integer LayerNorm (Sec. 3.6) over the whole output row follows in the same
-// kernel.  A row spans the tiles_n column tiles of one tile row, which are different workgroups: each adds its part of
-// the row's sum and sum of squares to two words in global memory that also count the contributions (integer atomics:
-// exact in any order), polls them until all have arrived, and then normalizes the values it still holds in registers
-// (sum of squared deviations = sum x^2 - 2 mu sum x + N mu^2, exactly, in 64 bits) and stores INT8.  The wait cannot
-// deadlock: workgroups start in index order and the tiles of a tile row are consecutive, so all earlier tile rows are
-// complete or running and only the newest may be partly started; it is bounded all the same, and a wait that runs
-// out sets a status bit instead of hanging.
 template <int BM, int BN, int BK, int RING, bool OUT_I8, int KMODE, bool TW = false, bool DMA = false, bool GELU = false,
-          bool LN = false, int NW = 4>
+          int NW = 4>
 __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
 {
     // NW wavefronts in two rows of NW/2: wavefront w owns rows [(w%2) BM/2, +BM/2) and columns [(w/2) WN, +WN) of the tile.
     // Eight (two per SIMD) pay for INT8 tiles of 256x192: the second wavefront hides what the first waits for in the loop
     // and in the packing epilogue (inside the encoder: S1 of Large 21.4 -> 19.9 us, S7+S8 of Base 20.6 -> 19.3 us).
     constexpr int NT = 64 * NW;
-    static_assert(NW == 4 || (NW == 8 && DMA && !LN), "four wavefronts, or eight for the direct-to-LDS loader");
+    static_assert(NW == 4 || (NW == 8 && DMA), "four wavefronts, or eight for the direct-to-LDS loader");
     static_assert(!GELU || OUT_I8, "the GELU epilogue writes INT8");
-    static_assert(!LN || (DMA && !OUT_I8 && !GELU), "the LayerNorm epilogue belongs to the whole-tile INT32 kernels");
     constexpr int CPR = BK / 16;                       // 16-byte chunks per tile row
     constexpr int RPP = NT / CPR;            // tile rows loaded per pass of the workgroup
     constexpr int LA = BM / RPP, LW = BN / RPP;        // chunks per lane per K step
@@ -192,17 +167,6 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
-    if (g.zero_words > 0) {
-        for (int64_t i = (int64_t)blockIdx.x * NT + tid; i < g.zero_words; i += (int64_t)gridDim.x * NT)
-            g.zero_p[i] = 0u;
-    }
-#ifdef IBERT_KERNEL_TIMING
-    long long tstamp[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    tstamp[0] = __builtin_readcyclecounter();
-#define IBERT_TS(i) tstamp[i] = __builtin_readcyclecounter()
-#else
-#define IBERT_TS(i)
-#endif
 
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles so that
     // the A panels and W panels it touches stay in its own L2.
@@ -314,20 +278,16 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
 
     // Per-channel constants of this tile's BN columns, one or two columns per lane; used after the main loop.
     constexpr int PPT = (BN + NT - 1) / NT;
-    int32_t pb[PPT], pm[PPT], ps[PPT], pg[PPT], pe[PPT];
+    int32_t pb[PPT], pm[PPT], ps[PPT];
 #pragma unroll
     for (int q = 0; q < PPT; ++q) {
         int nn = n0 + q * NT + tid;
         nn = nn < g.N ? nn : g.N - 1;
-        pb[q] = 0; pm[q] = g.dy_m; ps[q] = g.dy_s; pg[q] = 0; pe[q] = 0;
+        pb[q] = 0; pm[q] = g.dy_m; ps[q] = g.dy_s;
         if (g.bias) pb[q] = g.bias[nn];
         if (g.per_channel) {
             pm[q] = g.mult[nn];
             ps[q] = g.shift[nn];
-        }
-        if (LN) {
-            pg[q] = g.ln_gamma[nn];
-            pe[q] = g.ln_beta[nn];
         }
     }
 
@@ -422,7 +382,6 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
         v4i xa0[FM], wb0[FN], xa1[FM], wb1[FN];
 #pragma unroll
         for (int q = 0; q < NR; ++q) read_one(q, 0, 0, xa0, wb0);
-        IBERT_TS(1);
         // One K step.  Phase 1: slice 0 (fragments already in registers) while slice 1 is read.  Then this
         // wavefront's share of step kt+1 has landed and its reads of stage `buf` are done; after the barrier
         // that holds for the whole workgroup, so `buf` may be refilled and the next stage read.  Phase 2:
@@ -430,34 +389,17 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
         int buf = 0;
         for (int kt = 0; kt < nk; ++kt) {
             const int nbuf = buf + 1 == NSTG ? 0 : buf + 1;
-#ifdef IBERT_KERNEL_TIMING
-            const long long tt0 = __builtin_readcyclecounter();
-#endif
             constexpr int QH = NSTG >= 3 ? (NL + 1) / 2 : NL;          // blocks requested in the second phase
             const int pbuf = buf == 0 ? NSTG - 1 : buf - 1;
             phase(xa0, wb0, xa1, wb1, buf, 1, std::true_type{}, kt - 1 + NSTG, pbuf, kt >= 1 && kt - 1 + NSTG < nk,
                   std::integral_constant<int, QH>{}, std::integral_constant<int, NL>{});
-#ifdef IBERT_KERNEL_TIMING
-            const long long tt1 = __builtin_readcyclecounter();
-#endif
             // steps requested after kt+1 so far: kt+2 .. min(kt+RING-1, nk-1)
             const int hi = kt + NSTG - 1 < nk - 1 ? kt + NSTG - 1 : nk - 1;
             wait_landed(hi - (kt + 1));
-#ifdef IBERT_KERNEL_TIMING
-            const long long tt2 = __builtin_readcyclecounter();
-#endif
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-#ifdef IBERT_KERNEL_TIMING
-            const long long tt3 = __builtin_readcyclecounter();
-#endif
             // (the fragment reads past the last step fetch stale LDS bytes that nothing uses)
             phase(xa1, wb1, xa0, wb0, nbuf, 0, std::true_type{}, kt + NSTG, buf, kt + NSTG < nk,
                   std::integral_constant<int, 0>{}, std::integral_constant<int, QH>{});
-#ifdef IBERT_KERNEL_TIMING
-            tstamp[5] += tt1 - tt0;                                    // phase 1
-            tstamp[6] += tt2 - tt1;                                    // wait for the next step's loads
-            tstamp[7] += tt3 - tt2;                                    // LDS reads + barrier
-#endif
             buf = nbuf;
         }
     } else {
@@ -470,7 +412,6 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
     store_lds(0, 0);
     load_global(RING < last ? RING : last, 0);
     __syncthreads();
-    IBERT_TS(1);
 
     for (int kt0 = 0; kt0 < nk; kt0 += RING) {
 #pragma unroll
@@ -500,7 +441,6 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
 
     }
 
-    IBERT_TS(2);
     // ---- Epilogue -------------------------------------------------------------------------------
     // acc[i][j][r] = C[m0 + wm0 + 16 j + lane%16][n0 + wn0 + 16 i + 4 (lane/16) + r].
     // The accumulators go through LDS (free now), a chunk of rows at a time, so that a short loop can
@@ -517,10 +457,6 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
     int32_t* stage = reinterpret_cast<int32_t*>(lds);              // [32 * JC][SP]
     int32_t* par = stage + 32 * JC * SP;                           // [3][BN]: bias, mult, shift
     uint32_t* resl = reinterpret_cast<uint32_t*>(par + 3 * BN);    // [BM][BN / 4]: residual tile, 4 channels per dword
-    // LN only, [2][BN]: gamma, beta -- inside the staging area (which that epilogue does not use), behind the
-    // BM x (BN + 16) bytes through which its packed output goes
-    int32_t* lnp = stage + BM * (BN + 16) / 4;
-    static_assert(!LN || BM * (BN + 16) / 4 + 2 * BN <= 32 * JC * SP, "room for the LayerNorm constants");
 
     const int64_t c_off = zo * g.sC_o + zi * g.sC_i;
     const int8_t* R = g.R ? g.R + zo * g.sR_o + zi * g.sR_i : nullptr;
@@ -534,10 +470,6 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
             par[c] = pb[q];
             par[BN + c] = pm[q];
             par[2 * BN + c] = ps[q];
-            if (LN) {
-                lnp[c] = pg[q];
-                lnp[BN + c] = pe[q];
-            }
             const int32_t ab = pb[q] < 0 ? -pb[q] : pb[q];
             bad |= (ps[q] < 33 || ps[q] > 62 || ab < 0 || ab >= (1 << 30)) ? 1 : 0;
         }
@@ -568,7 +500,6 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
     // shifted by s-32, every term fits 32 bits, and an element costs one 64-bit multiply-add, a shift and a
     // three-operand clamp.
     const bool fast = !__syncthreads_or(bad) && g.res_fast && (int64_t)g.K * 16129 < (1 << 30);
-    IBERT_TS(3);
 
     const int wrow = wave & 1;
     const int c4 = tid % G4, r0 = tid / G4;                        // lane = (row of the pass, 4-channel group)
@@ -712,7 +643,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
         // [32768,768] outputs: K 768 48.3 -> 43.5 us, K 3072 91.7 -> 89.5 us; the four-wavefront tiles lose by it
         // (128x96: 9.6 -> 11.0 us; 256x128: 66.5 -> 76.4 us), their lanes' own 8-byte stores stay.
         constexpr int SPH = 2 * BN + 8;
-        constexpr bool OST16 = !OUT_I8 && !LN && NW == 8 && BM <= 64 * JC;
+        constexpr bool OST16 = !OUT_I8 && NW == 8 && BM <= 64 * JC;
         static_assert(!OST16 || BM * SPH <= 32 * JC * SP * 4, "the 16-bit staging tile ends where the constants begin");
         const bool use_ost16 = OST16 && g.c16;
         int8_t* const ostage = lds;
@@ -792,160 +723,11 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
             }
         }
     };
-    if constexpr (LN) {
-        // The launcher admits whole tiles with vector-aligned residual and output rows only.
-        const bool has_res = R != nullptr;
-        int32_t s1[FM];
-        uint64_t s2[FM];
-#pragma unroll
-        for (int j = 0; j < FM; ++j) { s1[j] = 0; s2[j] = 0; }
-        const uint32_t* const r_base = resl + (wm0 + frow) * G4 + (wn0 >> 2) + fch;
-        // 1: requantize in place (the accumulator registers now hold the LayerNorm input, clamped to 16 bits), and
-        //    add up the lane's share of each row
-        auto requant_rows = [&](auto fast_tag) __attribute__((always_inline)) {
-            constexpr bool FAST = decltype(fast_tag)::value;
-#pragma clang loop unroll(full)
-            for (int i = 0; i < FN; ++i) {
-                const int cl = wn0 + 16 * i + 4 * fch;
-                const v4i bb = *reinterpret_cast<const v4i*>(par + cl);
-                const v4i mm = *reinterpret_cast<const v4i*>(par + BN + cl);
-                const v4i ss = *reinterpret_cast<const v4i*>(par + 2 * BN + cl);
-                int64_t cc[4];
-                int32_t sh[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    cc[e] = (int64_t)bb[e] * mm[e] + ((int64_t)1 << ((ss[e] - 1) & 63));
-                    sh[e] = (ss[e] - 32) & 31;
-                }
-#pragma clang loop unroll(full)
-                for (int j = 0; j < FM; ++j) {
-                    const uint32_t pk = has_res ? r_base[j * 16 * G4 + i * 4] : 0u;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int32_t r8 = (int32_t)(int8_t)(pk >> (8 * e));
-                        int32_t v;
-                        if (FAST) {
-                            const int64_t p = (int64_t)acc[i][j][e] * mm[e] + cc[e];
-                            v = (int32_t)(p >> 32) >> sh[e];
-                            if (has_res) v += (int32_t)(((int64_t)r8 * g.res_m + g.res_rnd) >> g.res_s);
-                            v = med3_i32(v, clamp_lo, clamp_hi);
-                        } else {
-                            const int32_t a = acc[i][j][e] + bb[e];
-                            const int shq = ss[e] & 63;
-                            int64_t w = ((int64_t)a * mm[e] + (shq > 0 ? (int64_t)1 << (shq - 1) : 0)) >> shq;
-                            if (has_res) w += ((int64_t)r8 * g.res_m + g.res_rnd) >> g.res_s;
-                            v = clamp_i64_to_i32(w, g.out_clamp);
-                        }
-                        acc[i][j][e] = v;
-                        s1[j] += v;                                // out_clamp = 2^15 - 1: a 24-bit square
-                        s2[j] += (uint32_t)smul24(v, v);
-                    }
-                }
-            }
-        };
-        if (fast) requant_rows(std::true_type{}); else requant_rows(std::false_type{});
-        // 2: the four lanes that share a token row combine, and one of them adds the wavefront's share to the row's two
-        //    totals.  Each total is one 64-bit word that also counts its contributions: sum of (x + 2^21) in bits
-        //    [0, 40) with the count from bit 40 up (a wavefront's share of a sum is below 2^21 in magnitude), sum of x^2
-        //    in bits [0, 48) (below 2^40) with the count from bit 48 up.  Integer additions: exact in any order.
-#pragma unroll
-        for (int j = 0; j < FM; ++j) {
-            s1[j] += __shfl_xor(s1[j], 16, 64);
-            s1[j] += __shfl_xor(s1[j], 32, 64);
-            uint32_t lo = (uint32_t)s2[j], hi = (uint32_t)(s2[j] >> 32);   // 64-bit values travel as two dwords
-            uint64_t t = s2[j];
-            t += ((uint64_t)(uint32_t)__shfl_xor((int32_t)hi, 16, 64) << 32) | (uint32_t)__shfl_xor((int32_t)lo, 16, 64);
-            lo = (uint32_t)t; hi = (uint32_t)(t >> 32);
-            t += ((uint64_t)(uint32_t)__shfl_xor((int32_t)hi, 32, 64) << 32) | (uint32_t)__shfl_xor((int32_t)lo, 32, 64);
-            s2[j] = t;
-            if (fch == 0) {
-                const int64_t row = (int64_t)m0 + wm0 + 16 * j + frow;
-                __hip_atomic_fetch_add(g.ln_sum + row, ((unsigned long long)1 << 40) + (unsigned long long)(s1[j] + (1 << 21)),
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_fetch_add(g.ln_sq + row, ((unsigned long long)1 << 48) + (unsigned long long)s2[j],
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-        // 3: wait until every column tile of this tile row has added its two shares per row: the totals themselves say
-        //    so, and the read that finds them complete is the read that is used.  Everything shared goes through
-        //    agent-scope atomics (performed where all workgroups see them), so no cache is written back or invalidated.
-        const uint32_t need = 2u * (uint32_t)g.tiles_n;
-        unsigned long long tsum[FM], tsq[FM];
-        for (int spins = 0;; ++spins) {
-            bool done = true;
-#pragma unroll
-            for (int j = 0; j < FM; ++j) {
-                const int64_t row = (int64_t)m0 + wm0 + 16 * j + frow;
-                tsum[j] = __hip_atomic_load(g.ln_sum + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                tsq[j] = __hip_atomic_load(g.ln_sq + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-#pragma unroll
-            for (int j = 0; j < FM; ++j) done = done && (uint32_t)(tsum[j] >> 40) == need && (uint32_t)(tsq[j] >> 48) == need;
-            if (__builtin_amdgcn_ballot_w64(!done) == 0) break;
-            if (spins > (1 << 16)) {                               // a tenth of a second: never in a healthy run
-                if (lane == 0) __hip_atomic_fetch_or(g.ln_status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                break;
-            }
-            __builtin_amdgcn_s_sleep(2);
-        }
-        // 4: per-row mean and factor.  The four lanes that share rows 16 j + l%16 (j = 0..3) split them: lane l works out
-        //    row l alone (j = l/16) and the results are handed round, so the divisions and the root are done once per row
-        //    and wavefront instead of four times.
-        static_assert(FM == 4, "one row per lane");
-        const uint32_t Nu = (uint32_t)g.N;
-        int32_t mu[FM], fr[FM];
-        bool big;
-        {
-            const unsigned long long ts = fch == 0 ? tsum[0] : (fch == 1 ? tsum[1] : (fch == 2 ? tsum[2] : tsum[3]));
-            const unsigned long long tq = fch == 0 ? tsq[0] : (fch == 1 ? tsq[1] : (fch == 2 ? tsq[2] : tsq[3]));
-            const int32_t S = (int32_t)(uint32_t)(ts & (((unsigned long long)1 << 40) - 1)) - (int32_t)(need << 21);
-            const unsigned long long Q = tq & (((unsigned long long)1 << 48) - 1);
-            const int32_t mu_own = ln_row_mean(S, Nu, g.ln_magic);
-            // sum (x - mu)^2 = Q - 2 mu S + N mu^2: exact in 64 bits, never negative
-            const int64_t ssd = (int64_t)Q - 2 * (int64_t)mu_own * S + (int64_t)Nu * mu_own * mu_own;
-            const int32_t f_own = ln_row_factor((uint64_t)ssd, Nu, g.ln_magic);
-            big = f_own >= (1 << 23);
-#pragma unroll
-            for (int j = 0; j < FM; ++j) {
-                mu[j] = __shfl(mu_own, 16 * j + frow, 64);
-                fr[j] = __shfl(f_own, 16 * j + frow, 64);
-            }
-        }
-        const bool f24 = __builtin_amdgcn_ballot_w64(big) == 0;   // else sigma <= 2 somewhere: full 32-bit multiplies
-        // 5: normalize, pack, and go through LDS once so that the stores are whole 16-byte pieces of rows
-        constexpr int SPB = BN + 16;
-        int8_t* const ostage = lds;
-        const int32_t lrnd = 1 << (g.ln_shift - 1);
-#pragma clang loop unroll(full)
-        for (int i = 0; i < FN; ++i) {
-            const int cl = wn0 + 16 * i + 4 * fch;
-            const v4i gm = *reinterpret_cast<const v4i*>(lnp + cl);
-            v4i bt = *reinterpret_cast<const v4i*>(lnp + BN + cl);
-            bt += lrnd;
-#pragma clang loop unroll(full)
-            for (int j = 0; j < FM; ++j) {
-                int32_t o[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int32_t d = acc[i][j][e] - mu[j];
-                    const int32_t nn = (f24 ? smul24(d, fr[j]) : d * fr[j]) >> 14;
-                    o[e] = med3_i32(smad24(nn, gm[e], bt[e]) >> g.ln_shift, -127, 127);
-                }
-                *reinterpret_cast<uint32_t*>(ostage + (wm0 + 16 * j + frow) * SPB + wn0 + 16 * i + 4 * fch) = pack4_perm(o[0], o[1], o[2], o[3]);
-            }
-        }
-        __syncthreads();
-        constexpr int C16 = BN / 16, CH = BM * C16;
-        int8_t* const yt = g.ln_y + (int64_t)m0 * g.ln_ldy + n0;
-#pragma unroll
-        for (int q0 = 0; q0 < CH; q0 += NT) {
-            const int q = q0 + tid;
-            if (CH % NT == 0 || q < CH) {
-                const int row = q / C16, c16 = q - row * C16;
-                *reinterpret_cast<v4i*>(yt + (int64_t)row * g.ln_ldy + c16 * 16) = *reinterpret_cast<const v4i*>(ostage + row * SPB + c16 * 16);
-            }
-        }
-    } else if (interior && fast) {
+    if (g.path_word && blockIdx.x == 0 && tid == 0)
+        *g.path_word = !interior ? IBERT_EPILOGUE_EDGE
+                                 : (!fast ? IBERT_EPILOGUE_STAGED
+                                          : (GELU && g.gelu_lut_n > 0 ? IBERT_EPILOGUE_DIRECT_GELU_TABLE : IBERT_EPILOGUE_DIRECT));
+    if (interior && fast) {
         // (GELU excludes a residual; without a table -- it did not fit, or the parameters are unusual -- the
         // arithmetic form runs, with the choice between its two variants made per value)
         if (GELU && g.gelu_lut_n > 0) finish_direct(std::false_type{}, std::false_type{}, std::true_type{});
@@ -961,20 +743,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
             for (int i = 0; i < FN; ++i)
                 *reinterpret_cast<v4i*>(stage + ((wrow * JC + jj) * 16 + frow) * SP + wn0 + i * 16 + fch * 4) = acc[i][jc * JC + jj];
         __syncthreads();
-        if (jc == 0) IBERT_TS(5);
         if (!interior) finish_edge(jc * JC);
         else if (fast) finish_interior(jc * JC, std::true_type{});
         else finish_interior(jc * JC, std::false_type{});
-        if (jc == 0) IBERT_TS(6);
     }
-#ifdef IBERT_KERNEL_TIMING
-    IBERT_TS(4);
-    if (g.dbg && lane == 0) {
-        long long* o = g.dbg + ((long long)blockIdx.x * NW + wave) * 8;
-        for (int i = 0; i < 8; ++i) o[i] = tstamp[i];
-    }
-#endif
-#undef IBERT_TS
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1064,12 +836,10 @@ static const GemmConfig kConfigs[] = {      // index = configuration number of i
     {64, 128, 128, 2, true},
 };
 constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
-#ifdef IBERT_KERNEL_TIMING
-static long long* g_dbg_buf = nullptr;
-#endif
 static int g_config_override = -1;
+static uint32_t* g_path_word = nullptr;
 
-template <int BM, int BN, int BK, int RING, bool TW = false, bool DMA = false, bool GELU = false, bool LN = false, int NW = 4>
+template <int BM, int BN, int BK, int RING, bool TW = false, bool DMA = false, bool GELU = false, int NW = 4>
 static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
 {
     g.tiles_m = (g.M + BM - 1) / BM;
@@ -1090,7 +860,7 @@ static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
     }
 #define IBERT_GEMM_LAUNCH(I8_, KT_)                                                                       \
     do {                                                                                                  \
-        auto kern = gemm_nt_mfma_kernel<BM, BN, BK, RING, I8_, KT_, TW, DMA, GELU && I8_, LN && !I8_, NW>;   \
+        auto kern = gemm_nt_mfma_kernel<BM, BN, BK, RING, I8_, KT_, TW, DMA, GELU && I8_, NW>;               \
         static size_t attr_bytes = 0;                                                                     \
         if (lds_bytes > attr_bytes) {                                                                     \
             IBERT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                      \
@@ -1102,11 +872,6 @@ static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
     if constexpr (GELU) {
         if (!i8 || g.K % BK != 0) return IBERT_ERR_NOT_IMPLEMENTED;
         IBERT_GEMM_LAUNCH(true, 0);
-    } else if constexpr (LN) {
-        if (i8 || g.K % BK != 0) return IBERT_ERR_NOT_IMPLEMENTED;
-        // tile rows must not straddle the XCD runs: the column tiles of a row start back to back
-        if (g.xcd_chunk % g.tiles_n != 0) g.xcd_chunk = 0;
-        IBERT_GEMM_LAUNCH(false, 0);
     } else if (g.K % BK == 0) {
         if (i8) IBERT_GEMM_LAUNCH(true, 0); else IBERT_GEMM_LAUNCH(false, 0);
     } else if constexpr (!DMA) {
@@ -1120,9 +885,9 @@ static int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
     static char label[2][2][96];
     char* l = label[i8 ? 1 : 0][g.K % BK == 0 ? 0 : 1];
     if (!l[0])
-        std::snprintf(l, sizeof label[0][0], "gemm_nt_mfma_kernel<%d, %d, %d, %d, %s, %d, %s, %s, %s, %s, %d>", BM, BN, BK, RING,
+        std::snprintf(l, sizeof label[0][0], "gemm_nt_mfma_kernel<%d, %d, %d, %d, %s, %d, %s, %s, %s, %d>", BM, BN, BK, RING,
                       i8 ? "true" : "false", g.K % BK == 0 ? 0 : 1, TW ? "true" : "false", DMA ? "true" : "false",
-                      GELU ? "true" : "false", LN ? "true" : "false", NW);
+                      GELU ? "true" : "false", NW);
     g_last_kernel = l;
     return IBERT_OK;
 }
@@ -1200,7 +965,7 @@ static bool dma_ok(const ibert_gemm_desc& d, int bm, int bn)
 // so that one workgroup's requantization overlaps another's MFMAs.
 // Everything else takes the register-ring loader: 128x128 tiles with a 64-wide K step while that gives every
 // CU something to do, below that 64x64 tiles.
-static int choose_config(const ibert_gemm_desc& d, int64_t nb, bool gelu, bool ln)
+static int choose_config(const ibert_gemm_desc& d, int64_t nb, bool gelu)
 {
     if (g_config_override >= 0 && g_config_override < kNumConfigs) return g_config_override;
     auto tiles = [&](int bm, int bn) -> int64_t { return dma_ok(d, bm, bn) ? (int64_t)(d.M / bm) * (d.N / bn) * nb : 0; };
@@ -1218,16 +983,15 @@ static int choose_config(const ibert_gemm_desc& d, int64_t nb, bool gelu, bool l
     if (tiles(128, 96) >= 256) {
         // (exactly one 128x96 tile per CU and a 16- or 32-bit output: 64x96 tiles, three or four of which share a CU, so
         //  that one's epilogue overlaps another's loop -- inside the encoder S5 of Base 9.7 -> 8.9 us, S9 17.9 -> 17.3 us;
-        //  a fourth LDS stage leaves room for one workgroup per CU only and loses, 24 us.  The LayerNorm epilogue keeps
-        //  the 128-row tiles: it needs few, large contributions per row.)
-        if (tiles(128, 96) <= 256 && d.out_dtype != IBERT_I8 && !gelu && !ln) return d.K >= 2048 ? 17 : 18;
+        //  a fourth LDS stage leaves room for one workgroup per CU only and loses, 24 us.)
+        if (tiles(128, 96) <= 256 && d.out_dtype != IBERT_I8 && !gelu) return d.K >= 2048 ? 17 : 18;
         return tiles(128, 96) <= 256 && d.K >= 2048 ? 11 : 9;
     }
     // (eight wavefronts for INT8 outputs: S7+S8 of Large 34.7 -> 32.5 us; INT32 outputs lose 5 % with them)
     if (tiles(256, 128) >= 448) return (gelu || d.out_dtype == IBERT_I8) ? 14 : 10;
     if (tiles(128, 128) >= 128) {
         // (likewise 64x128 tiles for a short K: S5 of Large 14.4 -> 12.9 us; with K 4096 they lose, 25.9 -> 30 us)
-        if (tiles(128, 128) <= 256 && d.K < 2048 && d.out_dtype != IBERT_I8 && !gelu && !ln) return 19;
+        if (tiles(128, 128) <= 256 && d.K < 2048 && d.out_dtype != IBERT_I8 && !gelu) return 19;
         return tiles(128, 128) <= 256 && d.K >= 2048 ? 12 : 7;
     }
     const int64_t tiles128 = (((int64_t)d.M + 127) / 128) * (((int64_t)d.N + 127) / 128) * nb;
@@ -1241,20 +1005,13 @@ static int choose_config(const ibert_gemm_desc& d, int64_t nb, bool gelu, bool l
 
 // gelu != nullptr asks for the GELU epilogue (INT8 output, no residual; out_clamp must be gelu->q_max): only the
 // direct-to-LDS tiles carry it, any other problem returns IBERT_ERR_NOT_IMPLEMENTED without launching.
-// ln != nullptr asks for the LayerNorm epilogue (INT32 result at out_clamp = 2^15 - 1, one problem, N <= 1024; C is
-// not written): only the direct-to-LDS 128-row tiles carry it, and only where such a tile is the choice for the
-// problem anyway; otherwise IBERT_ERR_NOT_IMPLEMENTED, nothing launched.
-// zero != nullptr: words the kernel clears while it starts (any MFMA-path launch; else IBERT_ERR_NOT_IMPLEMENTED).
 int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, const int32_t* bias,
                 const int32_t* mult, const int32_t* shift, const int8_t* residual, void* C, hipStream_t stream,
-                const ibert_gelu_params* gelu, const LnFuse* ln, const ZeroReq* zero)
+                const ibert_gelu_params* gelu)
 {
     const int64_t nb = (int64_t)d.batch_outer * d.batch_inner;
     if (nb == 0 || d.M == 0 || d.N == 0) return IBERT_OK;
     GemmArgs g;
-#ifdef IBERT_KERNEL_TIMING
-    g.dbg = g_dbg_buf;
-#endif
     g.A = A; g.W = W; g.bias = bias; g.mult = mult; g.shift = shift; g.R = residual; g.C = C;
     g.M = d.M; g.N = d.N; g.K = d.K;
     g.batch_inner = d.batch_inner; g.nbatch = (int32_t)nb;
@@ -1273,6 +1030,7 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
     g.res_rnd = (residual && d.residual_dy.s >= 1 && d.residual_dy.s <= 62) ? ((int64_t)1 << (d.residual_dy.s - 1)) : 0;
     const bool i8 = d.out_dtype == IBERT_I8;
     g.c16 = d.out_dtype == IBERT_I16 ? 1 : 0;
+    g.path_word = g_path_word;
     g.gelu_fast = 0;
     g.gelu = GeluConst{0, 0, 0, 0, 0, 0};
     g.gelu_lut_lo = g.gelu_lut_n = 0;
@@ -1282,48 +1040,17 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
         g.gelu_fast = gelu_fast_ok(*gelu) ? 1 : 0;
         gelu_table_range(*gelu, &g.gelu_lut_lo, &g.gelu_lut_n);
     }
-    g.ln_gamma = g.ln_beta = nullptr; g.ln_y = nullptr; g.ln_ldy = 0; g.ln_sum = nullptr; g.ln_sq = nullptr;
-    g.ln_status = nullptr; g.ln_shift = 1; g.ln_magic = 0;
-    g.zero_p = zero ? zero->p : nullptr;
-    g.zero_words = zero ? zero->words : 0;
-    if (ln) {
-        // (N / 96 <= 10 column tiles: the contribution counts stay far inside their bit fields)
-        if (gelu || i8 || nb != 1 || d.out_clamp != 32767 || d.N > 1024 || d.trans_w) return IBERT_ERR_NOT_IMPLEMENTED;
-        if (!aligned(ln->y, 16) || ln->ldy % 16 != 0 || !aligned(ln->gamma_q, 4) || (residual && !(aligned(residual, 16) && d.ldr % 16 == 0)))
-            return IBERT_ERR_NOT_IMPLEMENTED;
-        g.ln_gamma = ln->gamma_q; g.ln_beta = ln->beta_q; g.ln_y = ln->y; g.ln_ldy = ln->ldy;
-        g.ln_sum = ln->sum; g.ln_sq = ln->sq; g.ln_status = ln->status;
-        g.ln_shift = ln->shift; g.ln_magic = ln_magic_for(d.N);
-    }
-    g.c_vec = ln ? 1 : aligned(C, i8 ? 4 : (g.c16 ? 8 : 16)) && d.ldc % 4 == 0 && d.strideC_outer % 4 == 0 && d.strideC_inner % 4 == 0;
+    g.c_vec = aligned(C, i8 ? 4 : (g.c16 ? 8 : 16)) && d.ldc % 4 == 0 && d.strideC_outer % 4 == 0 && d.strideC_inner % 4 == 0;
     g.c_vec16 = i8 && aligned(C, 16) && d.ldc % 16 == 0 && d.strideC_outer % 16 == 0 && d.strideC_inner % 16 == 0;
     g.r_vec = residual && aligned(residual, 16) && d.ldr % 16 == 0 && d.strideR_outer % 16 == 0 && d.strideR_inner % 16 == 0;
 
     const bool fast = d.trans_w == 0 && d.K > 0 && aligned(A, 16) && aligned(W, 16) && d.lda % 16 == 0 && d.ldw % 16 == 0 &&
                       d.strideA_outer % 16 == 0 && d.strideA_inner % 16 == 0 && d.strideW_outer % 16 == 0 &&
                       d.strideW_inner % 16 == 0;
-    if ((gelu || ln) && !(fast && d.K % 16 == 0)) return IBERT_ERR_NOT_IMPLEMENTED;
-    if (zero && !(fast && d.K % 16 == 0)) return IBERT_ERR_NOT_IMPLEMENTED;
+    if (gelu && !(fast && d.K % 16 == 0)) return IBERT_ERR_NOT_IMPLEMENTED;
     if (fast) {
         if (d.K % 16 != 0) return launch_tail(g, i8, stream);       // bytewise K tail
-        const int cfg = choose_config(d, nb, gelu != nullptr, ln != nullptr);
-        if (ln) {
-            g.ldc = d.N;                                            // (unused: keeps the epilogue's row offsets small)
-            // Only where a 128-row tile is the choice for this problem anyway: measured, the exchange between the column
-            // tiles costs 4-5 us, which beats a LayerNorm kernel of its own when every CU has one tile (Base and Large
-            // at 4096 tokens), and loses both when the tiles are few (a smaller MatMul tile and a 4 us LayerNorm do
-            // better) and when they are many (bigger tiles do better, and waiting tiles hold their CU).
-            const bool w96 = dma_ok(d, 128, 96), w128 = dma_ok(d, 128, 128);
-            const int lcfg = (cfg == 7 || cfg == 9 || cfg == 11 || cfg == 12) ? cfg : -1;
-            switch (lcfg) {
-                case 7: if (w128) return launch_mfma<128, 128, 128, 2, false, true, false, true>(g, i8, stream); break;
-                case 9: if (w96) return launch_mfma<128, 96, 128, 2, false, true, false, true>(g, i8, stream); break;
-                case 11: if (w96) return launch_mfma<128, 96, 128, 3, false, true, false, true>(g, i8, stream); break;
-                case 12: if (w128) return launch_mfma<128, 128, 128, 3, false, true, false, true>(g, i8, stream); break;
-                default: break;
-            }
-            return IBERT_ERR_NOT_IMPLEMENTED;
-        }
+        const int cfg = choose_config(d, nb, gelu != nullptr);
         if (gelu) {
             switch (cfg) {
                 case 3: return launch_mfma<64, 64, 128, 3, false, false, true>(g, i8, stream);
@@ -1332,8 +1059,8 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
                 case 7: if (dma_ok(d, 128, 128)) return launch_mfma<128, 128, 128, 2, false, true, true>(g, i8, stream); break;
                 case 9: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 2, false, true, true>(g, i8, stream); break;
                 case 10: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 2, false, true, true>(g, i8, stream); break;
-                case 13: if (dma_ok(d, 256, 192)) return launch_mfma<256, 192, 128, 2, false, true, true, false, 8>(g, i8, stream); break;
-                case 14: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 2, false, true, true, false, 8>(g, i8, stream); break;
+                case 13: if (dma_ok(d, 256, 192)) return launch_mfma<256, 192, 128, 2, false, true, true, 8>(g, i8, stream); break;
+                case 14: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 2, false, true, true, 8>(g, i8, stream); break;
                 default: break;
             }
             return IBERT_ERR_NOT_IMPLEMENTED;
@@ -1352,10 +1079,10 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
             case 10: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 2, false, true>(g, i8, stream); break;
             case 11: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 3, false, true>(g, i8, stream); break;
             case 12: if (dma_ok(d, 128, 128)) return launch_mfma<128, 128, 128, 3, false, true>(g, i8, stream); break;
-            case 13: if (dma_ok(d, 256, 192)) return launch_mfma<256, 192, 128, 2, false, true, false, false, 8>(g, i8, stream); break;
-            case 14: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 2, false, true, false, false, 8>(g, i8, stream); break;
+            case 13: if (dma_ok(d, 256, 192)) return launch_mfma<256, 192, 128, 2, false, true, false, 8>(g, i8, stream); break;
+            case 14: if (dma_ok(d, 256, 128)) return launch_mfma<256, 128, 128, 2, false, true, false, 8>(g, i8, stream); break;
             case 15: return launch_mfma<32, 32, 128, 4>(g, i8, stream);
-            case 16: if (dma_ok(d, 256, 256)) return launch_mfma<256, 256, 128, 2, false, true, false, false, 8>(g, i8, stream); break;
+            case 16: if (dma_ok(d, 256, 256)) return launch_mfma<256, 256, 128, 2, false, true, false, 8>(g, i8, stream); break;
             case 17: if (dma_ok(d, 64, 96)) return launch_mfma<64, 96, 128, 3, false, true>(g, i8, stream); break;
             case 18: if (dma_ok(d, 64, 96)) return launch_mfma<64, 96, 128, 2, false, true>(g, i8, stream); break;
             case 19: if (dma_ok(d, 64, 128)) return launch_mfma<64, 128, 128, 2, false, true>(g, i8, stream); break;
@@ -1367,7 +1094,6 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
                          aligned(W, 4) && d.lda % 16 == 0 && d.ldw % 4 == 0 && d.strideA_outer % 16 == 0 &&
                          d.strideA_inner % 16 == 0 && d.strideW_outer % 4 == 0 && d.strideW_inner % 4 == 0;
     if (fast_tw) {
-        if (zero) return IBERT_ERR_NOT_IMPLEMENTED;
         if (d.N <= 64) return launch_mfma<128, 64, 64, 2, true>(g, i8, stream);
         return launch_mfma<128, 128, 64, 2, true>(g, i8, stream);
     }
@@ -1410,15 +1136,14 @@ int launch_gemm_gelu(const ibert_gemm_desc& d0, const int8_t* A, const int8_t* W
 
 }  // namespace ibert
 
-#ifdef IBERT_KERNEL_TIMING
-extern "C" void ibert_debug_timing_buffer(void* p) { ibert::g_dbg_buf = (long long*)p; }
-#endif
 
 extern "C" int ibert_gemm_config_override(int32_t config)
 {
     ibert::g_config_override = config;
     return ibert::kNumConfigs;
 }
+
+extern "C" void ibert_gemm_epilogue_record(uint32_t* device_word) { ibert::g_path_word = device_word; }
 
 extern "C" int ibert_gemm_i8_requant(const ibert_gemm_desc* desc, const int8_t* A, const int8_t* W,
                                      const int32_t* bias, const int32_t* mult, const int32_t* shift,

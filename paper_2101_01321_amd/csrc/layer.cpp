@@ -43,26 +43,6 @@ static double gemm_bytes(double M, double N, double K, double batch, double out_
            (w_shared ? N * K : 0.0) + 12.0 * N;
 }
 
-// Fusions the layer applies (bit 0: GELU inside the FFN up-projection; bit 1: scores, Softmax and context in one
-// kernel; bit 2: LayerNorm inside the output projection and inside the FFN down-projection).  Results do not depend
-// on it.
-static int32_t g_fusion = 11;
-
-// Row statistics of the LayerNorm epilogue for `rows` tokens: two 64-bit words a row (sum, sum of squares, each with
-// its count of contributions), the sums of squares first; `words` 32-bit words in all.
-struct LnStats {
-    size_t words;
-    size_t sq_off, sum_off;               // in bytes from the start of a set
-};
-static LnStats ln_stats_shape(size_t rows)
-{
-    LnStats s;
-    s.sq_off = 0;
-    s.sum_off = 8 * rows;
-    s.words = 4 * rows;
-    return s;
-}
-
 static int layout(int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn,
                   ibert_layer_workspace_layout* o)
 {
@@ -78,8 +58,6 @@ static int layout(int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int
     o->f1 = p;     p += align_up(T * F * 4);
     o->g = p;      p += align_up(T * F);
     o->r2 = p;     p += align_up(T * H * 4);
-    // two sets of LayerNorm row statistics (one per LayerNorm of the layer) and a status word behind them
-    o->ln_stats = p; p += align_up(2 * ln_stats_shape(T).words * 4 + 4);
     o->total = p;
     return IBERT_OK;
 }
@@ -166,20 +144,9 @@ static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, c
     int8_t* g = reinterpret_cast<int8_t*>(ws + lo.g);
     int32_t* r2 = reinterpret_cast<int32_t*>(ws + lo.r2);
 
-    // LayerNorm in the epilogue of steps 5 and 9: each needs its set of row statistics zero when it starts; the
-    // set of step 5 is cleared by step 1's kernel and the set of step 9 by step 5's, so nothing carries over
-    // between calls.  Whether a step fuses is only known once its launch accepts; a cleared set nobody uses is harmless.
-    const LnStats st = ln_stats_shape((size_t)T);
-    char* const set_a = ws + lo.ln_stats;
-    char* const set_b = set_a + st.words * 4;
-    uint32_t* const ln_status = reinterpret_cast<uint32_t*>(set_b + st.words * 4);
-    const bool try_ln = (g_fusion & 4) != 0 && H <= 1024;
-    const ZeroReq zero_a{reinterpret_cast<uint32_t*>(set_a), (int64_t)st.words};
-    const ZeroReq zero_b{reinterpret_cast<uint32_t*>(set_b), (int64_t)st.words};
-    auto ln_fuse = [&](char* set, const int32_t* gq, const int32_t* bq, int32_t shift, int8_t* out) {
-        return LnFuse{gq, bq, shift, out, H, reinterpret_cast<unsigned long long*>(set + st.sum_off),
-                      reinterpret_cast<unsigned long long*>(set + st.sq_off), ln_status};
-    };
+    const bool fuse_gelu = !(q.route & IBERT_ROUTE_SEPARATE_GELU);
+    const bool fuse_attention = !(q.route & IBERT_ROUTE_SEPARATE_ATTENTION);
+    const bool half = !(q.route & IBERT_ROUTE_I32_LN_INPUT);       // r1 / r2 as int16: half the bytes both ways
 
     ibert_gemm_desc d;
     int rc;
@@ -190,44 +157,21 @@ static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, c
         rc = launch_gemm(d, A_, W_, b_, m_, s_, R_, C_, stream);                         \
         if (rc) return rc;                                                               \
     } while (0)
-    // A MatMul followed by LayerNorm: one kernel where the launch accepts it (then the INT32 tensor R32_ is never
-    // written), else the two steps.  ZERO_: statistics this launch clears for the next such pair (or nullptr).
-#define RUN_GEMM_LN(STEP_, A_, W_, b_, m_, s_, R_, R32_, SET_, GQ_, BQ_, SH_, OUT_, ZERO_, OPS_, K_)            \
+    // A projection with residual (INT32 at the LayerNorm input scale, stored in 16 or 32 bits) and its LayerNorm.
+#define RUN_GEMM_LN(STEP_, A_, W_, b_, m_, s_, R_, R32_, GQ_, BQ_, SH_, OUT_, OPS_, K_)                        \
     do {                                                                                                     \
-        rc = check_gemm(d, A_, W_, m_, s_, R_, R32_);                                                        \
+        if (half) d.out_dtype = IBERT_I16;                                                                   \
+        prof_before(stream);                                                                                 \
+        RUN_GEMM(A_, W_, b_, m_, s_, R_, R32_);                                                              \
+        prof_after(stream, STEP_, OPS_, gemm_bytes(T, H, K_, 1, half ? 2 : 4, true, true));                  \
+        prof_before(stream);                                                                                 \
+        if (half)                                                                                            \
+            rc = launch_layernorm16(reinterpret_cast<const int16_t*>(R32_), OUT_, T, (int32_t)H, H, H,       \
+                                    GQ_, BQ_, SH_, stream);                                                  \
+        else                                                                                                 \
+            rc = launch_layernorm(R32_, OUT_, T, (int32_t)H, H, H, GQ_, BQ_, SH_, stream);                   \
         if (rc) return rc;                                                                                   \
-        bool fused_ln = false;                                                                               \
-        if (try_ln && ln_ready) {                                                                            \
-            const LnFuse lf = ln_fuse(SET_, GQ_, BQ_, SH_, OUT_);                                            \
-            prof_before(stream);                                                                             \
-            rc = launch_gemm(d, A_, W_, b_, m_, s_, R_, R32_, stream, nullptr, &lf, ZERO_);                  \
-            if (rc == IBERT_OK) {                                                                            \
-                fused_ln = true;                                                                             \
-                prof_after(stream, STEP_, OPS_, gemm_bytes(T, H, K_, 1, 1, true, true));                     \
-            } else if (rc != IBERT_ERR_NOT_IMPLEMENTED) {                                                    \
-                return rc;                                                                                   \
-            }                                                                                                \
-        }                                                                                                    \
-        if (!fused_ln) {                                                                                     \
-            const bool half = (g_fusion & 8) != 0;           /* r as int16: half the bytes both ways */      \
-            if (half) d.out_dtype = IBERT_I16;                                                               \
-            prof_before(stream);                                                                             \
-            rc = launch_gemm(d, A_, W_, b_, m_, s_, R_, R32_, stream, nullptr, nullptr, ZERO_);              \
-            if (rc == IBERT_ERR_NOT_IMPLEMENTED && (ZERO_) != nullptr) {                                     \
-                zero_ok = false;                                                                             \
-                rc = launch_gemm(d, A_, W_, b_, m_, s_, R_, R32_, stream);                                   \
-            }                                                                                                \
-            if (rc) return rc;                                                                               \
-            prof_after(stream, STEP_, OPS_, gemm_bytes(T, H, K_, 1, half ? 2 : 4, true, true));              \
-            prof_before(stream);                                                                             \
-            if (half)                                                                                        \
-                rc = launch_layernorm16(reinterpret_cast<const int16_t*>(R32_), OUT_, T, (int32_t)H, H, H,   \
-                                        GQ_, BQ_, SH_, stream);                                              \
-            else                                                                                             \
-                rc = launch_layernorm(R32_, OUT_, T, (int32_t)H, H, H, GQ_, BQ_, SH_, stream);               \
-            if (rc) return rc;                                                                               \
-            prof_after(stream, (STEP_) + 1, 0.0, (half ? 3.0 : 5.0) * T * H);                                \
-        }                                                                                                    \
+        prof_after(stream, (STEP_) + 1, 0.0, (half ? 3.0 : 5.0) * T * H);                                    \
     } while (0)
 
     // 1: QKV projection, one GEMM with N = 3H
@@ -235,23 +179,12 @@ static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, c
     d.M = (int32_t)T; d.N = (int32_t)(3 * H); d.K = (int32_t)H; d.batch_outer = d.batch_inner = 1;
     d.lda = H; d.ldw = H; d.ldc = 3 * H; d.per_channel = 1; d.out_dtype = IBERT_I8; d.out_clamp = 127;
     prof_before(stream);
-    bool ln_ready = false;          // the statistics of the next LayerNorm epilogue have been cleared
-    bool zero_ok = true;
-    rc = check_gemm(d, x, w.w_qkv, w.m_qkv, w.s_qkv, nullptr, qkv);
-    if (rc) return rc;
-    rc = try_ln ? launch_gemm(d, x, w.w_qkv, w.b_qkv, w.m_qkv, w.s_qkv, nullptr, qkv, stream, nullptr, nullptr, &zero_a)
-                : IBERT_ERR_NOT_IMPLEMENTED;
-    if (rc == IBERT_OK) {
-        ln_ready = true;
-    } else if (rc == IBERT_ERR_NOT_IMPLEMENTED) {
-        rc = launch_gemm(d, x, w.w_qkv, w.b_qkv, w.m_qkv, w.s_qkv, nullptr, qkv, stream);
-    }
-    if (rc) return rc;
+    RUN_GEMM(x, w.w_qkv, w.b_qkv, w.m_qkv, w.s_qkv, nullptr, qkv);
     prof_after(stream, 1, 2.0 * T * 3 * H * H, gemm_bytes(T, 3 * H, H, 1, 1, false, true));
 
     // 2-4: attention scores, Softmax, context
     rc = run_attention(qkv, scores, probs, ctx, B, L, H, nh, q.scores_dy, q.softmax, q.ctx_dy, key_lens,
-                       (g_fusion & 2) != 0, stream);
+                       fuse_attention, stream);
     if (rc) return rc;
 
     // 5: output projection + residual x, INT32 at the LayerNorm input scale
@@ -259,17 +192,15 @@ static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, c
     d.M = (int32_t)T; d.N = (int32_t)H; d.K = (int32_t)H; d.batch_outer = d.batch_inner = 1;
     d.lda = H; d.ldw = H; d.ldc = H; d.ldr = H; d.per_channel = 1; d.out_dtype = IBERT_I32; d.out_clamp = 32767;
     d.residual_dy = q.res1_dy;
-    // (+ 6: LayerNorm, in the same kernel where that is possible; the launch also clears the statistics of step 9)
-    RUN_GEMM_LN(5, ctx, w.w_o, w.b_o, w.m_o, w.s_o, x, r1, set_a, w.ln1_gamma_q, w.ln1_beta_q, q.ln1_shift, h1,
-                (try_ln ? &zero_b : nullptr), 2.0 * T * H * H, H);
-    ln_ready = try_ln && zero_ok;
+    // (+ 6: LayerNorm)
+    RUN_GEMM_LN(5, ctx, w.w_o, w.b_o, w.m_o, w.s_o, x, r1, w.ln1_gamma_q, w.ln1_beta_q, q.ln1_shift, h1, 2.0 * T * H * H, H);
 
     // 7: FFN up-projection, INT32 at the GELU input scale
     std::memset(&d, 0, sizeof d);
     d.M = (int32_t)T; d.N = (int32_t)F; d.K = (int32_t)H; d.batch_outer = d.batch_inner = 1;
     d.lda = H; d.ldw = H; d.ldc = F; d.per_channel = 1; d.out_dtype = IBERT_I32; d.out_clamp = q.gelu.q_max;
     bool fused78 = false;
-    if (g_fusion & 1) {
+    if (fuse_gelu) {
         // 7+8 in one kernel when a tile fits: f1 is then never written
         rc = check_gemm(d, h1, w.w_1, w.m_1, w.s_1, nullptr, g);
         if (rc) return rc;
@@ -302,8 +233,7 @@ static int run_layer(const ibert_layer_weights& w, const ibert_layer_quant& q, c
     d.lda = F; d.ldw = F; d.ldc = H; d.ldr = H; d.per_channel = 1; d.out_dtype = IBERT_I32; d.out_clamp = 32767;
     d.residual_dy = q.res2_dy;
     // (+ 10: LayerNorm)
-    RUN_GEMM_LN(9, g, w.w_2, w.b_2, w.m_2, w.s_2, h1, r2, set_b, w.ln2_gamma_q, w.ln2_beta_q, q.ln2_shift, y,
-                (const ZeroReq*)nullptr, 2.0 * T * H * F, F);
+    RUN_GEMM_LN(9, g, w.w_2, w.b_2, w.m_2, w.s_2, h1, r2, w.ln2_gamma_q, w.ln2_beta_q, q.ln2_shift, y, 2.0 * T * H * F, F);
     return IBERT_OK;
 #undef RUN_GEMM
 #undef RUN_GEMM_LN
@@ -331,13 +261,6 @@ static int check_layer(const ibert_layer_weights& w, const ibert_layer_quant& q,
 }  // namespace ibert
 
 extern "C" {
-
-int ibert_set_fusion(int32_t flags)
-{
-    const int32_t old = ibert::g_fusion;
-    if (flags >= 0) ibert::g_fusion = flags & 15;
-    return old;
-}
 
 size_t ibert_attention_scratch_bytes(int32_t batch, int32_t seq, int32_t heads)
 {
@@ -376,49 +299,7 @@ int ibert_attention_masked_i(const int8_t* qkv, int8_t* ctx, int32_t batch, int3
         probs = static_cast<int8_t*>(scratch) + align_up(n * 4);
     }
     return run_attention(qkv, scores, probs, ctx, batch, seq, hidden, heads, *scores_dy, *softmax, *ctx_dy, key_lens,
-                         (g_fusion & 2) != 0, (hipStream_t)stream);
-}
-
-size_t ibert_gemm_layernorm_scratch_bytes(int32_t M, int32_t N)
-{
-    if (M < 0 || N < 0) return 0;
-    return ibert::align_up((size_t)M * N * 4) + ibert::align_up(ibert::ln_stats_shape((size_t)M).words * 4 + 4);
-}
-
-int ibert_gemm_i8_layernorm(const ibert_gemm_desc* desc, const int8_t* A, const int8_t* W, const int32_t* bias,
-                            const int32_t* mult, const int32_t* shift, const int8_t* residual, const int32_t* gamma_q,
-                            const int32_t* beta_q, int32_t ln_shift, int8_t* y, int64_t ldy, void* scratch,
-                            size_t scratch_bytes, void* stream_)
-{
-    using namespace ibert;
-    hipStream_t stream = (hipStream_t)stream_;
-    if (!desc) return IBERT_ERR_NULL;
-    ibert_gemm_desc d = *desc;
-    if (d.batch_outer != 1 || d.batch_inner != 1 || d.out_dtype != IBERT_I32 || d.out_clamp != 32767) return IBERT_ERR_SHAPE;
-    if (ldy < d.N) return IBERT_ERR_SHAPE;
-    int rc = check_layernorm(d.N, ln_shift);
-    if (rc) return rc;
-    if (!scratch || scratch_bytes < ibert_gemm_layernorm_scratch_bytes(d.M, d.N) || ((uintptr_t)scratch & 255)) return IBERT_ERR_WORKSPACE;
-    int32_t* r32 = static_cast<int32_t*>(scratch);
-    d.ldc = d.N;
-    rc = check_gemm(d, A, W, mult, shift, residual, r32);
-    if (rc) return rc;
-    if (d.M == 0) return IBERT_OK;
-    if (!gamma_q || !beta_q || !y) return IBERT_ERR_NULL;
-    const LnStats st = ln_stats_shape((size_t)d.M);
-    char* set = static_cast<char*>(scratch) + align_up((size_t)d.M * d.N * 4);
-    uint32_t* status = reinterpret_cast<uint32_t*>(set + st.words * 4);
-    if (g_fusion & 4) {
-        const LnFuse lf{gamma_q, beta_q, ln_shift, y, ldy, reinterpret_cast<unsigned long long*>(set + st.sum_off),
-                        reinterpret_cast<unsigned long long*>(set + st.sq_off), status};
-        rc = launch_zero_words(reinterpret_cast<uint32_t*>(set), (int64_t)st.words + 1, stream);   // statistics and status
-        if (rc) return rc;
-        rc = launch_gemm(d, A, W, bias, mult, shift, residual, r32, stream, nullptr, &lf, nullptr);
-        if (rc != IBERT_ERR_NOT_IMPLEMENTED) return rc;
-    }
-    rc = launch_gemm(d, A, W, bias, mult, shift, residual, r32, stream);
-    if (rc) return rc;
-    return launch_layernorm(r32, y, d.M, d.N, d.N, ldy, gamma_q, beta_q, ln_shift, stream);
+                         true, (hipStream_t)stream);
 }
 
 int ibert_profile_begin(int32_t capacity)

@@ -1,9 +1,9 @@
 // Integer-only LayerNorm (Sec. 3.6, Eq. 15, Alg. 4).  HBM-bound: 4 bytes in, 1 byte out per element.
 //
 // A row (C <= 1024 int32) is owned by LPR lanes of one wavefront and kept in registers, so HBM is
-// read once.  Sum and sum of squared deviations are butterfly reductions inside the lane group; the
-// per-row scalar work (mean, variance, Newton integer square root, reciprocal factor) is done
-// redundantly by the lanes of the group.
+// read once.  Sum and sum of squares are butterfly reductions inside the lane group; mean, variance and the
+// reciprocal factor are worked out redundantly by the lanes of the group, the integer square root (the value
+// Alg. 4 returns) by the lanes of the group together, each testing one candidate per round.  No floating point.
 //
 // The same kernel also serves the INT8 embedding (Sec. 1, contribution 3; App. C.1): there the row is not read from
 // an INT32 buffer but made on the fly from one row of the INT8 token table and one of the INT8 position table, each
@@ -176,7 +176,8 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
     // (|2 mu sum| < 2^42, C mu^2 <= 2^40)
     const uint64_t ss = (uint64_t)((int64_t)sq - 2 * (int64_t)mu * sum + (int64_t)C * ((int64_t)mu * mu));
 
-    const int32_t f = ln_row_factor(ss, Cu, a.magic_c);
+    const uint32_t var = ln_row_variance(ss, Cu, a.magic_c);
+    const int32_t f = ln_factor_of_sigma(isqrt_floor_rowwise<LPR>(var, lane));
     if (!live) return;
     // d*f: |d| < 2^17 always; f < 2^23 unless sigma <= 2, where the full 32-bit multiply is used instead
     const bool f24 = __builtin_amdgcn_ballot_w64(f >= (1 << 23)) == 0;
@@ -209,19 +210,28 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_rows_kernel(LayerNormArg
     }
 }
 
-__global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* p, int64_t words)
+// Alg. 4's integer square root on its own.  METHOD 0: a value per lane.  METHOD 1-3: the LPR = 64, 32, 16 lanes of a
+// group take the group's values one after the other, all lanes working on one value, as the row kernel does with its
+// one variance per row.
+template <int METHOD>
+__global__ __launch_bounds__(256) void isqrt_kernel(const uint32_t* n, uint32_t* root, int64_t count)
 {
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < words; i += (int64_t)gridDim.x * 256) p[i] = 0u;
-}
-
-// Clears `words` 32-bit words with a kernel (a memset node may not be recorded into a captured graph).
-int launch_zero_words(uint32_t* p, int64_t words, hipStream_t stream)
-{
-    if (words <= 0) return IBERT_OK;
-    const int64_t blocks = (words + 1023) / 1024;
-    hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)(blocks > 1024 ? 1024 : blocks)), dim3(256), 0, stream, p, words);
-    IBERT_LAUNCH_CHECK("zero_words_kernel");
-    return IBERT_OK;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const uint32_t v = n[i < count ? i : count - 1];               // (every lane stays for the cross-lane rounds)
+    uint32_t r;
+    if (METHOD == 0) {
+        r = isqrt_floor_lane(v);
+    } else {
+        constexpr int LPR = METHOD == 1 ? 64 : (METHOD == 2 ? 32 : 16);
+        const int lane = threadIdx.x & 63, lir = lane % LPR, base = lane - lir;
+        r = 0;
+        for (int k = 0; k < LPR; ++k) {
+            const uint32_t vk = (uint32_t)__shfl((int32_t)v, base + k, 64);
+            const uint32_t rk = isqrt_floor_rowwise<LPR>(vk, lir);
+            r = lir == k ? rk : r;
+        }
+    }
+    if (i < count) root[i] = r;
 }
 
 int check_layernorm(int32_t C, int32_t shift)
@@ -326,6 +336,27 @@ extern "C" int ibert_layernorm_i(const int32_t* x, int8_t* y, int64_t rows, int3
     if (rows == 0) return IBERT_OK;
     if (!x || !y || !gamma_q || !beta_q) return IBERT_ERR_NULL;
     return ibert::launch_layernorm(x, y, rows, C, ldx, ldy, gamma_q, beta_q, shift, (hipStream_t)stream);
+}
+
+extern "C" int ibert_isqrt_i(const uint32_t* n, uint32_t* root, int64_t count, int32_t method, void* stream_)
+{
+    using namespace ibert;
+    if (count < 0) return IBERT_ERR_SHAPE;
+    if (method < 0 || method > 3) return IBERT_ERR_PARAM_RANGE;
+    if (count == 0) return IBERT_OK;
+    if (!n || !root) return IBERT_ERR_NULL;
+    const int64_t blocks = (count + 255) / 256;
+    if (blocks > 0x7fffffffLL) return IBERT_ERR_SHAPE;
+    hipStream_t stream = (hipStream_t)stream_;
+    const dim3 grid((unsigned)blocks), block(256);
+    switch (method) {
+        case 0: hipLaunchKernelGGL(isqrt_kernel<0>, grid, block, 0, stream, n, root, count); break;
+        case 1: hipLaunchKernelGGL(isqrt_kernel<1>, grid, block, 0, stream, n, root, count); break;
+        case 2: hipLaunchKernelGGL(isqrt_kernel<2>, grid, block, 0, stream, n, root, count); break;
+        default: hipLaunchKernelGGL(isqrt_kernel<3>, grid, block, 0, stream, n, root, count); break;
+    }
+    IBERT_LAUNCH_CHECK("isqrt_kernel");
+    return IBERT_OK;
 }
 
 extern "C" int ibert_layernorm_i16(const int16_t* x, int8_t* y, int64_t rows, int32_t C, int64_t ldx, int64_t ldy,

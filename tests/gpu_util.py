@@ -64,35 +64,6 @@ def gemm_gelu(desc_kwargs, A, W, bias, mult, shift, gelu_params, out_elems, with
     return out[:out_elems], (None if tS is None else tS.cpu().numpy())
 
 
-def gemm_layernorm(desc_kwargs, A, W, bias, mult, shift, residual, gamma_q, beta_q, ln_shift, ldy=None, y_off=0):
-    """ibert_gemm_i8_layernorm.  Returns (y int8 [M, N], status word, first words of the INT32 scratch tensor)."""
-    d = B.GemmDesc()
-    for k, v in desc_kwargs.items():
-        setattr(d, k, B.Dyadic(*v) if k in ("requant", "residual_dy") else v)
-    M, N = d.M, d.N
-    ldy = N if ldy is None else ldy
-    tA, tW = to_dev(A, np.int8).reshape(-1), to_dev(W, np.int8).reshape(-1)
-    tb = None if bias is None else to_dev(bias, np.int32)
-    tm = None if mult is None else to_dev(mult, np.int32)
-    ts = None if shift is None else to_dev(shift, np.int32)
-    tR = None if residual is None else to_dev(residual, np.int8).reshape(-1)
-    ty = torch.full((M * ldy + y_off + 16,), 77, dtype=torch.int8, device=DEV)
-    nbytes = B.ibert_gemm_layernorm_scratch_bytes(M, N)
-    tS = torch.full((nbytes,), 0x5A, dtype=torch.uint8, device=DEV)          # dirty on purpose: the call clears what it needs
-    B.ibert_gemm_i8_layernorm(d, tA, tW, tb, tm, ts, tR, to_dev(gamma_q, np.int32), to_dev(beta_q, np.int32), ln_shift,
-                              ty[y_off:], ldy, tS)
-    torch.cuda.synchronize()
-    out = ty.cpu().numpy()
-    assert np.all(out[:y_off] == 77) and np.all(out[y_off + M * ldy:] == 77), "wrote outside the output"
-    body = out[y_off:y_off + M * ldy].reshape(M, ldy)
-    assert np.all(body[:, N:] == 77), "wrote into the row padding"
-    raw = tS.cpu().numpy()
-    r_bytes = (M * N * 4 + 255) // 256 * 256
-    words = 4 * M
-    status = int(raw[r_bytes + 4 * words:r_bytes + 4 * words + 4].view(np.uint32)[0])
-    return body[:, :N], status, raw[:16].view(np.int32)
-
-
 def attention(qkv, batch, seq, hidden, heads, scores_dy, softmax_params, ctx_dy, with_scratch=True, key_lens=None):
     """Steps 2-4 through ibert_attention_i (ibert_attention_masked_i with key_lens).  qkv: int8 [batch*seq, 3*hidden];
     returns ctx int8 [batch*seq, hidden]."""
@@ -186,6 +157,18 @@ def embedding(ids, seq, tok, pos, tok_dy, pos_dy, gamma_q, beta_q, shift, ldy=No
     return body[:, :H]
 
 
+def isqrt(n, method):
+    """ibert_isqrt_i on a uint32 array."""
+    n = np.ascontiguousarray(n, np.uint32)
+    tn = torch.from_numpy(n.view(np.int32)).to(DEV)
+    tr = torch.full((n.size + 8,), -1, dtype=torch.int32, device=DEV)
+    B.ibert_isqrt_i(tn, tr, n.size, method)
+    torch.cuda.synchronize()
+    out = tr.cpu().numpy()
+    assert np.all(out[n.size:] == -1), "wrote outside the output"
+    return out[:n.size].view(np.uint32)
+
+
 class DeviceModel:
     """All layers of a synthetic encoder resident on the GPU, plus workspace."""
 
@@ -223,12 +206,11 @@ class DeviceModel:
                                            c.heads, c.ffn, key_lens, self.ws)
         return y
 
-    def ln_status(self) -> int:
-        """The status word of the fused MatMul + LayerNorm kernels (0 in a healthy run)."""
-        T = self.cfg.tokens
-        words = 4 * T
-        off = self.layout.ln_stats + 2 * words * 4
-        return int(self.ws[off:off + 4].view(torch.int32).item())
+    def set_route(self, route: int):
+        """ibert_layer_quant.route of every layer (0 = every fusion; B.ROUTE_* flags)."""
+        for l in range(self.n_layers):
+            self.layers[l].quant.route = route
+            self.quant[l].route = route
 
     def mark_unwritten(self):
         """Plants a pattern at the start of the INT32 tensors r1 and r2, to see afterwards whether a step wrote them."""
@@ -240,7 +222,7 @@ class DeviceModel:
         return not bool(torch.all(self.ws[off:off + 16] == 0x7B).item())
 
     def intermediates(self, r_half: bool = False) -> dict:
-        """r_half: r1 / r2 were stored as int16 (fusion bit 3); they are returned widened."""
+        """r_half: r1 / r2 were stored as int16 (the default route); they are returned widened."""
         c, lo = self.cfg, self.layout
         T, H, F, BH, L = c.tokens, c.hidden, c.ffn, c.batch * c.heads, c.seq
         spec = {"qkv": (lo.qkv, (T, 3 * H), torch.int8), "scores": (lo.scores, (BH, L, L), torch.int32),

@@ -34,16 +34,6 @@ def _eq(got, want, what):
             what, len(bad), np.asarray(want).size, first, np.asarray(got)[first], np.asarray(want)[first]))
 
 
-@pytest.fixture(autouse=True)
-def _every_kernel_fusion_on():
-    # the cases below were written against "all three kernel fusions on" (mask 7) and say so where they look at which
-    # kernels ran; the library's own default (mask 11) is one of the masks the layer tests go through
-    from paper_2101_01321_amd import binding as B
-    old = B.ibert_set_fusion(7)
-    yield
-    B.ibert_set_fusion(old)
-
-
 # ------------------------------------------------------------------------------------------- GELU
 @pytest.mark.parametrize("S_in,S_out", [(2.0 ** -7, 8.0 / 127), (2.0 ** -6, 0.406), (2.0 ** -4, 0.1), (0.011, 0.02)])
 def test_gelu_matches_oracle(G, S_in, S_out):
@@ -215,6 +205,21 @@ def test_layernorm_full_shape_and_small_sigma(G):
     _eq(G.layernorm(x, gq, bq, s), oracle.layernorm(x, gq, bq, s), "layernorm sigma sweep")
 
 
+@pytest.mark.parametrize("method", [0, 1, 2, 3])
+def test_isqrt_matches_oracle(G, method):
+    # Alg. 4's result on the device, by both routines the LayerNorm kernels use: every perfect square and its two
+    # neighbours, powers of two and their neighbours, the ends of the range, the paper's six-pass example, random values
+    k = np.arange(65536, dtype=np.uint64)
+    sq = k * k
+    p2 = np.uint64(1) << np.arange(33, dtype=np.uint64)
+    n = np.concatenate([sq, sq + 1, np.maximum(sq, 1) - 1, p2, p2 + 1, p2 - 1, [0, 1, 2, 3, 17413928, 2 ** 32 - 1, 2 ** 32 - 2],
+                        np.random.default_rng(4).integers(0, 2 ** 32, size=1_000_000, dtype=np.uint64)])
+    n = n[n < 2 ** 32].astype(np.uint32)
+    want, _ = oracle.isqrt_array(n)
+    G.say("isqrt method %d on %d values" % (method, n.size))
+    _eq(G.isqrt(n, method), np.asarray(want, np.uint32), "isqrt method %d" % method)
+
+
 # ------------------------------------------------------------------------------------------- GEMM
 def _gemm_case(G, M, N, K, out_dtype, per_channel, bias, residual, seed, clamp=None):
     from paper_2101_01321_amd import binding as B
@@ -341,12 +346,6 @@ def test_attention_equals_scores_softmax_context(G, B_, nh, L, S, sdy, cdy):
     if L in (128, 256, 384, 512):
         G.say("attention, one-kernel form without scratch")
         _eq(G.attention(qkv, B_, L, H, nh, sdy, sp, cdy, with_scratch=False), want, "attention (no scratch)")
-        old = B.ibert_set_fusion(0)
-        try:
-            G.say("attention, fusion off")
-            _eq(G.attention(qkv, B_, L, H, nh, sdy, sp, cdy), want, "attention (three kernels)")
-        finally:
-            B.ibert_set_fusion(old)
     else:
         with pytest.raises(B.IbertError):
             G.attention(qkv, B_, L, H, nh, sdy, sp, cdy, with_scratch=False)
@@ -481,36 +480,46 @@ def test_gemm_direct_to_lds_tiles_batched(G, cfg, M, N, K):
         B.lib().ibert_gemm_config_override(-1)
 
 
-@pytest.mark.parametrize("cfg", [6, 9])
+@pytest.mark.parametrize("cfg", [6, 9, 13])
+@pytest.mark.parametrize("table", [True, False])
 @pytest.mark.parametrize("S_in,S_out", [(2.0 ** -7, 8.0 / 127), (2.0 ** -6, 0.748), (0.011, 0.02)])
-def test_gemm_gelu_every_gelu_input_value(G, cfg, S_in, S_out):
-    # the fused epilogue reads GELU from a table outside of which the function is constant: drive the MatMul so that
-    # its requantized outputs walk through every integer from below -q_max to above +q_max
+def test_gemm_gelu_every_gelu_input_value(G, cfg, table, S_in, S_out):
+    # Drive the MatMul so that its requantized outputs walk through every integer from below -q_max to above +q_max.
+    # table=True: shifts of 33 (the register-direct epilogue), where the fused kernel reads GELU from its table in LDS,
+    # outside of which the function is constant -- the kernel's label must say that the table was used;
+    # table=False: shifts of 30, which take the general requantization and the arithmetic form of GELU.
     from paper_2101_01321_amd import binding as B
     gp, op = B.ibert_gelu_params_from_scale(S_in, S_out), P.gelu_params(S_in, S_out)
     M, N, K = 768, 384, 128
+    f_mul = 8 if table else 1                               # accumulators are f_mul times the value they requantize to
     A = np.zeros((M, K), np.int8)
     W = np.zeros((N, K), np.int8)
-    W[:, 0] = 127
-    W[:, 1] = 127
-    A[:, 0] = np.arange(M) % 255 - 127                      # acc = 127 a0 + 16129 c + bias, c in {-1, 0, 1}
-    A[:, 1] = 127 * np.where(np.arange(M) < 765, np.arange(M) // 255 - 1, 0)
-    bias = (np.arange(N) % 128 - 64).astype(np.int32)       # fills the gaps of 127 between products
+    a0 = np.arange(M) % 255 - 127
+    c = np.where(np.arange(M) < 765, np.arange(M) // 255 - 1, 0)
+    W[:, :2 * f_mul] = 127
+    A[:, :f_mul] = a0[:, None]                              # acc = f_mul (127 a0 + 16129 c + bias'), c in {-1, 0, 1}
+    A[:, f_mul:2 * f_mul] = (127 * c)[:, None]
+    bias = (f_mul * (np.arange(N) % 128 - 64)).astype(np.int32)   # fills the gaps of 127 between products
     mult = np.full(N, 2 ** 30, np.int32)
-    shift = np.full(N, 30, np.int32)                        # DY(acc; 2^30, 30) = acc
+    shift = np.full(N, 33 if table else 30, np.int32)       # DY(acc; 2^30, 33) = acc / 8 exactly; DY(acc; 2^30, 30) = acc
     kw = dict(M=M, N=N, K=K, batch_outer=1, batch_inner=1, lda=K, ldw=K, ldc=N, per_channel=1, out_dtype=I8, out_clamp=5)
     f = oracle.gemm_requant(GemmSpec(M, N, K, per_channel=1, dy=(1, 0), out_dtype=I32, out_clamp=gp.q_max), A, W, bias, mult, shift, None)
     hit = np.unique(f)
     span = min(gp.q_max, 32000)
     assert hit.min() <= -span and hit.max() >= span and np.all(np.diff(hit) == 1)      # every integer in between
     want = oracle.gelu(f.reshape(-1), op)
+    import torch
+    word = torch.zeros(1, dtype=torch.int32, device=G.DEV)
     B.lib().ibert_gemm_config_override(cfg)
+    B.ibert_gemm_epilogue_record(word)
     try:
-        G.say("gemm+gelu sweep cfg=%d S_in=%g" % (cfg, S_in))
+        G.say("gemm+gelu sweep cfg=%d S_in=%g table=%s" % (cfg, S_in, table))
         got, scratch = G.gemm_gelu(kw, A, W, bias, mult, shift, gp, M * N)
     finally:
+        B.ibert_gemm_epilogue_record(None)
         B.lib().ibert_gemm_config_override(-1)
     assert np.all(scratch == -5)                             # one kernel
+    assert int(word.item()) == (B.EPILOGUE_DIRECT_GELU_TABLE if table else B.EPILOGUE_STAGED)
     _eq(got, want, "gemm+gelu sweep")
 
 
@@ -522,95 +531,70 @@ def test_gemm_base_shapes_full(G):
         _gemm_case(G, M, N, K, od, 1, True, res, seed=N + K)
 
 
+@pytest.mark.parametrize("H,F", [(1024, 4096), (768, 3072)])
+def test_gemm_projection_shapes_at_32768_tokens_full(G, H, F):
+    # the four projection GEMMs of RoBERTa-Large at batch 256 and of RoBERTa-Base at 512 tokens x 64 (T = 32768), whole
+    # outputs, in the output types and with the tile configurations the encoder runs them with
+    T = 32768
+    for M, N, K, od, res in [(T, 3 * H, H, I8, False), (T, H, H, I16, True), (T, F, H, I32, False), (T, H, F, I16, True)]:
+        G.say("gemm T=32768 M=%d N=%d K=%d out=%d" % (M, N, K, od))
+        _gemm_case(G, M, N, K, od, 1, True, res, seed=N + K + 1)
+
+
 # ------------------------------------------------------------------------------------------- layer / encoder
-def _layer_case(G, cfg, n_layers=1, fusion=0):
-    import torch
-    from paper_2101_01321_amd import binding as B
-    B.ibert_set_fusion(fusion)
-    try:
-        return _layer_case_body(G, cfg, n_layers, fusion)
-    finally:
-        B.ibert_set_fusion(7)
+def _layer_case(G, cfg, n_layers=1, route=0):
+    return _layer_case_body(G, cfg, n_layers, route)
 
 
-def _layer_case_body(G, cfg, n_layers, fusion):
+def _layer_case_body(G, cfg, n_layers, route):
     import torch
     x_q, S_x, _ = synth.input_activations(cfg)
+    from paper_2101_01321_amd import binding as B
     model = G.DeviceModel(cfg, S_x, n_layers=n_layers)
+    model.set_route(route)
+    one_kernel_attention = cfg.seq in (128, 256, 384, 512) and cfg.hidden == 64 * cfg.heads
     cur = x_q
     tx = G.to_dev(x_q)
     for l in range(n_layers):
         raw = synth.layer_raw(cfg, l)
         w, q = P.layer_params(raw, model.scales[l], cfg.hidden, cfg.heads)
         want, inter = oracle.encoder_layer(w, q, cur, cfg.batch, cfg.seq, cfg.hidden, cfg.heads, cfg.ffn, dump=True)
-        G.say("layer %s l=%d fusion=%d" % (cfg.name, l, fusion))
+        G.say("layer %s l=%d route=%d" % (cfg.name, l, route))
         model.mark_unwritten()
         ty = model.layer_forward(l, tx)
         torch.cuda.synchronize()
-        got_inter = model.intermediates(r_half=bool(fusion & 8))
+        got_inter = model.intermediates(r_half=not (route & B.ROUTE_I32_LN_INPUT))
         for k in ("qkv", "scores", "probs", "ctx", "r1", "h1", "f1", "g", "r2"):
-            if k == "f1" and (fusion & 1):
+            if k == "f1" and not (route & B.ROUTE_SEPARATE_GELU):
                 continue                                     # not materialised when GELU runs in the MatMul epilogue
-            if k in ("r1", "r2") and (fusion & 4) and not model.was_written(k):
-                continue                                     # nor these when LayerNorm runs in the MatMul epilogue
             if k in ("r1", "r2"):
                 assert model.was_written(k)
-            if k in ("scores", "probs") and (fusion & 2) and cfg.seq in (128, 256, 384, 512) and cfg.hidden == 64 * cfg.heads:
+            if k in ("scores", "probs") and not (route & B.ROUTE_SEPARATE_ATTENTION) and one_kernel_attention:
                 continue                                     # nor these when attention is one kernel
             _eq(got_inter[k], inter[k], "%s layer %d %s" % (cfg.name, l, k))
         _eq(ty.cpu().numpy(), want, "%s layer %d output" % (cfg.name, l))
         cur, tx = want, ty
-    assert model.ln_status() == 0
     return model, x_q, cur
 
 
 def test_layer_tiny_every_intermediate(G):
-    _layer_case(G, synth.CONFIGS["tiny"])
-    _layer_case(G, synth.CONFIGS["tiny"], fusion=3)
-    _layer_case(G, synth.CONFIGS["tiny"], fusion=7)
-    _layer_case(G, synth.CONFIGS["tiny"], fusion=8)
-    _layer_case(G, synth.CONFIGS["tiny"], fusion=15)
+    for route in range(8):                                   # every combination of fused and separate kernels
+        _layer_case(G, synth.CONFIGS["tiny"], route=route)
 
 
 def test_layer_whole_tile_shape_fused_and_unfused(G):
     # hidden/ffn/tokens that fit the whole-tile MatMul configurations, so that every fusion really runs its fused kernel
     cfg = synth.EncoderConfig("tiles", 256, 4, 1024, 128, 16, 1)
-    for fusion in (0, 1, 2, 3, 4, 5, 7, 8, 11, 15):
-        _layer_case(G, cfg, fusion=fusion)
-    # the LayerNorm fusion is the library's own choice at about one 128-row tile per compute unit; force its tile
-    # configurations on small layers (128-wide column tiles at hidden 256, 96-wide at hidden 384; two layers)
-    for tile_cfg, cfg in ((7, cfg), (9, synth.EncoderConfig("tiles96", 384, 6, 1536, 128, 4, 2)),
-                          (11, synth.EncoderConfig("tiles96", 384, 6, 1536, 128, 4, 2))):
-        B_ = __import__("paper_2101_01321_amd.binding", fromlist=["lib"])
-        B_.lib().ibert_gemm_config_override(tile_cfg)
-        try:
-            for fusion in (4, 7):
-                model, _, _ = _layer_case(G, cfg, n_layers=cfg.layers, fusion=fusion)
-                assert not model.was_written("r1") and not model.was_written("r2")
-        finally:
-            B_.lib().ibert_gemm_config_override(-1)
+    for route in range(8):
+        _layer_case(G, cfg, route=route)
+    _layer_case(G, synth.EncoderConfig("tiles96", 384, 6, 1536, 128, 4, 2), n_layers=2)
 
 
-@pytest.mark.parametrize("M,N,K,cfg", [
-    (4096, 768, 768, -1), (4096, 768, 3072, -1), (4096, 1024, 1024, -1),       # the library's own choice: one kernel
-    (128, 96, 128, 9), (256, 768, 768, 9), (512, 768, 3072, 11), (384, 1024, 1024, 7), (256, 128, 256, 7),
-    (1024, 384, 2048, 11), (256, 1024, 4096, 12), (256, 96, 128, 11),           # forced tile configurations
-    (100, 96, 128, None), (128, 100, 128, None), (128, 96, 100, None), (130, 250, 64, None), (5, 3, 16, None),
-    (256, 768, 768, None)])                                                     # two kernels
-def test_gemm_layernorm_equals_matmul_then_layernorm(G, M, N, K, cfg):
-    # steps 5+6 / 9+10 in one call: shapes the one-kernel form takes (one to eight column tiles per row, several tile
-    # rows, two and three LDS stages) and shapes that fall back to two kernels
-    from paper_2101_01321_amd import binding as B
-    fused = cfg is not None
-    if fused and cfg >= 0:
-        assert B.lib().ibert_gemm_config_override(cfg) > cfg
-    try:
-        _gemm_layernorm_case(G, M, N, K, fused)
-    finally:
-        B.lib().ibert_gemm_config_override(-1)
-
-
-def _gemm_layernorm_case(G, M, N, K, fused):
+@pytest.mark.parametrize("M,N,K", [(4096, 768, 768), (4096, 768, 3072), (4096, 1024, 1024), (256, 768, 768), (1024, 384, 2048),
+                                   (100, 96, 128), (130, 250, 64), (5, 3, 16)])
+def test_gemm_i16_then_layernorm_i16(G, M, N, K):
+    # steps 5+6 / 9+10 as the layer runs them: a projection with residual whose clamped result is stored as int16, and the
+    # LayerNorm kernel that reads int16 -- against the oracle's INT32 MatMul and LayerNorm
     from paper_2101_01321_amd import binding as B
     A, W, sw, b = synth.gemm_operands(M, N, K, layer=M + N + K)
     mult, shift = B.ibert_channel_dyadics_from_scales(0.03, sw, 2.5e-4 * math.sqrt(K))   # rows spread over the 16-bit range
@@ -619,69 +603,20 @@ def _gemm_layernorm_case(G, M, N, K, fused):
     beta = np.random.default_rng(N + 1).normal(0.0, 0.1, size=N)
     gq, bq, s = B.ibert_layernorm_params_from_float(gamma, beta, 5.0 / 127)
     res_dy = (1717986918, 23)
-    kw = dict(M=M, N=N, K=K, batch_outer=1, batch_inner=1, lda=K, ldw=K, ldc=N, ldr=N, per_channel=1, out_dtype=I32,
+    kw = dict(M=M, N=N, K=K, batch_outer=1, batch_inner=1, lda=K, ldw=K, ldc=N, ldr=N, per_channel=1, out_dtype=I16,
               out_clamp=32767, residual_dy=res_dy)
     spec = GemmSpec(M, N, K, per_channel=1, dy=(1, 0), out_dtype=I32, out_clamp=32767, res_dy=res_dy)
     r = oracle.gemm_requant(spec, A, W, b, mult, shift, R).reshape(M, N)
     top, clamped = int(np.abs(r).max()), float((np.abs(r) == 32767).mean())
     assert top > 2000 and clamped < 0.2, (top, clamped)                           # a real spread, few clamped values
-    want = oracle.layernorm(r, gq, bq, s)
-    for with_res in (True, False):
-        if not with_res:
-            r0 = oracle.gemm_requant(spec, A, W, b, mult, shift, None).reshape(M, N)
-            want = oracle.layernorm(r0, gq, bq, s)
-        G.say("gemm+layernorm M=%d N=%d K=%d residual=%s" % (M, N, K, with_res))
-        got, status, r_head = G.gemm_layernorm(kw, A, W, b, mult, shift, R if with_res else None, gq, bq, s)
-        assert status == 0 or not fused
-        _eq(got, want, "gemm+layernorm")
-        # the INT32 tensor is only written on the two-kernel route
-        assert bool(np.all(r_head == 0x5A5A5A5A)) == fused
-    if fused:
-        G.say("gemm+layernorm fusion off")
-        old = B.ibert_set_fusion(3)
-        try:
-            got, _, r_head = G.gemm_layernorm(kw, A, W, b, mult, shift, None, gq, bq, s)
-        finally:
-            B.ibert_set_fusion(old)
-        _eq(got, want, "gemm+layernorm, two kernels")
-        assert not np.all(r_head == 0x5A5A5A5A)
-        G.say("gemm+layernorm padded output rows")
-        got, status, _ = G.gemm_layernorm(kw, A, W, b, mult, shift, None, gq, bq, s, ldy=N + 16)
-        assert status == 0
-        _eq(got, want, "gemm+layernorm ldy")
+    G.say("gemm int16 + layernorm int16 M=%d N=%d K=%d" % (M, N, K))
+    got_r = G.gemm(kw, A, W, b, mult, shift, R, out_elems=M * N).reshape(M, N)
+    _eq(got_r.astype(np.int32), r, "int16 MatMul output")
+    _eq(G.layernorm(got_r, gq, bq, s, half=True), oracle.layernorm(r, gq, bq, s), "layernorm of the int16 rows")
 
 
-def test_gemm_layernorm_many_tile_rows(G):
-    # far more tiles than the chip holds at once (2048 and 1280 workgroups, several rounds): tile rows that start late
-    # must still find their neighbours, and waiting tiles must not starve the ones they wait for
-    from paper_2101_01321_amd import binding as B
-    for M, N, K, cfg in ((32768, 768, 256, 9), (16384, 1024, 256, 7), (20480, 768, 2048, 11)):
-        rng = np.random.default_rng(M + N)
-        A = rng.integers(-127, 128, size=(M, K), dtype=np.int8)
-        W = rng.integers(-127, 128, size=(N, K), dtype=np.int8)
-        b = rng.integers(-2 ** 15, 2 ** 15, size=N).astype(np.int32)
-        R = rng.integers(-127, 128, size=(M, N), dtype=np.int8)
-        mult = np.full(N, 1518500250, np.int32)
-        shift = np.full(N, 36 + int(math.log2(K) // 2), np.int32)
-        gq, bq, s = B.ibert_layernorm_params_from_float(rng.normal(1.0, 0.1, size=N), rng.normal(0.0, 0.1, size=N), 5.0 / 127)
-        res_dy = (1717986918, 23)
-        kw = dict(M=M, N=N, K=K, batch_outer=1, batch_inner=1, lda=K, ldw=K, ldc=N, ldr=N, per_channel=1, out_dtype=I32,
-                  out_clamp=32767, residual_dy=res_dy)
-        spec = GemmSpec(M, N, K, per_channel=1, dy=(1, 0), out_dtype=I32, out_clamp=32767, res_dy=res_dy)
-        want = oracle.layernorm(oracle.gemm_requant(spec, A, W, b, mult, shift, R).reshape(M, N), gq, bq, s)
-        B.lib().ibert_gemm_config_override(cfg)
-        try:
-            G.say("gemm+layernorm M=%d N=%d K=%d cfg=%d" % (M, N, K, cfg))
-            got, status, r_head = G.gemm_layernorm(kw, A, W, b, mult, shift, R, gq, bq, s)
-        finally:
-            B.lib().ibert_gemm_config_override(-1)
-        assert status == 0 and np.all(r_head == 0x5A5A5A5A)
-        _eq(got, want, "gemm+layernorm M=%d" % M)
-
-
-def test_fused_layer_replayed_from_a_graph(G):
-    # the whole layer with all three fusions captured into a HIP graph: the row statistics of the LayerNorm epilogues are
-    # cleared by kernels of the graph itself, so every replay (with eager work and synchronisation in between, and a
+def test_layer_replayed_from_a_graph(G):
+    # the whole layer captured into a HIP graph: every replay (with eager work and synchronisation in between, and a
     # different input each time) must give the oracle's result
     import torch
     from paper_2101_01321_amd import binding as B
@@ -689,90 +624,38 @@ def test_fused_layer_replayed_from_a_graph(G):
     x_q, S_x, _ = synth.input_activations(cfg)
     model = G.DeviceModel(cfg, S_x)
     w, q = P.layer_params(synth.layer_raw(cfg, 0), model.scales[0], cfg.hidden, cfg.heads)
-    B.lib().ibert_gemm_config_override(9)
-    try:
-        stream = torch.cuda.Stream()
-        tx = G.to_dev(x_q)
-        ty = torch.empty_like(tx)
+    stream = torch.cuda.Stream()
+    tx = G.to_dev(x_q)
+    ty = torch.empty_like(tx)
 
-        def run():
-            B.ibert_encoder_layer_i(model.layers[0].weights, model.layers[0].quant, tx, ty, cfg.batch, cfg.seq, cfg.hidden,
-                                    cfg.heads, cfg.ffn, model.ws, stream=stream)
-        with torch.cuda.stream(stream):
-            model.mark_unwritten()
-            run()
+    def run():
+        B.ibert_encoder_layer_i(model.layers[0].weights, model.layers[0].quant, tx, ty, cfg.batch, cfg.seq, cfg.hidden,
+                                cfg.heads, cfg.ffn, model.ws, stream=stream)
+    with torch.cuda.stream(stream):
+        run()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        run()
+    for rep in range(3):
+        x_rep = np.roll(x_q, rep * 7 + 1, axis=0) if rep else x_q
+        x_rep = np.ascontiguousarray(x_rep)
+        want = oracle.encoder_layer(w, q, x_rep, cfg.batch, cfg.seq, cfg.hidden, cfg.heads, cfg.ffn)
+        tx.copy_(G.to_dev(x_rep))
+        ty.zero_()
         torch.cuda.synchronize()
-        assert not model.was_written("r1") and not model.was_written("r2")       # the fused kernels did run
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=stream):
-            run()
-        rng = np.random.default_rng(11)
-        for rep in range(3):
-            x_rep = np.roll(x_q, rep * 7 + 1, axis=0) if rep else x_q
-            x_rep = np.ascontiguousarray(x_rep)
-            want = oracle.encoder_layer(w, q, x_rep, cfg.batch, cfg.seq, cfg.hidden, cfg.heads, cfg.ffn)
-            tx.copy_(G.to_dev(x_rep))
-            ty.zero_()
-            torch.cuda.synchronize()
-            G.say("graph replay %d of the fused layer" % rep)
-            graph.replay()
-            torch.cuda.synchronize()
-            _eq(ty.cpu().numpy(), want, "replay %d" % rep)
-            assert model.ln_status() == 0
-    finally:
-        B.lib().ibert_gemm_config_override(-1)
-
-
-def test_gemm_layernorm_degenerate_rows_and_general_requantization(G):
-    # constant rows (sigma clamps to 1, the 32-bit multiply form), saturated rows, and multipliers / shifts outside the
-    # fast requantization form (shift below 33), all inside the one-kernel shape
-    from paper_2101_01321_amd import binding as B
-    M, N, K = 256, 192, 256
-    B.lib().ibert_gemm_config_override(9)
-    try:
-        _gemm_layernorm_degenerate(G, M, N, K)
-    finally:
-        B.lib().ibert_gemm_config_override(-1)
-
-
-def _gemm_layernorm_degenerate(G, M, N, K):
-    from paper_2101_01321_amd import binding as B
-    rng = np.random.default_rng(5)
-    A = rng.integers(-127, 128, size=(M, K), dtype=np.int8)
-    W = rng.integers(-127, 128, size=(N, K), dtype=np.int8)
-    A[0:3] = 0                                                # accumulator 0: the row is bias and residual only
-    b = rng.integers(-2 ** 15, 2 ** 15, size=N).astype(np.int32)
-    gamma, beta = rng.normal(1.0, 0.1, size=N), rng.normal(0.0, 0.1, size=N)
-    gq, bq, s = B.ibert_layernorm_params_from_float(gamma, beta, 5.0 / 127)
-    R = rng.integers(-127, 128, size=(M, N), dtype=np.int8)
-    R[0] = 5
-    R[1] = 0
-    for mult_v, shift_v, bias_on in ((1518500250, 36, True), (1518500250, 30, True), (3, 1, False), (1 << 30, 62, True),
-                                     (1518500250, 45, False)):
-        mult = np.full(N, mult_v, np.int32)
-        shift = np.full(N, shift_v, np.int32)
-        shift[::7] = max(0, shift_v - 3)                      # mixed shifts inside a tile
-        bias = b if bias_on else np.zeros(N, np.int32)
-        if not bias_on:
-            bias[:] = 0
-        res_dy = (1717986918, 23)
-        kw = dict(M=M, N=N, K=K, batch_outer=1, batch_inner=1, lda=K, ldw=K, ldc=N, ldr=N, per_channel=1, out_dtype=I32,
-                  out_clamp=32767, residual_dy=res_dy)
-        spec = GemmSpec(M, N, K, per_channel=1, dy=(1, 0), out_dtype=I32, out_clamp=32767, res_dy=res_dy)
-        r = oracle.gemm_requant(spec, A, W, bias, mult, shift, R).reshape(M, N)
-        want = oracle.layernorm(r, gq, bq, s)
-        G.say("gemm+layernorm degenerate m=%d s=%d" % (mult_v, shift_v))
-        got, status, r_head = G.gemm_layernorm(kw, A, W, bias, mult, shift, R, gq, bq, s)
-        assert status == 0 and np.all(r_head == 0x5A5A5A5A)                      # one kernel: the INT32 tensor was never written
-        _eq(got, want, "gemm+layernorm m=%d s=%d" % (mult_v, shift_v))
+        G.say("graph replay %d of the layer" % rep)
+        graph.replay()
+        torch.cuda.synchronize()
+        _eq(ty.cpu().numpy(), want, "replay %d" % rep)
 
 
 def test_layer_ragged_every_intermediate(G):
     _layer_case(G, synth.EncoderConfig("ragged", 192, 3, 320, 40, 2, 1))
     _layer_case(G, synth.EncoderConfig("ragged2", 320, 5, 200, 77, 3, 2), n_layers=2)
-    # 16-bit LayerNorm inputs on shapes that take the ragged-tile, K-tail and byte-load MatMul kernels
-    _layer_case(G, synth.EncoderConfig("ragged", 192, 3, 320, 40, 2, 1), fusion=8)
-    _layer_case(G, synth.EncoderConfig("ragged2", 320, 5, 200, 77, 3, 2), n_layers=2, fusion=11)
+    # 32-bit LayerNorm inputs and separate kernels on shapes that take the ragged-tile, K-tail and byte-load MatMul kernels
+    _layer_case(G, synth.EncoderConfig("ragged", 192, 3, 320, 40, 2, 1), route=7)
+    _layer_case(G, synth.EncoderConfig("ragged2", 320, 5, 200, 77, 3, 2), n_layers=2, route=4)
 
 
 def test_encoder_base_b1_all_layers(G):
@@ -799,18 +682,30 @@ def _oracle_sequences(cfg, x_q, scales, seqs, n_layers):
     return cur
 
 
-@pytest.mark.parametrize("name,seqs", [("base_b32", (0, 13, 31)), ("large_b32", (5,)), ("large_b256", (0, 255)),
-                                       ("base512_b64", (63,))])
+# Sampled sequences: the first and the last, sequences in the middle of a 256-row MatMul tile and at its edges, on both
+# sides of the boundaries between the runs of tiles the eight XCDs work on, and (32768 tokens) far past row 8192, where
+# the LayerNorm kernel switches to its wide form.
+@pytest.mark.parametrize("name,seqs", [("base_b32", (0, 1, 7, 13, 16, 24, 31)), ("large_b32", (0, 5, 11, 16, 21, 27, 31)),
+                                       ("large_b256", (0, 1, 37, 63, 64, 100, 128, 129, 200, 255)),
+                                       ("base512_b64", (0, 7, 21, 32, 33, 50, 63))])
 def test_encoder_full_size_sampled_sequences(G, name, seqs):
     import torch
     cfg = synth.CONFIGS[name]
     x_q, S_x, _ = synth.input_activations(cfg)
     G.say("encoder %s: building %d layers" % (name, cfg.layers))
     model = G.DeviceModel(cfg, S_x)
-    G.say("encoder %s: GPU forward" % name)
+    G.say("encoder %s: GPU forward (the default route, which the benchmark times)" % name)
     y = model.forward(G.to_dev(x_q))
     torch.cuda.synchronize()
     y = y.cpu().numpy()
+    # the whole output again with every step a kernel of its own and 32-bit LayerNorm inputs: the two routes share the
+    # MatMul main loops and little else, and must agree on every element
+    model.set_route(7)
+    G.say("encoder %s: GPU forward, separate kernels" % name)
+    y7 = model.forward(G.to_dev(x_q))
+    torch.cuda.synchronize()
+    _eq(y7.cpu().numpy(), y, "%s: separate kernels against the default route, whole output" % name)
+    del y7
     G.say("encoder %s: oracle on sequences %s" % (name, (seqs,)))
     want = _oracle_sequences(cfg, x_q, model.scales, seqs, cfg.layers)
     L = cfg.seq
@@ -818,6 +713,27 @@ def test_encoder_full_size_sampled_sequences(G, name, seqs):
         _eq(y[s * L:(s + 1) * L], want[s], "%s sequence %d" % (name, s))
     # properties that hold at any size: int8 range, not degenerate
     assert y.min() >= -127 and y.std() > 5
+
+
+@pytest.mark.parametrize("shape", ["base", "large"])
+@pytest.mark.parametrize("batch", [1, 8])
+def test_encoder_latency_grid_shapes(G, shape, batch):
+    # the shapes of Table 3 at sequence length 256 (the grid's other half, length 128, is covered by the configurations
+    # above and below): all layers, whole output against the oracle
+    import torch
+    base = synth.CONFIGS["base_b1" if shape == "base" else "large_b32"]
+    cfg = synth.EncoderConfig("%s_s256_b%d" % (shape, batch), base.hidden, base.heads, base.ffn, 256, batch, base.layers)
+    x_q, S_x, _ = synth.input_activations(cfg)
+    model = G.DeviceModel(cfg, S_x)
+    G.say("encoder %s: GPU forward" % cfg.name)
+    y = model.forward(G.to_dev(x_q))
+    torch.cuda.synchronize()
+    G.say("encoder %s: oracle" % cfg.name)
+    cur = x_q
+    for l in range(cfg.layers):
+        w, q = P.layer_params(synth.layer_raw(cfg, l), model.scales[l], cfg.hidden, cfg.heads)
+        cur = oracle.encoder_layer(w, q, cur, cfg.batch, cfg.seq, cfg.hidden, cfg.heads, cfg.ffn)
+    _eq(y.cpu().numpy(), cur, "%s encoder" % cfg.name)
 
 
 # ------------------------------------------------------------------------------------------- padded sequences
@@ -874,12 +790,6 @@ def test_attention_masked(G, B_, nh, L, S, sdy, cdy, lens):
     assert not np.array_equal(want, _attention_oracle(qkv, B_, L, H, nh, sdy, op, cdy))   # the mask matters
     G.say("masked attention B=%d heads=%d L=%d" % (B_, nh, L))
     _eq(G.attention(qkv, B_, L, H, nh, sdy, sp, cdy, key_lens=lens), want, "masked attention")
-    old = B.ibert_set_fusion(0)
-    try:
-        G.say("masked attention, fusion off")
-        _eq(G.attention(qkv, B_, L, H, nh, sdy, sp, cdy, key_lens=lens), want, "masked attention (three kernels)")
-    finally:
-        B.ibert_set_fusion(old)
 
 
 @pytest.mark.parametrize("cfg,lens", [
@@ -892,25 +802,22 @@ def test_layer_masked_every_row(G, cfg, lens):
     x_q, S_x, _ = synth.input_activations(cfg)
     lens = np.array(lens, np.int32)
     tl = G.to_dev(lens)
-    for fusion in (7, 0):
-        B.ibert_set_fusion(fusion)
-        try:
-            model = G.DeviceModel(cfg, S_x)
-            cur, tx = x_q, G.to_dev(x_q)
-            for l in range(cfg.layers):
-                w, q = P.layer_params(synth.layer_raw(cfg, l), model.scales[l], cfg.hidden, cfg.heads)
-                want = oracle.encoder_layer(w, q, cur, cfg.batch, cfg.seq, cfg.hidden, cfg.heads, cfg.ffn, key_lens=lens)
-                G.say("masked layer %s l=%d fusion=%d" % (cfg.name, l, fusion))
-                ty = model.layer_forward(l, tx, key_lens=tl)
-                torch.cuda.synchronize()
-                _eq(ty.cpu().numpy(), want, "%s layer %d" % (cfg.name, l))
-                cur, tx = want, ty
-            G.say("masked encoder %s in one call" % cfg.name)
-            y = model.forward(G.to_dev(x_q), key_lens=tl)
+    for route in (0, 7):
+        model = G.DeviceModel(cfg, S_x)
+        model.set_route(route)
+        cur, tx = x_q, G.to_dev(x_q)
+        for l in range(cfg.layers):
+            w, q = P.layer_params(synth.layer_raw(cfg, l), model.scales[l], cfg.hidden, cfg.heads)
+            want = oracle.encoder_layer(w, q, cur, cfg.batch, cfg.seq, cfg.hidden, cfg.heads, cfg.ffn, key_lens=lens)
+            G.say("masked layer %s l=%d route=%d" % (cfg.name, l, route))
+            ty = model.layer_forward(l, tx, key_lens=tl)
             torch.cuda.synchronize()
-            _eq(y.cpu().numpy(), cur, "%s encoder" % cfg.name)
-        finally:
-            B.ibert_set_fusion(7)
+            _eq(ty.cpu().numpy(), want, "%s layer %d" % (cfg.name, l))
+            cur, tx = want, ty
+        G.say("masked encoder %s in one call" % cfg.name)
+        y = model.forward(G.to_dev(x_q), key_lens=tl)
+        torch.cuda.synchronize()
+        _eq(y.cpu().numpy(), cur, "%s encoder" % cfg.name)
 
 
 def test_encoder_masked_full_size_sampled_sequences(G):
@@ -990,12 +897,9 @@ def test_dequantised_output_tracks_float_layer(G):
     x_q, S_x, _ = synth.input_activations(cfg)
     from paper_2101_01321_amd import binding as B
     model = G.DeviceModel(cfg, S_x)
-    old = B.ibert_set_fusion(0)                               # every intermediate is materialised
-    try:
-        y = model.layer_forward(0, G.to_dev(x_q))
-        torch.cuda.synchronize()
-    finally:
-        B.ibert_set_fusion(old)
+    model.set_route(7)                                        # every intermediate is materialised, 32 bits wide
+    y = model.layer_forward(0, G.to_dev(x_q))
+    torch.cuda.synchronize()
     d, sc, raw = model.intermediates(), model.scales[0], synth.layer_raw(cfg, 0)
     assert np.abs(d["scores"]).max() > 0 and d["probs"].max() > 0 and np.abs(d["f1"]).max() > 0 and np.abs(d["r2"]).max() > 0
     assert np.max(np.abs(d["probs"] / 128.0 - fpref.softmax(d["scores"] * sc["S_s"]))) <= 0.02

@@ -20,9 +20,12 @@ RNG = np.random.default_rng(7)
 
 
 def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "ibert.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(ibert_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for header in ("ibert.h", "ibert_testing.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(ibert_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -44,8 +47,8 @@ def test_struct_sizes_match_the_header_layout():
     assert C.sizeof(B.SoftmaxParams) == 20
     assert C.sizeof(B.GeluParams) == 24
     assert C.sizeof(B.LayerWeights) == 20 * 8
-    assert C.sizeof(B.LayerQuant) == 8 + 20 + 8 + 8 + 4 + 24 + 8 + 4
-    assert C.sizeof(B.WorkspaceLayout) == 11 * 8
+    assert C.sizeof(B.LayerQuant) == 8 + 20 + 8 + 8 + 4 + 24 + 8 + 4 + 4
+    assert C.sizeof(B.WorkspaceLayout) == 10 * 8
 
 
 def test_dyadic_helper_agrees_with_the_oracle_derivation():
@@ -113,9 +116,7 @@ def test_workspace_layout_is_aligned_and_disjoint():
     lo = B.ibert_encoder_layer_workspace_layout(32, 128, 768, 12, 3072)
     T, H, F, BH, L = 4096, 768, 3072, 384, 128
     sizes = {"qkv": T * 3 * H, "scores": BH * L * L * 4, "probs": BH * L * L, "ctx": T * H, "r1": T * H * 4,
-             "h1": T * H, "f1": T * F * 4, "g": T * F, "r2": T * H * 4,
-             # two sets of two 64-bit words a row, and a status word
-             "ln_stats": 2 * 16 * T + 4}
+             "h1": T * H, "f1": T * F * 4, "g": T * F, "r2": T * H * 4}
     spans = sorted((getattr(lo, k), getattr(lo, k) + v) for k, v in sizes.items())
     for (a0, a1), (b0, _) in zip(spans, spans[1:]):
         assert a1 <= b0
@@ -220,12 +221,12 @@ def test_fused_entry_points_reject_bad_arguments_before_touching_the_gpu():
     assert gg(C.byref(d), dummy, dummy, C.byref(gp), dummy, None) == -2
     d.lda, d.M = 4, 0
     assert gg(C.byref(d), None, None, C.byref(gp), None, None) == 0                                        # empty problem
-    # the fusion mask: query, set, unknown bits dropped
-    old = L.ibert_set_fusion(-1)
-    assert old == 11                                                 # the library's default
-    assert L.ibert_set_fusion(0) == old and L.ibert_set_fusion(-1) == 0
-    assert L.ibert_set_fusion(0xff) == 0 and L.ibert_set_fusion(-1) == 15
-    L.ibert_set_fusion(old)
+    # the integer square root
+    assert L.ibert_isqrt_i(dummy, dummy, -1, 0, None) == -2 and L.ibert_isqrt_i(dummy, dummy, 8, 4, None) == -3
+    assert L.ibert_isqrt_i(dummy, dummy, 8, -1, None) == -3 and L.ibert_isqrt_i(None, dummy, 8, 0, None) == -1
+    assert L.ibert_isqrt_i(None, None, 0, 1, None) == 0
+    # a layer's route flags start at zero (every fusion) when the quantization constants come from the helper
+    assert B.ibert_layer_quant_from_scales(synth.static_scales(synth.CONFIGS["tiny"], 0.03), 128, 64).route == 0
 
 
 def test_embedding_and_masked_entry_points_reject_bad_arguments_before_touching_the_gpu():
@@ -267,18 +268,44 @@ def test_embedding_and_masked_entry_points_reject_bad_arguments_before_touching_
     assert L.ibert_attention_masked_i(dummy, dummy, 1, 128, 768, 5, C.byref(dy), C.byref(sp), C.byref(dy), dummy, None, 0, None) == -2
 
 
-def test_single_precision_root_estimate_is_off_by_at_most_one():
-    # the LayerNorm kernel takes floor(sqrt(n)) from a correctly rounded single-precision root of n (itself
-    # rounded to single precision) plus one integer correction step; the recipe is replayed here in numpy
-    # (float32 sqrt is correctly rounded there too) on every n next to a perfect square and on random n
-    import math
+def _isqrt_inputs():
     k = np.arange(1, 65536, dtype=np.uint64)
-    n = np.unique(np.concatenate([k * k - 1, k * k, k * k + 1, np.array([0, 1, 2, 3, 2 ** 32 - 1], np.uint64),
-                                  np.random.default_rng(4).integers(0, 2 ** 32, size=400000, dtype=np.uint64)]))
-    n = n[n < 2 ** 32]
-    x = np.sqrt(n.astype(np.float32)).astype(np.uint64)
-    x = np.minimum(x, 65535)
-    x = np.where(x * x > n, x - 1, np.where((x < 65535) & ((x + 1) * (x + 1) <= n), x + 1, x))
-    want = np.array([math.isqrt(int(v)) for v in n[::97]], np.uint64)
-    assert np.array_equal(x[::97], want)
+    n = np.unique(np.concatenate([k * k - 1, k * k, k * k + 1, np.array([0, 1, 2, 3, 17413928, 2 ** 32 - 1], np.uint64),
+                                  np.random.default_rng(4).integers(0, 2 ** 32, size=1_000_000, dtype=np.uint64)]))
+    return n[n < 2 ** 32]
+
+
+def _check_floor_sqrt(n, x):
     assert np.all(x * x <= n) and np.all((x + 1) * (x + 1) > n)            # the defining property, on all of them
+    assert np.array_equal(x[::97], np.array([math.isqrt(int(v)) for v in n[::97]], np.uint64))
+
+
+@pytest.mark.parametrize("lanes,shifts", [(64, (10, 4, 0)), (32, (11, 6, 1, 0)), (16, (12, 8, 4, 0))])
+def test_lane_parallel_square_root_recipe_is_exact(lanes, shifts):
+    # the LayerNorm kernel's square root: in each round the lanes of a row test r + (lane + 1) << s, those whose square
+    # does not exceed n are counted, r grows by count << s.  Replayed here with 32-bit wrap-around products, as on the
+    # device, on every n next to a perfect square and on 10^6 random n.
+    n = _isqrt_inputs()
+    r = np.zeros_like(n)
+    for s in shifts:
+        cnt = np.zeros_like(n)
+        for lane in range(lanes):
+            c = r + (np.uint64(lane + 1) << np.uint64(s))
+            ok = (c <= 65535) & (((c * c) & np.uint64(0xffffffff)) <= n)
+            cnt += ok.astype(np.uint64)
+        r = r + (cnt << np.uint64(s))
+    _check_floor_sqrt(n, r)
+
+
+def test_shift_and_subtract_square_root_recipe_is_exact():
+    # the per-lane form: sixteen steps of an add, a compare and a conditional subtract
+    n0 = _isqrt_inputs()
+    n, res = n0.copy(), np.zeros_like(n0)
+    bit = np.uint64(1 << 30)
+    while bit:
+        t = res + bit
+        ge = n >= t
+        n = np.where(ge, n - t, n)
+        res = np.where(ge, (res >> np.uint64(1)) + bit, res >> np.uint64(1))
+        bit >>= np.uint64(2)
+    _check_floor_sqrt(n0, res)
