@@ -321,6 +321,26 @@ int ibert_encoder_layer_masked_i(const ibert_layer_weights* weights, const ibert
                                  int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn,
                                  const int32_t* key_lens, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ibert_encoder_layer_static_i -- ibert_encoder_layer_masked_i for callers that cannot allocate device memory and have
+ * no workspace to hand over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * intermediates live in an array inside the library's own device image (ibert_static_scratch_bytes() = 32 MiB; each GPU
+ * the library runs on holds its copy until the process ends) instead of a caller's workspace; the call allocates and frees
+ * nothing and gives the same y as ibert_encoder_layer_masked_i, bit for bit.  key_lens may be NULL (no padding).
+ * Limit: ibert_encoder_layer_workspace_bytes(batch, seq, hidden, heads, ffn) must not exceed
+ * ibert_static_scratch_bytes() -- e.g. up to 7 sequences of 128 tokens at hidden 768 / ffn 3072 -- else
+ * IBERT_ERR_WORKSPACE and nothing is launched.  All calls on one GPU share that GPU's array: calls that overlap in time on
+ * one GPU (two streams, two threads) race on it; calls on one stream, or ordered by events, are fine.  The array keeps
+ * the last call's intermediates; no step depends on them (each region is written before it is read).
+ * The array's address is looked up once per device, on the first call there (a host-side query of the loaded image, no
+ * allocation); ibert_static_scratch_init() does that lookup for the current device ahead of time, e.g. before a graph
+ * capture starts.  Errors otherwise as ibert_encoder_layer_masked_i. */
+size_t ibert_static_scratch_bytes(void);
+int ibert_static_scratch_init(void);
+int ibert_encoder_layer_static_i(const ibert_layer_weights* weights, const ibert_layer_quant* quant,
+                                 const int8_t* x, int8_t* y,
+                                 int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn,
+                                 const int32_t* key_lens, void* stream);
+
 /* n_layers layers back to back (layer l+1 reads layer l's output); weights/quant: host arrays of
  * n_layers entries.  x is not modified; y receives the last layer's output.  The workspace needs
  * ibert_encoder_workspace_bytes() (one layer's workspace plus two ping-pong activation buffers). */

@@ -123,6 +123,10 @@ SIGNATURES = {
     "ibert_encoder_layer_workspace_layout": (C.c_int, [C.c_int32] * 5 + [C.POINTER(WorkspaceLayout)]),
     "ibert_encoder_layer_i": (C.c_int, [C.POINTER(LayerWeights), C.POINTER(LayerQuant), _P, _P] + [C.c_int32] * 5 +
                               [_P, C.c_size_t, _P]),
+    "ibert_static_scratch_bytes": (C.c_size_t, []),
+    "ibert_static_scratch_init": (C.c_int, []),
+    "ibert_encoder_layer_static_i": (C.c_int, [C.POINTER(LayerWeights), C.POINTER(LayerQuant), _P, _P] + [C.c_int32] * 5 +
+                                     [_P, _P]),
     "ibert_encoder_workspace_bytes": (C.c_size_t, [C.c_int32] * 5),
     "ibert_encoder_i": (C.c_int, [C.POINTER(LayerWeights), C.POINTER(LayerQuant), C.c_int32, _P, _P] +
                         [C.c_int32] * 5 + [_P, C.c_size_t, _P]),
@@ -337,6 +341,20 @@ def ibert_encoder_layer_masked_i(weights: LayerWeights, quant: LayerQuant, x, y,
                                             ffn, _dp(key_lens), _dp(workspace),
                                             workspace.numel() * workspace.element_size(), _stream(stream)),
          "ibert_encoder_layer_masked_i")
+
+
+def ibert_static_scratch_bytes() -> int:
+    return int(lib().ibert_static_scratch_bytes())
+
+
+def ibert_static_scratch_init():
+    _chk(lib().ibert_static_scratch_init(), "ibert_static_scratch_init")
+
+
+def ibert_encoder_layer_static_i(weights: LayerWeights, quant: LayerQuant, x, y, batch, seq, hidden, heads, ffn,
+                                 key_lens=None, stream=None):
+    _chk(lib().ibert_encoder_layer_static_i(C.byref(weights), C.byref(quant), _dp(x), _dp(y), batch, seq, hidden, heads,
+                                            ffn, _dp(key_lens), _stream(stream)), "ibert_encoder_layer_static_i")
 
 
 def ibert_encoder_masked_i(weights, quant, n_layers: int, x, y, batch, seq, hidden, heads, ffn, key_lens, workspace,

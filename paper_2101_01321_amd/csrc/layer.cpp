@@ -2,10 +2,39 @@
 // kernel launches on one stream (Fig. 1 right; Sec. 4.1; App. C.1).  Host code only: validation,
 // workspace carving, enqueueing.  No allocation, no synchronisation.
 #include <cstring>
+#include <mutex>
 
 #include "common.h"
 
 namespace ibert {
+
+// Workspace of the layer call that takes none from its caller: one array in the library's own device image, so that
+// nothing is allocated at run time.  Every GPU the library runs on holds its own copy (at its own address) until the
+// process ends.  Host code must not use the array's name as an address: it asks the runtime for the copy's address
+// once per device (static_scratch_address) and uses that pointer from then on.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];          // per device: address of that device's copy of `scratch`
+static std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of `scratch`; looked up on the first call on each device.
+static int static_scratch_address(void** out)
+{
+    int dev = -1;
+    IBERT_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return IBERT_ERR_NOT_IMPLEMENTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        IBERT_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || !aligned(p, 256)) return IBERT_ERR_WORKSPACE;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return IBERT_OK;
+}
 
 static size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
@@ -401,6 +430,35 @@ int ibert_encoder_layer_masked_i(const ibert_layer_weights* weights, const ibert
     rc = ibert::check_layer(*weights, *quant, seq, hidden);
     if (rc) return rc;
     return ibert::run_layer(*weights, *quant, x, y, batch, seq, hidden, heads, ffn, key_lens, (char*)workspace, lo,
+                            (hipStream_t)stream);
+}
+
+size_t ibert_static_scratch_bytes(void) { return ibert::kStaticScratchBytes; }
+
+int ibert_static_scratch_init(void)
+{
+    void* p = nullptr;
+    return ibert::static_scratch_address(&p);
+}
+
+int ibert_encoder_layer_static_i(const ibert_layer_weights* weights, const ibert_layer_quant* quant, const int8_t* x,
+                                 int8_t* y, int32_t batch, int32_t seq, int32_t hidden, int32_t heads, int32_t ffn,
+                                 const int32_t* key_lens, void* stream)
+{
+    if (!weights || !quant || !x || !y) return IBERT_ERR_NULL;
+    ibert_layer_workspace_layout lo;
+    int rc = ibert::layout(batch, seq, hidden, heads, ffn, &lo);
+    if (rc) return rc;
+    if (x == y) return IBERT_ERR_SHAPE;
+    if (lo.total > ibert::kStaticScratchBytes) return IBERT_ERR_WORKSPACE;     // the problem needs more than the array holds
+    rc = ibert::check_layer(*weights, *quant, seq, hidden);
+    if (rc) return rc;
+    void* ws = nullptr;
+    rc = ibert::static_scratch_address(&ws);
+    if (rc) return rc;
+    // every region of the workspace is written by the step that produces it before any step reads it, so nothing of
+    // the previous call's contents has to be cleared
+    return ibert::run_layer(*weights, *quant, x, y, batch, seq, hidden, heads, ffn, key_lens, (char*)ws, lo,
                             (hipStream_t)stream);
 }
 
