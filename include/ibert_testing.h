@@ -17,6 +17,10 @@ extern "C" {
  * (Sec. 4.1's MatMuls are the same arithmetic under every tiling). */
 int ibert_gemm_config_override(int32_t config);
 
+/* Switch for A/B measurements: with `on` = 0 the MFMA MatMul gives each XCD a linear run of tiles instead of a near-square
+ * block of the tile grid (the default, which fetches fewer operand bytes over the fabric).  Process-wide. */
+void ibert_gemm_xcd_blocks(int32_t on);
+
 /* While `device_word` (device uint32, owned by the caller) is non-NULL, every MFMA MatMul launch of this process has its
  * first workgroup store there which form of the epilogue it ran -- the choice depends on the per-channel shifts and
  * biases, which only the device sees.  NULL switches the record off.  Process-wide, not thread-safe. */

@@ -98,6 +98,7 @@ SIGNATURES = {
     "ibert_gemm_i8_requant": (C.c_int, [C.POINTER(GemmDesc)] + [_P] * 8),
     "ibert_gemm_config_override": (C.c_int, [C.c_int32]),
     "ibert_gemm_epilogue_record": (None, [_P]),
+    "ibert_gemm_xcd_blocks": (None, [C.c_int32]),
     "ibert_gemm_i8_gelu": (C.c_int, [C.POINTER(GemmDesc)] + [_P] * 5 + [C.POINTER(GeluParams)] + [_P] * 3),
     "ibert_isqrt_i": (C.c_int, [_P, _P, C.c_int64, C.c_int32, _P]),
     "ibert_attention_scratch_bytes": (C.c_size_t, [C.c_int32] * 3),

@@ -9,13 +9,14 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libibert.so")
-SOURCES = ["host.cpp", "layer.cpp", "gelu.hip", "softmax.hip", "layernorm.hip", "attention.hip", "gemm.hip"]
+GEMM_UNITS = ["gemm_inst_%s.hip" % u for u in "abcdef"]      # the MFMA kernel's tile configurations, one group per unit
+SOURCES = GEMM_UNITS + ["gemm.hip", "attention.hip", "host.cpp", "layer.cpp", "gelu.hip", "softmax.hip", "layernorm.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-FP32 instruction forms are switched off for all device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # MFMA accumulators in ordinary vector registers (destination tied to the addend): with the accumulator-register
 # form the register allocator shuffles the accumulators between the two halves of the pipelined K step.
-SOURCE_FLAGS = {"gemm.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+SOURCE_FLAGS = {u: ["-mllvm", "-amdgpu-mfma-vgpr-form"] for u in GEMM_UNITS}
 
 
 def build(verbose: bool = False, extra_flags=()) -> str:
