@@ -356,6 +356,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
     // (direct-to-LDS kernels: the constants live in LDS behind the stages, requested before the loop starts, see below)
     int32_t* const par_early = reinterpret_cast<int32_t*>(lds + EL::LDS_BYTES);
     constexpr int PAR_BYTES = (3 * BN * 4 + 255) & ~255;
+    bool fast_early = false, fold_early = false;
 
     if constexpr (DMA) {
         // With eight wavefronts (two per SIMD) only the first four request tiles: a wavefront whose request waits for the
@@ -435,7 +436,11 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
             else if (younger == 2) __builtin_amdgcn_s_waitcnt(vm(2 * NL));
             else __builtin_amdgcn_s_waitcnt(vm(3 * NL));               // RING <= 4: never more than three
         };
-        const int npro = nk < NSTG ? nk : NSTG;
+        // With two stages only the first step is requested up front and the second during the first MFMA phase: the
+        // address unit takes as long over a stage's requests as the MFMAs of a phase take, so asking for both first
+        // would only delay the first MFMA by that much.
+        constexpr bool DEFER = NSTG == 2;
+        const int npro = DEFER ? 1 : (nk < NSTG ? nk : NSTG);
         {
             // The per-channel constants (bias, mult, shift: 3 x BN dwords) go from global memory straight into LDS behind
             // the stages, 64 dwords per request, the requests dealt round the wavefronts -- before the tile requests, so
@@ -475,11 +480,15 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
             // outside of which it is constant -- below q_b the result is DY(0), from the first saturated value up
             // it stays saturated -- so that the epilogue replaces ~17 instructions per value by a clamp and a byte
             // read.  Every workgroup builds its own copy with the very function the table stands for.
+            // (by the wavefronts that request no tiles, where there are such: the others are busy asking)
             int8_t* lut = lds + EL::LDS_BYTES + PAR_BYTES;
             const int32_t rnd = 1 << ((g.gelu.s - 33) & 31), sh = (g.gelu.s - 32) & 31;
-            for (int e = tid; e < g.gelu_lut_n; e += NT) {
-                const int32_t q = g.gelu_lut_lo + e;
-                lut[e] = (int8_t)(g.gelu_fast ? gelu_one_fast(q, g.gelu, rnd, sh) : gelu_one(q, g.gelu));
+            constexpr int NB = ND < NW ? NT - 64 * ND : NT;            // threads that build
+            if (ND == NW || !asker) {
+                for (int e = ND < NW ? tid - 64 * ND : tid; e < g.gelu_lut_n; e += NB) {
+                    const int32_t q = g.gelu_lut_lo + e;
+                    lut[e] = (int8_t)(g.gelu_fast ? gelu_one_fast(q, g.gelu, rnd, sh) : gelu_one(q, g.gelu));
+                }
             }
         }
         wait_landed(npro - 1);
@@ -487,6 +496,20 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
         v4i xa0[FM], wb0[FN], xa1[FM], wb1[FN];
 #pragma unroll
         for (int q = 0; q < NR; ++q) read_one(q, 0, 0, xa0, wb0);
+        {
+            // The constants have landed with the first stage.  Every wavefront looks at all BN channels itself and decides
+            // whether they allow the register-direct epilogue (see "Fast path" below): the same answer in all of
+            // them without another barrier, and nothing but the epilogue itself is left to do after the loop.
+            int badc = 0, bigs = 0;
+            for (int c = lane; c < BN; c += 64) {
+                const int32_t pbc = par_early[c], psc = par_early[2 * BN + c];
+                const int32_t ab = pbc < 0 ? -pbc : pbc;
+                badc |= (psc < 33 || psc > 62 || ab < 0 || ab >= (1 << 30)) ? 1 : 0;
+                bigs |= psc > 43 ? 1 : 0;
+            }
+            fast_early = __builtin_amdgcn_ballot_w64(badc != 0) == 0 && g.res_fast && (int64_t)g.K * 16129 < (1 << 30);
+            fold_early = __builtin_amdgcn_ballot_w64(bigs != 0) == 0;  // every shift at most 43
+        }
         // One K step.  Phase 1: slice 0 (fragments already in registers) while slice 1 is read.  Then this
         // wavefront's share of step kt+1 has landed and its reads of stage `buf` are done; after the barrier
         // that holds for the whole workgroup, so `buf` may be refilled and the next stage read.  Phase 2:
@@ -496,8 +519,12 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
             const int nbuf = buf + 1 == NSTG ? 0 : buf + 1;
             constexpr int QH = NSTG >= 3 ? (NL + 1) / 2 : NL;          // blocks requested in the second phase
             const int pbuf = buf == 0 ? NSTG - 1 : buf - 1;
-            phase(xa0, wb0, xa1, wb1, buf, 1, std::true_type{}, kt - 1 + NSTG, pbuf, asker && kt >= 1 && kt - 1 + NSTG < nk,
-                  std::integral_constant<int, QH>{}, std::integral_constant<int, NL>{});
+            if (DEFER && kt == 0)
+                phase(xa0, wb0, xa1, wb1, buf, 1, std::true_type{}, 1, 1, asker && nk > 1,
+                      std::integral_constant<int, 0>{}, std::integral_constant<int, NL>{});
+            else
+                phase(xa0, wb0, xa1, wb1, buf, 1, std::true_type{}, kt - 1 + NSTG, pbuf, asker && kt >= 1 && kt - 1 + NSTG < nk,
+                      std::integral_constant<int, QH>{}, std::integral_constant<int, NL>{});
             // steps requested after kt+1 so far: kt+2 .. min(kt+RING-1, nk-1)
             const int hi = kt + NSTG - 1 < nk - 1 ? kt + NSTG - 1 : nk - 1;
             wait_landed(hi - (kt + 1));
@@ -613,14 +640,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
     // three-operand clamp.
     bool fast;
     if constexpr (DMA) {
-        // every wavefront looks at all BN channels itself: the same answer in all of them without a barrier
-        int badc = 0;
-        for (int c = lane; c < BN; c += 64) {
-            const int32_t pbc = par[c], psc = par[2 * BN + c];
-            const int32_t ab = pbc < 0 ? -pbc : pbc;
-            badc |= (psc < 33 || psc > 62 || ab < 0 || ab >= (1 << 30)) ? 1 : 0;
-        }
-        fast = __builtin_amdgcn_ballot_w64(badc != 0) == 0 && g.res_fast && (int64_t)g.K * 16129 < (1 << 30);
+        fast = fast_early;
         if (R && interior) __syncthreads();                        // the residual tile is complete
     } else {
         fast = !__syncthreads_or(bad) && g.res_fast && (int64_t)g.K * 16129 < (1 << 30);
@@ -748,11 +768,19 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
     // are issued back to back, then they are packed and stored.
     // SM = how a lane's four values leave: 0 the lane's own store, 1 through LDS as whole row pieces (INT8: 16 bytes;
     // int16: 8 bytes).  ES = bytes per stored element (1, 2, 4).
-    auto finish_direct = [&](auto res_tag, auto gf_tag, auto lut_tag, auto sm_tag, auto es_tag) {
+    // FOLD (table form of GELU with every shift at most 43): the table's LDS address is folded into the requantization
+    // constant -- (acc m + c - (lo - base) 2^s) >> s = v - lo + base exactly, the subtrahend being a multiple of 2^s, and
+    // below 2^62 in magnitude, so the sum stays inside 64 bits -- which leaves a multiply-add, a shift, a clamp and a
+    // byte read per value.  (Byte loads into register halves would pack four values with one instruction, but with
+    // ECC on the register file they clear the other half instead of keeping it.)
+    auto finish_direct = [&](auto res_tag, auto gf_tag, auto lut_tag, auto sm_tag, auto es_tag, auto fold_tag) {
         constexpr bool RES = decltype(res_tag)::value, GF = decltype(gf_tag)::value, LUT = decltype(lut_tag)::value;
         constexpr int SM = decltype(sm_tag)::value, ES = decltype(es_tag)::value;
+        constexpr bool FOLD = decltype(fold_tag)::value;
+        static_assert(!FOLD || (LUT && ES == 1 && !RES), "folding belongs to the table form");
         static_assert((ES == 1) == OUT_I8, "INT8 kernels store bytes");
         const int8_t* const lut = lds + EL::LDS_BYTES + PAR_BYTES;
+        const uint32_t lut_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t*)lds + (uint32_t)(EL::LDS_BYTES + PAR_BYTES);
         const int32_t lut_hi = g.gelu_lut_n - 1;
         // staged row pitch in bytes (16-byte aligned rows): padded by one piece, or -- where only the bare tile fits and
         // a row is a whole number of 256-byte bank cycles -- unpadded with the pieces of a row permuted by the row
@@ -792,9 +820,35 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 cc[e] = (int64_t)bb[e] * mm[e] + ((int64_t)1 << ((ss[e] - 1) & 63));
+                if (FOLD) cc[e] -= (int64_t)(g.gelu_lut_lo - (int32_t)lut_lds) << (ss[e] & 63);
                 sh[e] = (ss[e] - 32) & 31;
             }
             uint32_t pk[FM];
+            if constexpr (FOLD) {
+                typedef const __attribute__((address_space(3))) uint8_t* lds_bytes;
+                uint32_t by[FM][4];
+#pragma unroll
+                for (int j = 0; j < FM; ++j)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int64_t p = (int64_t)acc[i][j][e] * mm[e] + cc[e];
+                        by[j][e] = (uint32_t)med3_i32((int32_t)(p >> 32) >> sh[e], (int32_t)lut_lds, (int32_t)lut_lds + lut_hi);
+                    }
+#pragma unroll
+                for (int j = 0; j < FM; ++j)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) by[j][e] = *(lds_bytes)(uintptr_t)by[j][e];
+#pragma unroll
+                for (int j = 0; j < FM; ++j) {
+                    const uint32_t pk4 = (by[j][0] | (by[j][1] << 8)) | ((by[j][2] | (by[j][3] << 8)) << 16);
+                    char* cp = c_base + ((uint32_t)(j * 16) * pitch + (uint32_t)(i * 16) * ES);
+                    const int row = wm0 + 16 * j + frow, colb = wn0 + 16 * i + 4 * fch;
+                    if (SM == 2) pq[i < 4 ? i : 0][j] = pk4;
+                    else if (SM == 1) *reinterpret_cast<uint32_t*>(ostage + ost_at(row, colb)) = pk4;
+                    else *reinterpret_cast<uint32_t*>(cp) = pk4;
+                }
+                continue;
+            }
             if (RES) {
 #pragma unroll
                 for (int j = 0; j < FM; ++j) pk[j] = r_base[j * 16 * G4 + i * 4];
@@ -925,10 +979,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
         if constexpr (LTS) {
             if (g.c_vec16 && !R) {
                 if constexpr (GELU) {
-                    if (g.gelu_lut_n > 0) finish_direct(F{}, F{}, T{}, I2s{}, I1{});
-                    else finish_direct(F{}, F{}, F{}, I2s{}, I1{});
+                    if (g.gelu_lut_n > 0) if (fold_early) finish_direct(F{}, F{}, T{}, I2s{}, I1{}, T{}); else finish_direct(F{}, F{}, T{}, I2s{}, I1{}, F{});
+                    else finish_direct(F{}, F{}, F{}, I2s{}, I1{}, F{});
                 } else {
-                    finish_direct(F{}, F{}, F{}, I2s{}, I1{});
+                    finish_direct(F{}, F{}, F{}, I2s{}, I1{}, F{});
                 }
                 stored = true;
             }
@@ -938,25 +992,25 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
             const bool via_lds = OST && g.c_vec16;
             if constexpr (GELU) {
                 if (g.gelu_lut_n > 0) {
-                    if constexpr (OST) { if (via_lds) finish_direct(F{}, F{}, T{}, I1{}, I1{}); else finish_direct(F{}, F{}, T{}, I0{}, I1{}); }
-                    else finish_direct(F{}, F{}, T{}, I0{}, I1{});
+                    if constexpr (OST) { if (via_lds) if (fold_early) finish_direct(F{}, F{}, T{}, I1{}, I1{}, T{}); else finish_direct(F{}, F{}, T{}, I1{}, I1{}, F{}); else if (fold_early) finish_direct(F{}, F{}, T{}, I0{}, I1{}, T{}); else finish_direct(F{}, F{}, T{}, I0{}, I1{}, F{}); }
+                    else if (fold_early) finish_direct(F{}, F{}, T{}, I0{}, I1{}, T{}); else finish_direct(F{}, F{}, T{}, I0{}, I1{}, F{});
                 } else {
-                    finish_direct(F{}, F{}, F{}, I0{}, I1{});
+                    finish_direct(F{}, F{}, F{}, I0{}, I1{}, F{});
                 }
             } else {
                 if constexpr (OST) {
-                    if (via_lds) { if (R) finish_direct(T{}, F{}, F{}, I1{}, I1{}); else finish_direct(F{}, F{}, F{}, I1{}, I1{}); }
-                    else { if (R) finish_direct(T{}, F{}, F{}, I0{}, I1{}); else finish_direct(F{}, F{}, F{}, I0{}, I1{}); }
+                    if (via_lds) { if (R) finish_direct(T{}, F{}, F{}, I1{}, I1{}, F{}); else finish_direct(F{}, F{}, F{}, I1{}, I1{}, F{}); }
+                    else { if (R) finish_direct(T{}, F{}, F{}, I0{}, I1{}, F{}); else finish_direct(F{}, F{}, F{}, I0{}, I1{}, F{}); }
                 } else {
-                    if (R) finish_direct(T{}, F{}, F{}, I0{}, I1{}); else finish_direct(F{}, F{}, F{}, I0{}, I1{});
+                    if (R) finish_direct(T{}, F{}, F{}, I0{}, I1{}, F{}); else finish_direct(F{}, F{}, F{}, I0{}, I1{}, F{});
                 }
             }
         } else {
             if (g.c16) {
-                if constexpr (OST16) { if (R) finish_direct(T{}, F{}, F{}, I1{}, I2{}); else finish_direct(F{}, F{}, F{}, I1{}, I2{}); }
-                else { if (R) finish_direct(T{}, F{}, F{}, I0{}, I2{}); else finish_direct(F{}, F{}, F{}, I0{}, I2{}); }
+                if constexpr (OST16) { if (R) finish_direct(T{}, F{}, F{}, I1{}, I2{}, F{}); else finish_direct(F{}, F{}, F{}, I1{}, I2{}, F{}); }
+                else { if (R) finish_direct(T{}, F{}, F{}, I0{}, I2{}, F{}); else finish_direct(F{}, F{}, F{}, I0{}, I2{}, F{}); }
             } else {
-                if (R) finish_direct(T{}, F{}, F{}, I0{}, I4{}); else finish_direct(F{}, F{}, F{}, I0{}, I4{});
+                if (R) finish_direct(T{}, F{}, F{}, I0{}, I4{}, F{}); else finish_direct(F{}, F{}, F{}, I0{}, I4{}, F{});
             }
         }
     } else
