@@ -146,6 +146,54 @@ def latency_grid(args):
                       "cells": cells}))
 
 
+def standalone_kernels(mode, launches):
+    """The three non-linear kernels on their own at the activation shapes of Base b32 (INT32 in, INT8 out, 5 bytes per
+    element), for a kernel trace: `warm` launches each on one pair of buffers (which stays in the 256 MB last-level
+    cache), `cold` cycles through enough distinct buffer pairs to exceed 1 GiB, so that every launch finds its input in
+    HBM.  Prints one JSON line with the per-launch times measured with events."""
+    import torch
+    from paper_2101_01321_amd import binding as B, synth
+
+    B.lib()
+    dev = torch.device("cuda:0")
+    c = synth.CONFIGS["base_b32"]
+    BH = c.batch * c.heads
+    sx, sS = synth.softmax_logits(BH * c.seq, c.seq)
+    gx, gS = synth.gelu_inputs(c.tokens, c.ffn)
+    lx, _, l_gamma, l_beta = synth.layernorm_inputs(c.tokens, c.hidden)
+    sp_ = B.ibert_softmax_params_from_scale(sS, c.seq)
+    gp = B.ibert_gelu_params_from_scale(gS, 8.0 / 127)
+    lgq, lbq, lsh = B.ibert_layernorm_params_from_float(l_gamma, l_beta, 5.0 / 127)
+    t_lgq, t_lbq = torch.from_numpy(lgq).to(dev), torch.from_numpy(lbq).to(dev)
+    cases = {
+        "i_softmax [%d,%d]" % (BH * c.seq, c.seq): (sx, lambda a_, b_: B.ibert_softmax_i(a_, b_, BH * c.seq, c.seq, c.seq, c.seq, sp_)),
+        "i_gelu [%d,%d]" % (c.tokens, c.ffn): (gx, lambda a_, b_: B.ibert_gelu_i(a_, b_, gx.size, gp)),
+        "i_layernorm [%d,%d]" % (c.tokens, c.hidden): (lx, lambda a_, b_: B.ibert_layernorm_i(a_, b_, c.tokens, c.hidden, c.hidden,
+                                                                                                 c.hidden, t_lgq, t_lbq, lsh)),
+    }
+    out = {}
+    for name, (x, call) in cases.items():
+        pair_bytes = 5 * x.size
+        n_buf = 1 if mode == "warm" else max(4, -(-(1 << 30) // pair_bytes) + 1)
+        fill = torch.from_numpy(x.reshape(-1)).to(dev)
+        ins = [fill.clone() for _ in range(n_buf)]
+        outs = [torch.empty(x.size, dtype=torch.int8, device=dev) for _ in range(n_buf)]
+        for k in range(max(3, n_buf)):
+            call(ins[k % n_buf], outs[k % n_buf])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for k in range(launches):
+            call(ins[k % n_buf], outs[k % n_buf])
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / launches
+        out[name] = {"us_per_launch_host_loop": round(us, 2), "algorithmic_bytes": pair_bytes, "buffers": n_buf}
+        del ins, outs
+        torch.cuda.empty_cache()
+    print(json.dumps({"standalone": mode, "launches": launches, "kernels": out}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -161,6 +209,9 @@ def main():
                     help="ibert_layer_quant.route of every layer (1: GELU as a kernel of its own, 2: attention as three kernels, "
                          "4: 32-bit LayerNorm inputs); default 0: every fusion")
     ap.add_argument("--print-digest", action="store_true", help="print the digest of the kernel sources and exit")
+    ap.add_argument("--standalone", choices=["warm", "cold"],
+                    help="instead of the headline workload: only the three non-linear kernels at Base b32 shapes, launched from the "
+                         "host --steps times each on one buffer pair (warm) or cycling through > 1 GiB of buffers (cold)")
     ap.add_argument("--latency-grid", action="store_true",
                     help="instead of the headline workload: Base/Large x seq 128/256 x batch 1/2/4/8, integer path vs a PyTorch float encoder")
     args = ap.parse_args()
@@ -173,6 +224,8 @@ def main():
         return
     if args.latency_grid:
         return latency_grid(args)
+    if args.standalone:
+        return standalone_kernels(args.standalone, max(args.steps, 40))
 
     import numpy as np
     import torch

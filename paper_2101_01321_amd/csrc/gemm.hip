@@ -103,7 +103,6 @@ static const GemmConfig kConfigs[] = {      // index = configuration number of i
 constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 static int g_config_override = -1;
 static bool g_xcd_blocks = true;
-static int g_wt = 0;
 bool xcd_blocks_enabled() { return g_xcd_blocks; }
 static uint32_t* g_path_word = nullptr;
 
@@ -223,7 +222,6 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
     const bool i8 = d.out_dtype == IBERT_I8;
     g.c16 = d.out_dtype == IBERT_I16 ? 1 : 0;
     g.path_word = g_path_word;
-    g.wt = g_wt;
     g.gelu_fast = 0;
     g.gelu = GeluConst{0, 0, 0, 0, 0, 0};
     g.gelu_lut_lo = g.gelu_lut_n = 0;
@@ -336,7 +334,6 @@ extern "C" int ibert_gemm_config_override(int32_t config)
     return ibert::kNumConfigs;
 }
 
-extern "C" void ibert_gemm_wt(int32_t v) { ibert::g_wt = v; }
 
 extern "C" void ibert_gemm_xcd_blocks(int32_t on) { ibert::g_xcd_blocks = on != 0; }
 

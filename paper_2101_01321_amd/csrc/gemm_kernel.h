@@ -57,7 +57,6 @@ struct GemmArgs {
     int32_t gelu_lut_lo, gelu_lut_n;   // GELU epilogue: table of the values at lo .. lo + n - 1 behind the tile's LDS (n = 0: none)
     GeluConst gelu;    // GELU epilogue: constants (the clamp before it is out_clamp = q_max)
     uint32_t* path_word;   // tests only (may be null): workgroup 0 records which epilogue form it ran
-    int32_t wt;            // experiment: cache policy of the lane-transposed stores
 };
 
 // Requantize one accumulator and finish the output value (before the store).
@@ -913,12 +912,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
                 t = __builtin_amdgcn_permlane16_swap(r0, r1, false, false); r0 = t.x; r1 = t.y;
                 t = __builtin_amdgcn_permlane16_swap(r2, r3, false, false); r2 = t.x; r3 = t.y;
                 if (fch < FN) {
-                    const v4i val = v4i{(int)r0, (int)r1, (int)r2, (int)r3};
-                    char* const dst = c16 + (uint32_t)(j * 16) * pitch;
-                    if (g.wt == 1) asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" :: "v"(dst), "v"(val) : "memory");
-                    else if (g.wt == 2) asm volatile("global_store_dwordx4 %0, %1, off nt" :: "v"(dst), "v"(val) : "memory");
-                    else if (g.wt == 3) asm volatile("global_store_dwordx4 %0, %1, off sc1" :: "v"(dst), "v"(val) : "memory");
-                    else *reinterpret_cast<v4i*>(dst) = val;
+                    *reinterpret_cast<v4i*>(c16 + (uint32_t)(j * 16) * pitch) = v4i{(int)r0, (int)r1, (int)r2, (int)r3};
                 }
             }
         }
