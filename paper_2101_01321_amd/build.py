@@ -16,7 +16,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # MFMA accumulators in ordinary vector registers (destination tied to the addend): with the accumulator-register
 # form the register allocator shuffles the accumulators between the two halves of the pipelined K step.
-SOURCE_FLAGS = {u: ["-mllvm", "-amdgpu-mfma-vgpr-form"] for u in GEMM_UNITS}
+SOURCE_FLAGS = {u: ["-mllvm", "-amdgpu-mfma-vgpr-form"] for u in GEMM_UNITS + ["attention.hip"]}
 
 
 def build(verbose: bool = False, extra_flags=()) -> str:

@@ -52,19 +52,23 @@ __device__ __forceinline__ int swz64(int row) { return (row >> 1) & 3; }      //
 // DY(x; m, s) for |x| < 2^b when b <= s <= 62 (b <= 23): x m + 2^(s-1) fits 63 bits and the result fits 32 (it is
 // below 2^(b+31-s)), so the floor-division by 2^s is bits [s, s+32) of the 64-bit sum: the high dword shifted by
 // s - 32, or for s < 32 a funnel shift of the two dwords.  rnd = 2^(s-1).
+// HI (the shift is known to be at least 32, the usual case: a multiplier in [2^30, 2^31) and a scale ratio below 1/2):
+// only the first form, two instructions a value.
+template <bool HI>
 __device__ __forceinline__ int32_t dyadic_hi(int32_t x, int32_t m, int64_t rnd, int32_t sh)
 {
     const int64_t p = (int64_t)x * m + rnd;
     const int32_t hi = (int32_t)(p >> 32);
     const int32_t a = hi >> ((sh - 32) & 31);
+    if (HI) return a;
     const int32_t b = (int32_t)__builtin_amdgcn_alignbit((uint32_t)hi, (uint32_t)p, (uint32_t)(sh & 31));
     return sh >= 32 ? a : b;
 }
 
 // FAST: the 24-bit Softmax forms apply.  RQ: the scores shift is in [21, 62] and the context shift in [23, 62]
 // (accumulators: 64 products of INT8 pairs, below 2^21; up to 512 products of a probability and an INT8 value,
-// below 2^23), so dyadic_hi applies; |scores| then stays below 2^31 and needs no clamp.
-template <int NKB, bool FAST, bool RQ>                    // NKB: key blocks of 64 (L = 64 NKB)
+// below 2^23), so dyadic_hi applies; |scores| then stays below 2^31 and needs no clamp.  RQ = 2: both are at least 32.
+template <int NKB, bool FAST, int RQ>                     // NKB: key blocks of 64 (L = 64 NKB)
 __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttentionArgs a)
 {
     constexpr int ATT_L = 64 * NKB, QBLKS = ATT_L / ATT_QB, NI = ATT_L / 16;
@@ -144,7 +148,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttentionArgs a)
         const v4i acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(kf, qf, v4i{0, 0, 0, 0}, 0, 0, 0);
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            sc[i][r] = RQ ? dyadic_hi(acc[r], a.s_m, s_rnd, a.s_s) : clamp_i64_to_i32(dyadic64(acc[r], a.s_m, a.s_s), 2147483647);
+            sc[i][r] = RQ ? dyadic_hi<RQ == 2>(acc[r], a.s_m, s_rnd, a.s_s) : clamp_i64_to_i32(dyadic64(acc[r], a.s_m, a.s_s), 2147483647);
     }
     if (a.key_lens) {                                      // uniform over the workgroup
         int32_t nk = a.key_lens[b];
@@ -210,7 +214,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttentionArgs a)
         int32_t o[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            o[r] = RQ ? med3_i32(dyadic_hi(acc[r], a.c_m, c_rnd, a.c_s), -127, 127) : clamp_i64_to_i32(dyadic64(acc[r], a.c_m, a.c_s), 127);
+            o[r] = RQ ? med3_i32(dyadic_hi<RQ == 2>(acc[r], a.c_m, c_rnd, a.c_s), -127, 127) : clamp_i64_to_i32(dyadic64(acc[r], a.c_m, a.c_s), 127);
         *reinterpret_cast<uint32_t*>(out + 16 * cb) = pack4_i8(o[0], o[1], o[2], o[3]);
     }
 }
@@ -223,7 +227,7 @@ bool attention_fused_ok(const int8_t* qkv, const int8_t* ctx, int32_t seq, int32
 }
 
 template <int NKB>
-static int launch_attention_l(const AttentionArgs& a, int64_t blocks, bool fast, bool rq, hipStream_t stream)
+static int launch_attention_l(const AttentionArgs& a, int64_t blocks, bool fast, int rq, hipStream_t stream)
 {
     constexpr int L = 64 * NKB;
     constexpr size_t lds_bytes = (size_t)L * ATT_DH + ATT_QB * ATT_DH + (size_t)ATT_DH * L;
@@ -240,9 +244,9 @@ static int launch_attention_l(const AttentionArgs& a, int64_t blocks, bool fast,
         hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, a);                                              \
     } while (0)
     if (fast) {
-        if (rq) IBERT_ATT_LAUNCH(true, true); else IBERT_ATT_LAUNCH(true, false);
+        if (rq == 2) IBERT_ATT_LAUNCH(true, 2); else if (rq) IBERT_ATT_LAUNCH(true, 1); else IBERT_ATT_LAUNCH(true, 0);
     } else {
-        if (rq) IBERT_ATT_LAUNCH(false, true); else IBERT_ATT_LAUNCH(false, false);
+        if (rq) IBERT_ATT_LAUNCH(false, 1); else IBERT_ATT_LAUNCH(false, 0);
     }
 #undef IBERT_ATT_LAUNCH
     return IBERT_OK;
@@ -264,7 +268,8 @@ int launch_attention(const int8_t* qkv, int8_t* ctx, int32_t batch, int32_t seq,
     a.sm = softmax_const(sp);
     a.key_lens = key_lens;
     // register-only requantization: accumulators are below 64*127^2 (scores) and L*127*127 (context) < 2^23
-    const bool rq = a.s_s >= 21 && a.s_s <= 62 && a.c_s >= 23 && a.c_s <= 62;
+    const int rq = (a.s_s >= 32 && a.s_s <= 62 && a.c_s >= 32 && a.c_s <= 62) ? 2
+                   : ((a.s_s >= 21 && a.s_s <= 62 && a.c_s >= 23 && a.c_s <= 62) ? 1 : 0);
     const bool fast = softmax_fast_ok(sp);
     int rc;
     switch (seq) {
