@@ -52,26 +52,29 @@ __device__ __forceinline__ int swz64(int row) { return (row >> 1) & 3; }      //
 // DY(x; m, s) for |x| < 2^b when b <= s <= 62 (b <= 23): x m + 2^(s-1) fits 63 bits and the result fits 32 (it is
 // below 2^(b+31-s)), so the floor-division by 2^s is bits [s, s+32) of the 64-bit sum: the high dword shifted by
 // s - 32, or for s < 32 a funnel shift of the two dwords.  rnd = 2^(s-1).
-// HI (the shift is known to be at least 32, the usual case: a multiplier in [2^30, 2^31) and a scale ratio below 1/2):
-// only the first form, two instructions a value.
-template <bool HI>
+// FORM 1: the shift is known to be at least 32 (a scale ratio below 1/2), FORM 2: known to be below 32 -- only that
+// form is computed, two instructions a value; FORM 0: both and a select.
+template <int FORM>
 __device__ __forceinline__ int32_t dyadic_hi(int32_t x, int32_t m, int64_t rnd, int32_t sh)
 {
     const int64_t p = (int64_t)x * m + rnd;
     const int32_t hi = (int32_t)(p >> 32);
     const int32_t a = hi >> ((sh - 32) & 31);
-    if (HI) return a;
+    if (FORM == 1) return a;
     const int32_t b = (int32_t)__builtin_amdgcn_alignbit((uint32_t)hi, (uint32_t)p, (uint32_t)(sh & 31));
+    if (FORM == 2) return b;
     return sh >= 32 ? a : b;
 }
 
 // FAST: the 24-bit Softmax forms apply.  RQ: the scores shift is in [21, 62] and the context shift in [23, 62]
 // (accumulators: 64 products of INT8 pairs, below 2^21; up to 512 products of a probability and an INT8 value,
-// below 2^23), so dyadic_hi applies; |scores| then stays below 2^31 and needs no clamp.  RQ = 2: both are at least 32.
+// below 2^23), so dyadic_hi applies; |scores| then stays below 2^31 and needs no clamp.  RQ = 2 .. 5 say in addition on
+// which side of 32 each shift lies: RQ - 2 = (scores shift >= 32) + 2 (context shift >= 32).
 template <int NKB, bool FAST, int RQ>                     // NKB: key blocks of 64 (L = 64 NKB)
 __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttentionArgs a)
 {
     constexpr int ATT_L = 64 * NKB, QBLKS = ATT_L / ATT_QB, NI = ATT_L / 16;
+    constexpr int S_FORM = RQ < 2 ? 0 : (((RQ - 2) & 1) ? 1 : 2), C_FORM = RQ < 2 ? 0 : (((RQ - 2) & 2) ? 1 : 2);
     extern __shared__ __attribute__((aligned(16))) int8_t att_lds[];
     int8_t* const ks = att_lds;                                               // K_h, row-major [L][64]
     int8_t* const qs = att_lds + ATT_L * ATT_DH;                              // the block's queries [64][64]
@@ -148,7 +151,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttentionArgs a)
         const v4i acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(kf, qf, v4i{0, 0, 0, 0}, 0, 0, 0);
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            sc[i][r] = RQ ? dyadic_hi<RQ == 2>(acc[r], a.s_m, s_rnd, a.s_s) : clamp_i64_to_i32(dyadic64(acc[r], a.s_m, a.s_s), 2147483647);
+            sc[i][r] = RQ ? dyadic_hi<S_FORM>(acc[r], a.s_m, s_rnd, a.s_s) : clamp_i64_to_i32(dyadic64(acc[r], a.s_m, a.s_s), 2147483647);
     }
     if (a.key_lens) {                                      // uniform over the workgroup
         int32_t nk = a.key_lens[b];
@@ -214,7 +217,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttentionArgs a)
         int32_t o[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            o[r] = RQ ? med3_i32(dyadic_hi<RQ == 2>(acc[r], a.c_m, c_rnd, a.c_s), -127, 127) : clamp_i64_to_i32(dyadic64(acc[r], a.c_m, a.c_s), 127);
+            o[r] = RQ ? med3_i32(dyadic_hi<C_FORM>(acc[r], a.c_m, c_rnd, a.c_s), -127, 127) : clamp_i64_to_i32(dyadic64(acc[r], a.c_m, a.c_s), 127);
         *reinterpret_cast<uint32_t*>(out + 16 * cb) = pack4_i8(o[0], o[1], o[2], o[3]);
     }
 }
@@ -244,9 +247,15 @@ static int launch_attention_l(const AttentionArgs& a, int64_t blocks, bool fast,
         hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, a);                                              \
     } while (0)
     if (fast) {
-        if (rq == 2) IBERT_ATT_LAUNCH(true, 2); else if (rq) IBERT_ATT_LAUNCH(true, 1); else IBERT_ATT_LAUNCH(true, 0);
+        switch (rq) {
+            case 0: IBERT_ATT_LAUNCH(true, 0); break;
+            case 2: IBERT_ATT_LAUNCH(true, 2); break;
+            case 3: IBERT_ATT_LAUNCH(true, 3); break;
+            case 4: IBERT_ATT_LAUNCH(true, 4); break;
+            default: IBERT_ATT_LAUNCH(true, 5); break;
+        }
     } else {
-        if (rq) IBERT_ATT_LAUNCH(false, 1); else IBERT_ATT_LAUNCH(false, 0);
+        if (rq) IBERT_ATT_LAUNCH(false, 1); else IBERT_ATT_LAUNCH(false, 0);      // (the general Softmax forms dominate there)
     }
 #undef IBERT_ATT_LAUNCH
     return IBERT_OK;
@@ -268,8 +277,7 @@ int launch_attention(const int8_t* qkv, int8_t* ctx, int32_t batch, int32_t seq,
     a.sm = softmax_const(sp);
     a.key_lens = key_lens;
     // register-only requantization: accumulators are below 64*127^2 (scores) and L*127*127 (context) < 2^23
-    const int rq = (a.s_s >= 32 && a.s_s <= 62 && a.c_s >= 32 && a.c_s <= 62) ? 2
-                   : ((a.s_s >= 21 && a.s_s <= 62 && a.c_s >= 23 && a.c_s <= 62) ? 1 : 0);
+    const int rq = (a.s_s >= 21 && a.s_s <= 62 && a.c_s >= 23 && a.c_s <= 62) ? 2 + (a.s_s >= 32 ? 1 : 0) + (a.c_s >= 32 ? 2 : 0) : 0;
     const bool fast = softmax_fast_ok(sp);
     int rc;
     switch (seq) {

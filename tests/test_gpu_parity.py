@@ -320,6 +320,9 @@ def _attention_oracle(qkv, B_, L, H, nh, scores_dy, op, ctx_dy):
     (1, 12, 128, 2.0 ** -6, (1920459399, 38), (1518500250, 36)),
     (2, 2, 128, 2.0 ** -6, (1187698534, 28), (1073741824, 37)),        # a multiplier above one: funnel-shift form
     (1, 3, 128, 2.0 ** -6, (1187698534, 32), (2800, 21)),        # shifts at the edges of the two forms
+    (2, 2, 128, 2.0 ** -6, (1187698534, 28), (700000, 25)),             # both shifts below 32, and each side of 32 in turn
+    (1, 3, 128, 2.0 ** -6, (1187698534, 32), (1400000, 26)),
+    (1, 2, 256, 2.0 ** -6, (1187698534, 31), (1073741824, 37)),
     (1, 2, 128, 2.0 ** -5, (1187698534, 20), (1518500250, 33)),        # below the fast range: general form
     (3, 2, 128, 2.0 ** -2, (1518500250, 41), (1073741824, 37)),       # q_ln2 = 2: the general Softmax path
     (2, 2, 128, 2.0 ** -9, (1518500250, 30), (1073741824, 35)),       # wide logits, context clamps at 127
