@@ -99,6 +99,7 @@ static const GemmConfig kConfigs[] = {      // index = configuration number of i
     {64, 96, 128, 3, true},
     {64, 96, 128, 2, true},
     {64, 128, 128, 2, true},
+    {128, 96, 128, 3, true},        // with eight wavefronts (four rows of two)
 };
 constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 static int g_config_override = -1;
@@ -174,7 +175,9 @@ static int choose_config(const ibert_gemm_desc& d, int64_t nb, bool gelu)
         // (exactly one 128x96 tile per CU and a 16- or 32-bit output: 64x96 tiles, three or four of which share a CU, so
         //  that one's epilogue overlaps another's loop -- inside the encoder S5 of Base 9.7 -> 8.9 us, S9 17.9 -> 17.3 us;
         //  a fourth LDS stage leaves room for one workgroup per CU only and loses, 24 us.)
-        if (tiles(128, 96) <= 256 && d.out_dtype != IBERT_I8 && !gelu) return d.K >= 2048 ? 17 : 18;
+        // (a long K instead: the whole 128x96 tile with eight wavefronts in four rows of two and three stages -- half the
+        //  barriers per MFMA and 30 % fewer bytes from L2 than two 64x96 tiles: S9 of Base 16.85 -> 16.23 us inside the encoder)
+        if (tiles(128, 96) <= 256 && d.out_dtype != IBERT_I8 && !gelu) return d.K >= 2048 ? 20 : 18;
         return tiles(128, 96) <= 256 && d.K >= 2048 ? 11 : 9;
     }
     // (eight wavefronts for INT8 outputs: S7+S8 of Large 34.7 -> 32.5 us; INT32 outputs lose 5 % with them)
@@ -277,6 +280,7 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
             case 17: if (dma_ok(d, 64, 96)) return launch_mfma<64, 96, 128, 3, false, true>(g, i8, stream); break;
             case 18: if (dma_ok(d, 64, 96)) return launch_mfma<64, 96, 128, 2, false, true>(g, i8, stream); break;
             case 19: if (dma_ok(d, 64, 128)) return launch_mfma<64, 128, 128, 2, false, true>(g, i8, stream); break;
+            case 20: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 3, false, true, false, 8>(g, i8, stream); break;
             default: break;
         }
         return launch_mfma<128, 128, 64, 2>(g, i8, stream);

@@ -153,6 +153,8 @@ template <int BM, int BN, int BK, int RING, bool OUT_I8, int KMODE, bool TW = fa
 __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
 {
     // NW wavefronts in two rows of NW/2: wavefront w owns rows [(w%2) BM/2, +BM/2) and columns [(w/2) WN, +WN) of the tile.
+    // (Eight wavefronts on a tile whose width does not divide into four strips of whole MFMA blocks -- 128x96 -- stand in
+    // four rows of two instead: rows [(w%4) BM/4, +BM/4), columns [(w/4) BN/2, +BN/2).)
     // Eight (two per SIMD) pay for INT8 tiles of 256x192: the second wavefront hides what the first waits for in the loop
     // and in the packing epilogue (inside the encoder: S1 of Large 21.4 -> 19.9 us, S7+S8 of Base 20.6 -> 19.3 us).
     constexpr int NT = 64 * NW;
@@ -161,10 +163,12 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
     constexpr int CPR = BK / 16;                       // 16-byte chunks per tile row
     constexpr int RPP = NT / CPR;            // tile rows loaded per pass of the workgroup
     constexpr int LA = BM / RPP, LW = BN / RPP;        // chunks per lane per K step
-    constexpr int WM = BM / 2, WN = BN / (NW / 2);     // wavefront tile
+    constexpr bool R4 = NW == 8 && (BN / 4) % 16 != 0;  // four rows of two wavefronts
+    constexpr int WR = R4 ? 4 : 2;                      // rows of wavefronts
+    constexpr int WM = BM / WR, WN = BN / (NW / WR);    // wavefront tile
     constexpr int FM = WM / 16, FN = WN / 16;
     constexpr int NS = BK / 64;                        // 64-wide K slices per step
-    static_assert(BM % RPP == 0 && BN % RPP == 0 && WM % 16 == 0 && WN % 16 == 0, "tile shape");
+    static_assert((DMA || (BM % RPP == 0 && BN % RPP == 0)) && WM % 16 == 0 && WN % 16 == 0, "tile shape");
     static_assert(!TW || (BK / 4) * (BN / 4) == LW * NT, "transposing loader covers the W tile exactly");
 
     // The argument block spans five 64-byte lines of a scalar cache that is cold when a kernel starts, and the compiler
@@ -188,7 +192,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
+    const int wm0 = (wave & (WR - 1)) * WM, wn0 = (wave / WR) * WN;
 
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles so that
     // the A panels and W panels it touches stay in its own L2.
@@ -585,7 +589,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
     constexpr int SP = EL::SP, JC = EL::JC;
     constexpr int G4 = BN / 4;                                     // 4-channel groups per row
     constexpr int RPS = NT / G4;                         // rows finished per pass of the workgroup
-    static_assert(FM % JC == 0 && RPS >= 1, "epilogue layout");
+    // JCW: MFMA block rows of a wavefront per staged chunk (with four rows of wavefronts the chunk is the whole tile)
+    constexpr int JCW = R4 ? FM : JC;
+    static_assert(FM % JCW == 0 && RPS >= 1 && 16 * WR * JCW == 32 * JC, "epilogue layout");
     int32_t* stage = reinterpret_cast<int32_t*>(lds);              // [32 * JC][SP]
     // [3][BN]: bias, mult, shift -- behind the stages for the direct-to-LDS kernels (written before the loop), else
     // behind the staging tile
@@ -645,7 +651,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
         fast = !__syncthreads_or(bad) && g.res_fast && (int64_t)g.K * 16129 < (1 << 30);
     }
 
-    const int wrow = wave & 1;
+    const int wrow = wave & (WR - 1);
     const int c4 = tid % G4, r0 = tid / G4;                        // lane = (row of the pass, 4-channel group)
     const int col = c4 * 4, n = n0 + col;
     const v4i b4 = *reinterpret_cast<const v4i*>(par + col);
@@ -653,7 +659,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
     const v4i s4 = *reinterpret_cast<const v4i*>(par + 2 * BN + col);
 
     auto tile_row = [&](int jc0, int lr) {                         // row inside the BM x BN tile of chunk row lr
-        const int w = lr / (16 * JC), rem = lr - w * 16 * JC;      // rem = 16 * jj + row-in-block
+        const int w = lr / (16 * JCW), rem = lr - w * 16 * JCW;    // rem = 16 * jj + row-in-block
         return w * WM + 16 * jc0 + rem;
     };
     // Fast-path constants of the lane's four channels: c0 = bias*m + 2^(s-1) (64 bits), so that one
@@ -1009,17 +1015,17 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
         }
     } else
 #pragma unroll
-    for (int jc = 0; jc < FM / JC; ++jc) {
+    for (int jc = 0; jc < FM / JCW; ++jc) {
         if (jc > 0) __syncthreads();                               // the previous chunk has been consumed
 #pragma unroll
-        for (int jj = 0; jj < JC; ++jj)
+        for (int jj = 0; jj < JCW; ++jj)
 #pragma unroll
             for (int i = 0; i < FN; ++i)
-                *reinterpret_cast<v4i*>(stage + ((wrow * JC + jj) * 16 + frow) * SP + wn0 + i * 16 + fch * 4) = acc[i][jc * JC + jj];
+                *reinterpret_cast<v4i*>(stage + ((wrow * JCW + jj) * 16 + frow) * SP + wn0 + i * 16 + fch * 4) = acc[i][jc * JCW + jj];
         __syncthreads();
-        if (!interior) finish_edge(jc * JC);
-        else if (fast) finish_interior(jc * JC, std::true_type{});
-        else finish_interior(jc * JC, std::false_type{});
+        if (!interior) finish_edge(jc * JCW);
+        else if (fast) finish_interior(jc * JCW, std::true_type{});
+        else finish_interior(jc * JCW, std::false_type{});
     }
 }
 

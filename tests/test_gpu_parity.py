@@ -390,7 +390,9 @@ def test_gemm_trans_w_mfma_path(G, M, N, K, ldw):
                                        (17, 64, 96, 128), (17, 128, 192, 256), (17, 192, 96, 384), (17, 256, 288, 1024),
                                        (18, 64, 96, 128), (18, 128, 192, 256), (18, 64, 96, 512), (18, 128, 96, 640),
                                        # 64x128
-                                       (19, 64, 128, 128), (19, 128, 256, 256), (19, 192, 128, 384), (19, 256, 384, 1024)])
+                                       (19, 64, 128, 128), (19, 128, 256, 256), (19, 192, 128, 384), (19, 256, 384, 1024),
+                                       # 128x96 with eight wavefronts in four rows of two, three stages
+                                       (20, 128, 96, 128), (20, 256, 192, 256), (20, 128, 288, 640), (20, 384, 96, 1024)])
 def test_gemm_direct_to_lds_tiles(G, cfg, M, N, K):
     # the tile configurations whose loader writes LDS straight from global memory (whole tiles only), forced
     # through the configuration override; 1, 2, odd and even numbers of K steps
@@ -402,6 +404,41 @@ def test_gemm_direct_to_lds_tiles(G, cfg, M, N, K):
             _gemm_case(G, M, N, K, out_dtype, pc, bias, res, seed=cfg + M + N + K)
     finally:
         B.lib().ibert_gemm_config_override(-1)
+
+
+@pytest.mark.parametrize("shift,form", [(40, "direct"), (30, "staged")])
+@pytest.mark.parametrize("out_dtype,res", [(I8, False), (I8, True), (I16, True), (I32, True), (I32, False)])
+def test_gemm_four_rows_of_wavefronts_epilogue_forms(G, out_dtype, res, shift, form):
+    # The 128x96 tile whose eight wavefronts stand in four rows of two: both epilogue forms -- the register-direct one
+    # (shifts of 40) and the staged general one (shifts of 30), whose staging tile is laid out by wavefront row -- for every
+    # output type, and the kernel's record must name the form.
+    from paper_2101_01321_amd import binding as B
+    import torch
+    M, N, K = 384, 192, 768
+    rng = np.random.default_rng(shift + out_dtype)
+    A = rng.integers(-127, 128, size=(M, K), dtype=np.int8)
+    W = rng.integers(-127, 128, size=(N, K), dtype=np.int8)
+    bias = rng.integers(-50000, 50000, size=N, dtype=np.int32)
+    mult = rng.integers(2 ** 29, 2 ** 30, size=N, dtype=np.int64).astype(np.int32)
+    shifts = np.full(N, shift, np.int32)
+    R = rng.integers(-127, 128, size=(M, N), dtype=np.int8) if res else None
+    clamp = 127 if out_dtype == I8 else (32767 if out_dtype == I16 else 2 ** 31 - 1)
+    kw = dict(M=M, N=N, K=K, batch_outer=1, batch_inner=1, lda=K, ldw=K, ldc=N, ldr=N, per_channel=1,
+              out_dtype=out_dtype, out_clamp=clamp, residual_dy=(1717986918, 29))
+    word = torch.zeros(1, dtype=torch.int32, device=G.DEV)
+    assert B.lib().ibert_gemm_config_override(20) > 20
+    B.ibert_gemm_epilogue_record(word)
+    try:
+        G.say("gemm four rows of wavefronts out=%d res=%s shift=%d" % (out_dtype, res, shift))
+        got = G.gemm(kw, A, W, bias, mult, shifts, R, out_elems=M * N)
+    finally:
+        B.ibert_gemm_epilogue_record(None)
+        B.lib().ibert_gemm_config_override(-1)
+    assert int(word.item()) == (B.EPILOGUE_DIRECT if form == "direct" else B.EPILOGUE_STAGED)
+    spec = GemmSpec(M, N, K, per_channel=1, dy=(1, 0), out_dtype=I32 if out_dtype == I16 else out_dtype, out_clamp=clamp,
+                    res_dy=(1717986918, 29))
+    want = oracle.gemm_requant(spec, A, W, bias, mult, shifts, R)
+    _eq(got, want, "gemm four rows of wavefronts")
 
 
 @pytest.mark.parametrize("cfg", [15, -1])
