@@ -100,6 +100,8 @@ static const GemmConfig kConfigs[] = {      // index = configuration number of i
     {64, 96, 128, 2, true},
     {64, 128, 128, 2, true},
     {128, 96, 128, 3, true},        // with eight wavefronts (four rows of two)
+    {128, 96, 128, 3, true},        // the same with four more wavefronts that only request tiles
+    {128, 128, 128, 3, true},       // eight wavefronts and four that only request tiles
 };
 constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 static int g_config_override = -1;
@@ -175,9 +177,12 @@ static int choose_config(const ibert_gemm_desc& d, int64_t nb, bool gelu)
         // (exactly one 128x96 tile per CU and a 16- or 32-bit output: 64x96 tiles, three or four of which share a CU, so
         //  that one's epilogue overlaps another's loop -- inside the encoder S5 of Base 9.7 -> 8.9 us, S9 17.9 -> 17.3 us;
         //  a fourth LDS stage leaves room for one workgroup per CU only and loses, 24 us.)
-        // (a long K instead: the whole 128x96 tile with eight wavefronts in four rows of two and three stages -- half the
-        //  barriers per MFMA and 30 % fewer bytes from L2 than two 64x96 tiles: S9 of Base 16.85 -> 16.23 us inside the encoder)
-        if (tiles(128, 96) <= 256 && d.out_dtype != IBERT_I8 && !gelu) return d.K >= 2048 ? 20 : 18;
+        // (a long K instead: the whole 128x96 tile with eight wavefronts in four rows of two, three stages, and four more
+        //  wavefronts that do nothing but request tiles, so that no MFMA wavefront ever waits for the address unit:
+        //  [4096,768] x K 3072, timed alone: 64x96 tiles 18.5 us, eight wavefronts 17.6, with the loaders 15.8; INT8 output
+        //  17.1 -> 14.4.  A short K gains nothing from it: S5 of Base 8.7 against 9.0.)
+        if (tiles(128, 96) <= 256 && d.K >= 2048 && !gelu) return 21;
+        if (tiles(128, 96) <= 256 && d.out_dtype != IBERT_I8 && !gelu) return 18;
         return tiles(128, 96) <= 256 && d.K >= 2048 ? 11 : 9;
     }
     // (eight wavefronts for INT8 outputs: S7+S8 of Large 34.7 -> 32.5 us; INT32 outputs lose 5 % with them)
@@ -185,6 +190,8 @@ static int choose_config(const ibert_gemm_desc& d, int64_t nb, bool gelu)
     if (tiles(128, 128) >= 128) {
         // (likewise 64x128 tiles for a short K: S5 of Large 14.4 -> 12.9 us; with K 4096 they lose, 25.9 -> 30 us)
         if (tiles(128, 128) <= 256 && d.K < 2048 && d.out_dtype != IBERT_I8 && !gelu) return 19;
+        // (one tile per CU and a long K: eight wavefronts plus four loaders -- S9 of Large, [4096,1024] x K 4096: 27.0 -> 23.3 us)
+        if (tiles(128, 128) <= 256 && d.K >= 2048 && !gelu) return 22;
         return tiles(128, 128) <= 256 && d.K >= 2048 ? 12 : 7;
     }
     const int64_t tiles128 = (((int64_t)d.M + 127) / 128) * (((int64_t)d.N + 127) / 128) * nb;
@@ -281,6 +288,8 @@ int launch_gemm(const ibert_gemm_desc& d, const int8_t* A, const int8_t* W, cons
             case 18: if (dma_ok(d, 64, 96)) return launch_mfma<64, 96, 128, 2, false, true>(g, i8, stream); break;
             case 19: if (dma_ok(d, 64, 128)) return launch_mfma<64, 128, 128, 2, false, true>(g, i8, stream); break;
             case 20: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 3, false, true, false, 8>(g, i8, stream); break;
+            case 21: if (dma_ok(d, 128, 96)) return launch_mfma<128, 96, 128, 3, false, true, false, 8, 4>(g, i8, stream); break;
+            case 22: if (dma_ok(d, 128, 128)) return launch_mfma<128, 128, 128, 3, false, true, false, 8, 4>(g, i8, stream); break;
             default: break;
         }
         return launch_mfma<128, 128, 64, 2>(g, i8, stream);

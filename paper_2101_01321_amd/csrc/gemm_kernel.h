@@ -148,9 +148,14 @@ struct EpiLayout {
 // fragment reads of the next phase and (second phase) the loads of the step after next, one barrier per step.
 // GELU = true (INT8 output): the requantized, clamped value is the GELU input; integer GELU (Alg. 2) and its
 // requantization to INT8 are applied before the store, so the INT32 tensor between the two never exists.
+// NLD > 0 (direct-to-LDS loader): NLD further wavefronts that only request tiles.  A wavefront whose request waits for
+// the address unit issues nothing else, so requests issued between MFMAs cost the MFMA wavefronts time (without any tile
+// request the loop of the 128x96 tile runs in three quarters of its time); a wavefront of their own takes that wait
+// instead.  They join every barrier of the loop and end before the epilogue (a barrier waits for the surviving
+// wavefronts only).
 template <int BM, int BN, int BK, int RING, bool OUT_I8, int KMODE, bool TW = false, bool DMA = false, bool GELU = false,
-          int NW = 4>
-__global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
+          int NW = 4, int NLD = 0>
+__global__ __launch_bounds__(64 * (NW + NLD)) void gemm_nt_mfma_kernel(GemmArgs g)
 {
     // NW wavefronts in two rows of NW/2: wavefront w owns rows [(w%2) BM/2, +BM/2) and columns [(w/2) WN, +WN) of the tile.
     // (Eight wavefronts on a tile whose width does not divide into four strips of whole MFMA blocks -- 128x96 -- stand in
@@ -160,6 +165,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
     constexpr int NT = 64 * NW;
     static_assert(NW == 4 || (NW == 8 && DMA), "four wavefronts, or eight for the direct-to-LDS loader");
     static_assert(!GELU || OUT_I8, "the GELU epilogue writes INT8");
+    static_assert(NLD == 0 || (NLD == 4 && DMA && !GELU), "loader wavefronts: four, direct-to-LDS tiles");
     constexpr int CPR = BK / 16;                       // 16-byte chunks per tile row
     constexpr int RPP = NT / CPR;            // tile rows loaded per pass of the workgroup
     constexpr int LA = BM / RPP, LW = BN / RPP;        // chunks per lane per K step
@@ -347,7 +353,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
     constexpr int RPRE = DMA && !OUT_I8 && RCH <= 6 * NT ? (RCH + NT - 1) / NT : 0;
     v4i rpre[RPRE > 0 ? RPRE : 1];
     const bool res_early = RPRE > 0 && R && interior;
-    if (RPRE > 0 && res_early) {
+    if (RPRE > 0 && res_early && (NLD == 0 || tid < NT)) {
 #pragma unroll
         for (int u = 0; u < RPRE; ++u) {
             const int q = u * NT + tid;
@@ -366,7 +372,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
         // address unit issues nothing else meanwhile, and when both wavefronts of a SIMD ask in the same phase (they run
         // in step, from barrier to barrier) its MFMA pipe idles -- a phase with requests took twice the time of one
         // without.  This way the second wavefront of each SIMD keeps the pipe busy while the first one asks.
-        constexpr int ND = NW == 8 ? 4 : NW;                          // wavefronts that request tiles
+        constexpr int ND = NLD > 0 ? NLD : (NW == 8 ? 4 : NW);        // wavefronts that request tiles
         constexpr int RG = 8 * ND;                                    // tile rows they fetch together
 
         static_assert(BK == 128 && !TW && KMODE == 0 && BM % RG == 0 && BN % RG == 0, "DMA loader: whole 1 KB blocks");
@@ -375,8 +381,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
         constexpr int SPC = NMF / NR > 0 ? NMF / NR : 1;              // MFMAs between two fragment reads
         static_assert(NL <= 2 * NR && (NMF + SPC - 1) / SPC >= NR, "one read and at most two loads per slot");
         static_assert(RG % 32 == 0, "the swizzle of a lane's row must not depend on the block");
-        const int wv = __builtin_amdgcn_readfirstlane(wave);
-        const bool asker = wv < ND;                                   // (uniform: a scalar branch, not an exec mask)
+        const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+        const bool loader = NLD > 0 && wave_u >= NW;                  // (uniform: scalar branches, not exec masks)
+        const int wv = NLD > 0 ? (loader ? wave_u - NW : wave_u) : wave_u;   // index among the requesting wavefronts
+        const bool asker = NLD > 0 ? loader : wv < ND;
         const int lr8 = lane >> 3, lp = lane & 7;
         // swz<8> of the lane's row: the row is RG i + 8 wave + lr8 with RG a multiple of 32, so (row >> 1) & 7 depends on
         // the wavefront's parity and the lane only
@@ -461,9 +469,19 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
                     for (int c = 0; c < CPA; ++c) {
                         if ((a * CPA + c) % ND == wv && asker && (BN % 64 == 0 || c * 64 + lane < BN)) {
                             const uint32_t la = par0 + (uint32_t)((a * BN + c * 64) * 4);
-                            const int32_t* sb = src + n0 + c * 64;
-                            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
-                                         :: "s"(la), "v"(voff4), "s"(sb) : "memory", "m0");
+                            if constexpr (NLD > 0) {
+                                // (the address is the same in every lane; say so: behind the loaders' branch the compiler
+                                // no longer sees it)
+                                const uint64_t sbv = (uint64_t)(uintptr_t)(src + n0 + c * 64);
+                                const uint64_t sb = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(sbv >> 32)) << 32) |
+                                                    (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(uint32_t)sbv);
+                                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                                             :: "s"(la), "v"(voff4), "s"(sb) : "memory", "m0");
+                            } else {
+                                const int32_t* sb = src + n0 + c * 64;
+                                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                                             :: "s"(la), "v"(voff4), "s"(sb) : "memory", "m0");
+                            }
                         }
                     }
                 } else {
@@ -494,8 +512,34 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
                 }
             }
         }
-        wait_landed(npro - 1);
+        if (NLD == 0 || asker) wait_landed(npro - 1);
         asm volatile("s_barrier" ::: "memory");
+        if (NLD > 0 && loader) {
+            // the loop of a loader wavefront: the requests of the MFMA wavefronts' two phases, the same waits and barriers
+            constexpr int QHL = NSTG >= 3 ? (NL + 1) / 2 : NL;
+            int lbuf = 0;
+            for (int kt = 0; kt < nk; ++kt) {
+                const int nbuf = lbuf + 1 == NSTG ? 0 : lbuf + 1, pbuf = lbuf == 0 ? NSTG - 1 : lbuf - 1;
+                if (DEFER && kt == 0) {
+                    if (nk > 1) {
+#pragma unroll
+                        for (int q = 0; q < NL; ++q) dma_one(q, 1, 1);
+                    }
+                } else if (kt >= 1 && kt - 1 + NSTG < nk) {
+#pragma unroll
+                    for (int q = QHL; q < NL; ++q) dma_one(q, kt - 1 + NSTG, pbuf);
+                }
+                const int hi = kt + NSTG - 1 < nk - 1 ? kt + NSTG - 1 : nk - 1;
+                wait_landed(hi - (kt + 1));
+                asm volatile("s_barrier" ::: "memory");
+                if (kt + NSTG < nk) {
+#pragma unroll
+                    for (int q = 0; q < QHL; ++q) dma_one(q, kt + NSTG, lbuf);
+                }
+                lbuf = nbuf;
+            }
+            return;
+        }
         v4i xa0[FM], wb0[FN], xa1[FM], wb1[FN];
 #pragma unroll
         for (int q = 0; q < NR; ++q) read_one(q, 0, 0, xa0, wb0);
@@ -530,7 +574,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
                       std::integral_constant<int, QH>{}, std::integral_constant<int, NL>{});
             // steps requested after kt+1 so far: kt+2 .. min(kt+RING-1, nk-1)
             const int hi = kt + NSTG - 1 < nk - 1 ? kt + NSTG - 1 : nk - 1;
-            wait_landed(hi - (kt + 1));
+            if (NLD == 0 || asker) wait_landed(hi - (kt + 1));
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
             // (the fragment reads past the last step fetch stale LDS bytes that nothing uses)
             phase(xa1, wb1, xa0, wb0, nbuf, 0, std::true_type{}, kt + NSTG, buf, asker && kt + NSTG < nk,
@@ -1035,7 +1079,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_nt_mfma_kernel(GemmArgs g)
 // ---------------------------------------------------------------------------------------------
 bool xcd_blocks_enabled();       // (gemm.hip: a switch for A/B measurements, on by default)
 
-template <int BM, int BN, int BK, int RING, bool TW = false, bool DMA = false, bool GELU = false, int NW = 4>
+template <int BM, int BN, int BK, int RING, bool TW = false, bool DMA = false, bool GELU = false, int NW = 4, int NLD = 0>
 int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
 {
     g.tiles_m = (g.M + BM - 1) / BM;
@@ -1079,14 +1123,14 @@ int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
     }
 #define IBERT_GEMM_LAUNCH(I8_, KT_)                                                                       \
     do {                                                                                                  \
-        auto kern = gemm_nt_mfma_kernel<BM, BN, BK, RING, I8_, KT_, TW, DMA, GELU && I8_, NW>;               \
+        auto kern = gemm_nt_mfma_kernel<BM, BN, BK, RING, I8_, KT_, TW, DMA, GELU && I8_, NW, NLD>;          \
         static size_t attr_bytes = 0;                                                                     \
         if (lds_bytes > attr_bytes) {                                                                     \
             IBERT_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                      \
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes)); \
             attr_bytes = lds_bytes;                                                                       \
         }                                                                                                 \
-        hipLaunchKernelGGL(kern, grid, dim3(64 * NW), lds_bytes, stream, g);                              \
+        hipLaunchKernelGGL(kern, grid, dim3(64 * (NW + NLD)), lds_bytes, stream, g);                      \
     } while (0)
     if constexpr (GELU) {
         if (!i8 || g.K % BK != 0) return IBERT_ERR_NOT_IMPLEMENTED;
@@ -1104,9 +1148,9 @@ int launch_mfma(GemmArgs& g, bool i8, hipStream_t stream)
     static char label[2][2][96];
     char* l = label[i8 ? 1 : 0][g.K % BK == 0 ? 0 : 1];
     if (!l[0])
-        std::snprintf(l, sizeof label[0][0], "gemm_nt_mfma_kernel<%d, %d, %d, %d, %s, %d, %s, %s, %s, %d>", BM, BN, BK, RING,
+        std::snprintf(l, sizeof label[0][0], "gemm_nt_mfma_kernel<%d, %d, %d, %d, %s, %d, %s, %s, %s, %d, %d>", BM, BN, BK, RING,
                       i8 ? "true" : "false", g.K % BK == 0 ? 0 : 1, TW ? "true" : "false", DMA ? "true" : "false",
-                      GELU ? "true" : "false", NW);
+                      GELU ? "true" : "false", NW, NLD);
     g_last_kernel = l;
     return IBERT_OK;
 }

@@ -43,10 +43,10 @@ def step_of(name):
         return "EMB" if len(a) > 3 and a[3] == "true" else "LN"
     if name.startswith("gelu_kernel"):
         return "hGELU" if name.endswith("true>") else "GELU"
-    m = re.match(r"gemm_nt_mfma_kernel<(\d+), (\d+), (\d+), (\d+), (\w+), (\d), (\w+), (\w+), (\w+), (\d+)>", name)
+    m = re.match(r"gemm_nt_mfma_kernel<(\d+), (\d+), (\d+), (\d+), (\w+), (\d), (\w+), (\w+), (\w+), (\d+), (\d+)>", name)
     if not m:
         return "?"
-    bm, bn, bk, ring, i8, km, tw, dma, gelu, nw = m.groups()
+    bm, bn, bk, ring, i8, km, tw, dma, gelu, nw, nld = m.groups()
     if gelu == "true":
         return "S7+8"
     if i8 == "true":

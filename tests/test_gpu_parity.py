@@ -392,7 +392,10 @@ def test_gemm_trans_w_mfma_path(G, M, N, K, ldw):
                                        # 64x128
                                        (19, 64, 128, 128), (19, 128, 256, 256), (19, 192, 128, 384), (19, 256, 384, 1024),
                                        # 128x96 with eight wavefronts in four rows of two, three stages
-                                       (20, 128, 96, 128), (20, 256, 192, 256), (20, 128, 288, 640), (20, 384, 96, 1024)])
+                                       (20, 128, 96, 128), (20, 256, 192, 256), (20, 128, 288, 640), (20, 384, 96, 1024),
+                                       # ... and with four loader wavefronts beside them
+                                       (21, 128, 96, 128), (21, 256, 192, 256), (21, 128, 288, 640), (21, 384, 96, 1024),
+                                       (22, 128, 128, 128), (22, 256, 256, 256), (22, 128, 384, 640), (22, 384, 128, 1024)])
 def test_gemm_direct_to_lds_tiles(G, cfg, M, N, K):
     # the tile configurations whose loader writes LDS straight from global memory (whole tiles only), forced
     # through the configuration override; 1, 2, odd and even numbers of K steps
@@ -406,15 +409,17 @@ def test_gemm_direct_to_lds_tiles(G, cfg, M, N, K):
         B.lib().ibert_gemm_config_override(-1)
 
 
+@pytest.mark.parametrize("cfg", [20, 21, 22])
 @pytest.mark.parametrize("shift,form", [(40, "direct"), (30, "staged")])
 @pytest.mark.parametrize("out_dtype,res", [(I8, False), (I8, True), (I16, True), (I32, True), (I32, False)])
-def test_gemm_four_rows_of_wavefronts_epilogue_forms(G, out_dtype, res, shift, form):
-    # The 128x96 tile whose eight wavefronts stand in four rows of two: both epilogue forms -- the register-direct one
-    # (shifts of 40) and the staged general one (shifts of 30), whose staging tile is laid out by wavefront row -- for every
-    # output type, and the kernel's record must name the form.
+def test_gemm_four_rows_of_wavefronts_epilogue_forms(G, cfg, out_dtype, res, shift, form):
+    # The 128x96 tile whose eight wavefronts stand in four rows of two (20), the same with four loader wavefronts that end
+    # before the epilogue (21), and the 128x128 tile with loaders (22): both epilogue forms -- the register-direct one
+    # (shifts of 40) and the staged general one (shifts of 30), whose staging tile is laid out by wavefront row and whose
+    # barriers the loaders no longer join -- for every output type, and the kernel's record must name the form.
     from paper_2101_01321_amd import binding as B
     import torch
-    M, N, K = 384, 192, 768
+    M, N, K = 384, 384 if cfg == 22 else 192, 768
     rng = np.random.default_rng(shift + out_dtype)
     A = rng.integers(-127, 128, size=(M, K), dtype=np.int8)
     W = rng.integers(-127, 128, size=(N, K), dtype=np.int8)
@@ -426,10 +431,10 @@ def test_gemm_four_rows_of_wavefronts_epilogue_forms(G, out_dtype, res, shift, f
     kw = dict(M=M, N=N, K=K, batch_outer=1, batch_inner=1, lda=K, ldw=K, ldc=N, ldr=N, per_channel=1,
               out_dtype=out_dtype, out_clamp=clamp, residual_dy=(1717986918, 29))
     word = torch.zeros(1, dtype=torch.int32, device=G.DEV)
-    assert B.lib().ibert_gemm_config_override(20) > 20
+    assert B.lib().ibert_gemm_config_override(cfg) > cfg
     B.ibert_gemm_epilogue_record(word)
     try:
-        G.say("gemm four rows of wavefronts out=%d res=%s shift=%d" % (out_dtype, res, shift))
+        G.say("gemm cfg %d out=%d res=%s shift=%d" % (cfg, out_dtype, res, shift))
         got = G.gemm(kw, A, W, bias, mult, shifts, R, out_elems=M * N)
     finally:
         B.ibert_gemm_epilogue_record(None)
