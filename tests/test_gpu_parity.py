@@ -496,7 +496,8 @@ def test_gemm_gelu_equals_matmul_then_gelu(G, cfg, M, N, K, S_in, S_out):
             G.gemm_gelu(kw, A, W, b, mult, shift, gp, M * N, with_scratch=False)
 
 
-@pytest.mark.parametrize("cfg,M,N,K", [(6, 256, 192, 256), (9, 128, 192, 384), (7, 128, 128, 128), (11, 128, 96, 640)])
+@pytest.mark.parametrize("cfg,M,N,K", [(6, 256, 192, 256), (9, 128, 192, 384), (7, 128, 128, 128), (11, 128, 96, 640),
+                                       (20, 128, 192, 384), (21, 128, 192, 384), (21, 256, 96, 128), (22, 128, 256, 640)])
 def test_gemm_direct_to_lds_tiles_batched(G, cfg, M, N, K):
     # whole-tile configurations on a batched problem: 2 x 3 batch elements, W shared along the outer batch axis,
     # odd workgroup counts (no XCD run) and even ones
